@@ -1,0 +1,19 @@
+"""CPU oracle for the two-stage depth-compression DP (test infrastructure).
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may
+import this package.  It wraps oracle/dpc_oracle.c (Algorithms 1 and 2 of the
+paper plus set recovery) and oracle/dpc_brute.c (exhaustive enumeration of
+Eq. 5a, Eq. 6 and Eq. 8 for tiny L) through ctypes, on numpy arrays.
+"""
+from .api import (  # noqa: F401
+    DPC_INF,
+    DPC_NOARG,
+    stage1,
+    stage2,
+    relax_row,
+    backtrack,
+    solve_batch,
+    brute_topt,
+    brute_objective,
+    brute_min_latency_given_A,
+)

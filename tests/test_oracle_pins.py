@@ -1,0 +1,358 @@
+"""Pins for the CPU oracle: everything here checks oracle/dpc_oracle.c against
+something other than itself - exhaustive enumeration of the definitions
+(Eq. 5a, Eq. 6, Eq. 8), a library shortest-path routine, the worked example
+of Fig. 2, closed forms, invariants, and a literal set-carrying transcription
+of the recurrences with the paper's strict budgets.  CPU only."""
+import os
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+from scipy.sparse.csgraph import shortest_path
+
+import oracle
+from paper_2301_12187_amd import inputs
+from helpers import (DPC_INF, assert_bits_equal, chain_importance,
+                     chain_latency, rand_tables)
+from literal_alg import surrogate_dp, time_dp
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- stage 1
+
+@pytest.mark.parametrize("seed", range(12))
+def test_topt_equals_enumeration_of_eq5a(seed):
+    rng = np.random.default_rng(100 + seed)
+    L = int(rng.integers(1, 11))
+    T, _ = rand_tables(rng, L, tmax=6, inf_frac=0.3 if seed % 2 else 0.0)
+    Topt, _ = oracle.stage1(T)
+    for k in range(L + 1):
+        for l in range(k, L + 1):
+            assert Topt[k, l] == oracle.brute_topt(T, k, l), (k, l)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_topt_equals_dag_shortest_path(seed):
+    """Eq. 5a is the shortest k -> l path in the DAG with an edge m -> l of
+    weight T[m,l] for every mergeable block (textbook reduction)."""
+    rng = np.random.default_rng(200 + seed)
+    L = 40
+    T, _ = rand_tables(rng, L, tmax=50, inf_frac=0.25, span=9)
+    Topt, _ = oracle.stage1(T)
+    ii, jj = np.triu_indices(L + 1, k=1)
+    ok = T[ii, jj] < DPC_INF
+    g = sp.csr_matrix((T[ii, jj][ok].astype(np.float64) + 0.0, (ii[ok], jj[ok])),
+                      shape=(L + 1, L + 1))
+    assert (T[ii, jj][ok] > 0).all()    # scipy treats explicit zeros as "no edge"
+    d = shortest_path(g, method="D", directed=True)
+    for k in range(L + 1):
+        for l in range(k + 1, L + 1):
+            want = DPC_INF if np.isinf(d[k, l]) else int(d[k, l])
+            assert Topt[k, l] == want, (k, l)
+
+
+def test_stage1_base_case_and_bounds():
+    rng = np.random.default_rng(5)
+    T, _ = rand_tables(rng, 30, tmax=30, inf_frac=0.2)
+    Topt, split = oracle.stage1(T)
+    L = 30
+    for k in range(L + 1):
+        assert Topt[k, k] == 0                       # base case of Eq. 5
+        for l in range(k + 1, L + 1):
+            assert Topt[k, l] <= T[k, l]             # S = {} is one candidate
+            assert k <= split[k, l] < l
+            for m in range(k + 1, l):                # any forced split is worse
+                assert Topt[k, l] <= min(Topt[k, m] + Topt[m, l], DPC_INF)
+
+
+def _sopt_nodes(split, k, l):
+    nodes = [l]
+    while split[k, nodes[-1]] != k:
+        nodes.append(int(split[k, nodes[-1]]))
+    nodes.append(k)
+    return nodes[::-1]
+
+
+def test_split_chain_rescoring_and_lowest_m_tiebreak():
+    rng = np.random.default_rng(6)
+    for _ in range(20):
+        L = int(rng.integers(2, 14))
+        T, _ = rand_tables(rng, L, tmax=4, inf_frac=0.2)   # tie-rich
+        Topt, split = oracle.stage1(T)
+        for k in range(L + 1):
+            for l in range(k + 1, L + 1):
+                nodes = _sopt_nodes(split, k, l)
+                if Topt[k, l] < DPC_INF:
+                    assert chain_latency(T, nodes) == Topt[k, l]
+                else:
+                    assert split[k, l] == k
+                # lowest arg-min m' of Algorithm 1's inner step
+                c = [min(int(Topt[k, m]) + int(T[m, l]), DPC_INF) for m in range(k, l)]
+                assert split[k, l] == k + int(np.argmin(c))
+    # hand case: both ways to cover layers 1..2 cost 2 -> one merged block
+    T = np.zeros((3, 3), np.int32)
+    T[0, 1], T[1, 2], T[0, 2] = 1, 1, 2
+    Topt, split = oracle.stage1(T)
+    assert Topt[0, 2] == 2 and split[0, 2] == 0
+    T[0, 2] = 3                                     # now splitting at 1 wins
+    Topt, split = oracle.stage1(T)
+    assert Topt[0, 2] == 2 and split[0, 2] == 1
+
+
+def test_stage1_matches_literal_time_dp():
+    rng = np.random.default_rng(7)
+    for _ in range(10):
+        L = int(rng.integers(1, 12))
+        T, _ = rand_tables(rng, L, tmax=5, inf_frac=0.2)
+        Topt, split = oracle.stage1(T)
+        Tl, Sl = time_dp(T, L)
+        for k in range(L + 1):
+            for l in range(k, L + 1):
+                assert Topt[k, l] == Tl[k][l]
+                if k < l and Tl[k][l] < DPC_INF:
+                    assert tuple(_sopt_nodes(split, k, l)[1:-1]) == Sl[k][l]
+
+
+# ---------------------------------------------------------------- stage 2
+
+def _solve(T, I, P):
+    Topt, split = oracle.stage1(T)
+    M, K = oracle.stage2(Topt, I, P)
+    return Topt, split, M, K
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_objective_equals_enumeration_of_all_A_S_pairs(seed):
+    """Proposition 4.1: every row l of the table is the optimum of Eq. 6."""
+    rng = np.random.default_rng(300 + seed)
+    L = int(rng.integers(1, 10))
+    ikind = ("int", "neg", "mixed")[seed % 3]
+    T, I = rand_tables(rng, L, tmax=5, inf_frac=0.25 if seed % 2 else 0.0, ikind=ikind)
+    if seed % 4 == 3 and L >= 3:
+        I[0, L] = -np.inf                            # an excluded block
+        I[1, 3] = -np.inf
+    P = int(rng.integers(1, 5 * L + 4))
+    _, _, M, _ = _solve(T, I, P)
+    assert_bits_equal(M[0], np.zeros(P, np.float32), "row 0")
+    for l in range(1, L + 1):
+        assert_bits_equal(M[l], oracle.brute_objective(T, I, l, P), f"row {l}")
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_objective_equals_enumeration_L12(seed):
+    rng = np.random.default_rng(400 + seed)
+    L = 12
+    cfg = inputs.CONFIGS[1]
+    T, I, _ = inputs.make_instance(L, cfg.base_lo, cfg.base_hi, cfg.span, cfg.mu,
+                                   0.0, (seed, 99, 0))
+    if seed == 1:
+        T, I = rand_tables(rng, L, tmax=7, inf_frac=0.2, ikind="int")
+    P = 64 if seed else 256
+    _, _, M, _ = _solve(T, I, P)
+    assert_bits_equal(M[L], oracle.brute_objective(T, I, L, P), "row L")
+    assert_bits_equal(M[7], oracle.brute_objective(T, I, 7, P), "row 7")
+
+
+def test_fig2_worked_example():
+    vals = {"Topt": {}, "I": {}, "D": {}}
+    expect = {}
+    with open(os.path.join(GOLD, "fig2_worked_example.txt")) as f:
+        for line in f:
+            w = line.split()
+            if not w or w[0].startswith("#"):
+                continue
+            if w[0] in vals:
+                vals[w[0]][(int(w[1]), int(w[2]))] = float(w[3])
+            else:
+                expect[w[0]] = w[1:]
+    L, P = 3, 22
+    Topt = np.zeros((L + 1, L + 1), np.int32)
+    I = np.zeros((L + 1, L + 1), np.float32)
+    for (i, j), v in vals["Topt"].items():
+        Topt[i, j] = int(v)
+    for (i, j), v in vals["I"].items():
+        I[i, j] = v
+    M = np.zeros((L + 1, P), np.float32)
+    K = np.zeros((L + 1, P), np.uint8)
+    for (l, t), v in vals["D"].items():
+        M[l, t] = v
+    oracle.relax_row(3, Topt, I, M, K)
+    l, t, d = int(expect["expect_D"][0]), int(expect["expect_D"][1]), float(expect["expect_D"][2])
+    assert (l, t) == (3, 21)
+    assert M[l, t] == np.float32(d)
+    assert K[l, t] == int(expect["expect_k"][2])
+    # the three candidates the figure prints, each made the only one in turn
+    for kp, c in enumerate(expect["expect_candidates"]):
+        I2 = I.copy()
+        for other in range(3):
+            if other != kp:
+                I2[other, 3] = -np.inf
+        M2, K2 = M.copy(), K.copy()
+        oracle.relax_row(3, Topt, I2, M2, K2)
+        assert M2[3, 21] == np.float32(np.float32(vals["D"][(kp, 21 - int(Topt[kp, 3]))])
+                                       + np.float32(vals["I"][(kp, 3)]))
+        assert abs(float(M2[3, 21]) - float(c)) < 1e-6 and K2[3, 21] == kp
+    # A[3,21] = A[1,7] + {1} = {1}: rows 1..2 of the figure keep no activation
+    split = np.zeros((L + 1, L + 1), np.uint8)
+    for i in range(L + 1):
+        split[i, :] = i
+    r = oracle.backtrack(Topt, split, I, M, K, 21)
+    assert r["status"] == 0 and list(r["A"]) == [int(expect["expect_A"][2])]
+    assert r["obj"] == np.float32(d)
+
+
+def test_invariants_on_config_shaped_instances():
+    for cid, nb in ((1, 1), (2, 1), (3, 3), (4, 2)):
+        cfg = inputs.CONFIGS[cid]
+        T, I, _ = inputs.make_batch(cfg, seed=1, B=nb)
+        P = min(cfg.P, 1500)
+        for b in range(nb):
+            Topt, _, M, K = _solve(T[b], I[b], P)
+            L = cfg.L
+            ii, jj = np.triu_indices(L + 1, k=1)
+            assert (Topt[ii, jj] <= T[b][ii, jj]).all()
+            for j in range(1, L + 1):
+                row = M[j]
+                assert (np.diff(row[np.isfinite(row)]) >= 0).all()      # monotone in t
+                first = int(Topt[0, j])
+                assert np.isneginf(row[:min(first, P)]).all()           # unreachable
+                assert np.isfinite(row[min(first, P):]).all()           # reachable
+                assert (K[j][:min(first, P)] == 0xFF).all()
+                assert (K[j][min(first, P):] < j).all()
+            # one layer: the only candidate is the block (0,1)
+            t01 = int(T[b][0, 1])
+            assert (M[1][t01:] == I[b][0, 1]).all()
+
+
+def test_closed_forms():
+    rng = np.random.default_rng(8)
+    L, P = 14, 120
+    T, _ = rand_tables(rng, L, tmax=7, inf_frac=0.1)
+    Topt, _ = oracle.stage1(T)
+    # (i) constant negative importance: every kept activation costs one more
+    #     block, so A = {} and the optimum is the single block value c
+    c = np.float32(-0.37)
+    I = np.full((L + 1, L + 1), c, np.float32)
+    M, K = oracle.stage2(Topt, I, P)
+    t0 = int(Topt[0, L])
+    assert t0 < P
+    assert (M[L][t0:] == c).all() and (K[L][t0:] == 0).all()
+    assert np.isneginf(M[L][:t0]).all()
+    # (ii) I <= 0 with I[i,i+1] = 0: keeping every activation gives exactly 0
+    #      as soon as the layer-by-layer chain fits the budget
+    I = np.zeros((L + 1, L + 1), np.float32)
+    for i in range(L + 1):
+        for j in range(i + 2, L + 1):
+            I[i, j] = -abs(rng.normal()) - 0.01
+    M, _ = oracle.stage2(Topt, I, P)
+    full = sum(int(Topt[k - 1, k]) for k in range(1, L + 1))
+    assert full < P
+    assert (M[L][full:] == 0).all()
+    assert (M[L][:full][np.isfinite(M[L][:full])] < 0).all()
+    # (iii) constant positive importance g: the optimum is g * (largest number
+    #       of blocks whose T_opt chain fits), a longest-path count
+    g = np.float32(1.0)
+    I = np.full((L + 1, L + 1), g, np.float32)
+    M, _ = oracle.stage2(Topt, I, P)
+    # cnt[j][t] = max blocks ending at j with latency <= t (tiny integer DP
+    # written independently here, integers only)
+    cnt = np.full((L + 1, P), -10**6, np.int64)
+    cnt[0, :] = 0
+    for j in range(1, L + 1):
+        for i in range(j):
+            w = int(Topt[i, j])
+            if w < P:
+                cnt[j, w:] = np.maximum(cnt[j, w:], cnt[i, :P - w] + 1)
+    ok = cnt[L] > 0
+    assert (M[L][ok] == cnt[L][ok].astype(np.float32)).all()
+    assert np.isneginf(M[L][~ok]).all()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_paper_strict_budget_transcription(seed):
+    """D_paper[l][t] == M[l][t-1]; A and S of the set-carrying recurrence equal
+    the back-tracked sets (same first-maximum tie-breaks)."""
+    rng = np.random.default_rng(500 + seed)
+    L = int(rng.integers(2, 9))
+    ikind = "int" if seed % 2 else "mixed"
+    T, I = rand_tables(rng, L, tmax=4, inf_frac=0.15, ikind=ikind)
+    T0 = 4 * L + 2
+    P = T0 + 1
+    D, A, S, _, _ = surrogate_dp(T0, L, T, I)
+    Topt, split, M, K = _solve(T, I, P)
+    for l in range(1, L + 1):
+        for t in range(1, T0 + 1):
+            if (l, t) in D:
+                assert M[l, t - 1] == D[(l, t)], (l, t)
+            else:
+                assert np.isneginf(M[l, t - 1]), (l, t)
+    for t in range(1, T0 + 1):
+        r = oracle.backtrack(Topt, split, I, M, K, t - 1)
+        if (L, t) in D:
+            assert r["status"] == 0
+            assert tuple(r["A"]) == A[(L, t)], t
+            assert tuple(r["S"]) == S[(L, t)], t
+        else:
+            assert r["status"] == 1 and r["A_len"] == -1 and r["S_len"] == -1
+
+
+# -------------------------------------------------------------- backtrack
+
+@pytest.mark.parametrize("seed", range(10))
+def test_backtracked_sets_rescore(seed):
+    rng = np.random.default_rng(600 + seed)
+    L = int(rng.integers(1, 13))
+    T, I = rand_tables(rng, L, tmax=6, inf_frac=0.2, ikind=("int", "mixed")[seed % 2])
+    P = 6 * L + 3
+    Topt, split, M, K = _solve(T, I, P)
+    for T0 in range(P):
+        r = oracle.backtrack(Topt, split, I, M, K, T0)
+        r2 = oracle.backtrack(Topt, split, I, M, None, T0)   # arg-max found again
+        assert r["status"] == r2["status"]
+        if r["status"]:
+            assert np.isneginf(M[L, T0]) and np.isneginf(r["obj"]) and r["lat"] == -1
+            continue
+        A, S = list(r["A"]), list(r["S"])
+        assert A == list(r2["A"]) and S == list(r2["S"]) and r["lat"] == r2["lat"]
+        assert A == sorted(set(A)) and S == sorted(set(S))
+        assert set(A) <= set(S) <= set(range(1, L))
+        lat = chain_latency(T, [0] + S + [L])
+        assert lat == r["lat"] <= T0                                   # Eq. 4 constraint
+        obj = chain_importance(I, [0] + A + [L])
+        assert obj.view(np.uint32) == r["obj"].view(np.uint32)         # Eq. 4 objective
+        assert r["obj"].view(np.uint32) == M[L, T0].view(np.uint32)
+        an = [0] + A + [L]
+        assert lat == sum(int(Topt[a, b]) for a, b in zip(an[:-1], an[1:]))
+        if L <= 11:                                                   # Proposition 4.2
+            assert lat == oracle.brute_min_latency_given_A(T, L, A)
+
+
+def test_backtrack_lowest_i_tiebreak_hand_case():
+    # two layers, every block free and worthless: all candidates tie at 0, the
+    # lowest predecessor (0) must win, so nothing is kept and one block merges
+    T = np.zeros((3, 3), np.int32)
+    T[0, 1] = T[1, 2] = T[0, 2] = 1
+    I = np.zeros((3, 3), np.float32)
+    Topt, split, M, K = _solve(T, I, 4)
+    assert K[2, 1] == 0 and K[2, 2] == 0 and K[2, 0] == 0xFF
+    r = oracle.backtrack(Topt, split, I, M, K, 3)
+    assert list(r["A"]) == [] and list(r["S"]) == [] and r["lat"] == 1
+    # make keeping activation 1 strictly better once it fits (latency 2)
+    I[0, 2] = -1.0
+    Topt, split, M, K = _solve(T, I, 4)
+    assert K[2, 1] == 0 and M[2, 1] == -1.0
+    assert K[2, 2] == 1 and M[2, 2] == 0.0
+    r = oracle.backtrack(Topt, split, I, M, K, 2)
+    assert list(r["A"]) == [1] and list(r["S"]) == [1] and r["lat"] == 2
+
+
+def test_zero_latency_blocks_are_legal():
+    # T = 0 entries: row j reads the same column of an earlier row
+    rng = np.random.default_rng(9)
+    L = 8
+    T, I = rand_tables(rng, L, tmax=1, ikind="mixed", tmin=0)
+    P = 12
+    _, _, M, _ = _solve(T, I, P)
+    for l in range(1, L + 1):
+        assert_bits_equal(M[l], oracle.brute_objective(T, I, l, P), f"row {l}")
