@@ -1,0 +1,166 @@
+/*
+ * libdpc - two-stage dynamic program for latency-aware depth compression,
+ * batched, on one AMD MI355X (gfx950).  C ABI.
+ *
+ * The problem (paper Section 4.1-4.2, Eq. 4): a chain of L convolution layers
+ * with an activation after each; choose the activations to keep, A, and the
+ * merge boundaries, S, with A inside S inside {1..L-1}, maximising the summed
+ * block importances I[a_{j-1}, a_j] over the chain 0 -> A -> L subject to the
+ * summed block latencies T[s_{i-1}, s_i] over the chain 0 -> S -> L staying
+ * within a budget T0.  The solution (Section 4.3) is two dynamic programs and
+ * a walk back through their arg-min / arg-max choices; the three entry points
+ * below are those three steps, each batched over B independent instances.
+ *
+ * Conventions common to all entry points
+ *   - Every array pointer is a DEVICE pointer owned by the caller; the library
+ *     allocates nothing and keeps no pointer after the call returns.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Work is queued on
+ *     it and the call returns without waiting; the usual stream ordering makes
+ *     the outputs of one call valid inputs of the next on the same stream.
+ *   - Shapes: B >= 1 instances, 1 <= L <= DPC_MAX_L layers, P >= 1 integer
+ *     latency budgets t = 0 .. P-1.  Tables indexed by two layer indices are
+ *     row-major [B][L+1][L+1]; only entries [i][j] with 0 <= i < j <= L of the
+ *     inputs are read.  Tables indexed by (layer, budget) are row-major
+ *     [B][L+1][P].
+ *   - Budgets are inclusive: column t covers total latency <= t.  The paper
+ *     writes the constraint strictly (Eq. 4: latency < T0); its column T0 is
+ *     column T0-1 here.
+ *   - Return value: DPC_OK, or a negative DPC_ERR_* in which case nothing was
+ *     queued and no output was touched.  dpc_status_string() names a code.
+ *   - Calls on different streams may run concurrently as long as their output
+ *     and workspace buffers are distinct.
+ */
+#ifndef DPC_H
+#define DPC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DPC_MAX_L 255          /* layer indices and arg-max pointers fit one byte  */
+#define DPC_INF   0x3FFFFFFF   /* latency of a block that cannot be merged; sums of
+                                  latencies saturate at this value                 */
+#define DPC_NOARG 0xFF         /* K entry of a cell that no (A, S) reaches          */
+
+enum {
+    DPC_OK          =  0,
+    DPC_ERR_NULL    = -1,      /* a required pointer is NULL                        */
+    DPC_ERR_SHAPE   = -2,      /* B, L, P or Q outside the supported range          */
+    DPC_ERR_WORKSPACE = -3,    /* workspace smaller than dpc_stage2_workspace_bytes */
+    DPC_ERR_HIP     = -4,      /* a HIP runtime call failed (launch, query)         */
+    DPC_ERR_TIMEOUT = -5       /* reported by dpc_stage2_check: a bounded in-kernel
+                                  wait ran out; M and K are incomplete              */
+};
+
+/* per-query status written by dpc_backtrack */
+enum {
+    DPC_Q_OK         = 0,
+    DPC_Q_INFEASIBLE = 1,      /* no (A, S) has latency <= T0                       */
+    DPC_Q_BAD_QUERY  = 2       /* q_inst outside [0,B) or q_T0 outside [0,P)        */
+};
+
+/*
+ * Stage 1 - optimal merged latency of every contiguous block (Algorithm 1,
+ * definitions Eq. 5a/5b):
+ *     Topt[k][l] = min over S inside {k+1..l-1} of the summed T along k -> S -> l
+ * computed by the algorithm's recurrence over the LAST merged block,
+ *     m = lowest arg-min over k <= m' < l of  sat(Topt[k][m'] + T[m'][l]),
+ * with sat(x) = min(x, DPC_INF) and Topt[k][k] = 0.
+ *
+ *   T      in   int32 [B][L+1][L+1]   block latency, >= 0, DPC_INF = not mergeable
+ *   Topt   out  int32 [B][L+1][L+1]   entries with k >= l are written as 0
+ *   split  out  uint8 [B][L+1][L+1]   the arg-min m: m == k means layers k+1..l
+ *                                     stay one merged block (S_opt[k,l] empty),
+ *                                     otherwise S_opt[k,l] = S_opt[k,m] + {m};
+ *                                     m = k when Topt[k][l] == DPC_INF; entries
+ *                                     with k >= l are written as 0
+ */
+int dpc_stage1_minplus(int32_t B, int32_t L, const int32_t *T, int32_t *Topt,
+                       uint8_t *split, void *stream);
+
+/*
+ * Stage 2 - latency-budgeted chain DP for every budget at once (Algorithm 2,
+ * recurrence Eq. 7; M is the table D of the footnote in Section 4.4):
+ *     M[0][t] = +0
+ *     M[j][t] = max over 0 <= i < j with Topt[i][j] <= t of
+ *                   fl32( M[i][t - Topt[i][j]] + I[i][j] )
+ *     K[j][t] = the lowest i attaining it
+ * One IEEE binary32 add (round to nearest even, denormals kept) per
+ * candidate, exact comparisons.  A cell no (A, S) reaches holds -inf and
+ * K = DPC_NOARG; this carries the feasibility side condition of Eq. 7.
+ *
+ *   Topt   in   int32 [B][L+1][L+1]   from stage 1 (any non-negative table works)
+ *   I      in   float [B][L+1][L+1]   block importance; finite or -inf (excluded
+ *                                     block); NaN and +inf are not supported
+ *   M      out  float [B][L+1][P]
+ *   K      out  uint8 [B][L+1][P]     may be NULL: back-pointers are then not
+ *                                     stored (dpc_backtrack can recompute them)
+ *   workspace   device scratch of at least dpc_stage2_workspace_bytes(B, L, P)
+ *               bytes, 256-byte aligned, private to this call until the work
+ *               queued by it has finished; contents on entry are irrelevant
+ *               (the call clears what it needs with a kernel of its own, so it
+ *               can be recorded into a HIP graph)
+ */
+size_t dpc_stage2_workspace_bytes(int32_t B, int32_t L, int32_t P);
+
+int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t *Topt,
+                        const float *I, float *M, uint8_t *K, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/*
+ * Waits for `stream` and reports whether the last dpc_stage2_knapsack that
+ * used `workspace` ran to completion: DPC_OK, DPC_ERR_TIMEOUT if a bounded
+ * wait inside the kernel expired (a defect or a lost device, never an input
+ * property), or DPC_ERR_HIP.  Optional; the only entry point that blocks.
+ */
+int dpc_stage2_check(const void *workspace, void *stream);
+
+/*
+ * Set recovery - A[L,T0] and S[L,T0] (the set updates of Algorithm 2,
+ * Eq. 7a/7b, and of Algorithm 1) for Q queries (instance, budget), by walking
+ * the arg-max pointers K from (L, T0) down to layer 0 and, inside every block
+ * (i, j) of that chain, the arg-min pointers split from j down to i.
+ *
+ *   Topt, split  in  as produced by stage 1
+ *   I, M         in  as given to / produced by stage 2
+ *   K            in  from stage 2, or NULL: the arg-max of each visited cell is
+ *                    then found again as the lowest i whose candidate reproduces
+ *                    the stored M bit for bit
+ *   Q            number of queries, >= 0 (0: nothing is queued)
+ *   q_inst,q_T0  in  int32 [Q]  instance index and inclusive budget
+ *   A            out int32 [Q][L]  kept activations, ascending, A_len[q] entries
+ *   S            out int32 [Q][L]  merge boundaries, ascending, S_len[q] entries,
+ *                                   A is a subset of S; entries past the lengths
+ *                                   are not written
+ *   obj          out float [Q]     M[L][T0], the optimal objective
+ *   lat          out int32 [Q]     summed latency of the chain 0 -> S -> L, <= T0
+ *   status       out int32 [Q]     DPC_Q_*; for a status other than DPC_Q_OK:
+ *                                   A_len = S_len = -1, obj = -inf, lat = -1
+ */
+int dpc_backtrack(int32_t B, int32_t L, int32_t P, const int32_t *Topt,
+                  const uint8_t *split, const float *I, const float *M,
+                  const uint8_t *K, int32_t Q, const int32_t *q_inst,
+                  const int32_t *q_T0, int32_t *A, int32_t *A_len, int32_t *S,
+                  int32_t *S_len, float *obj, int32_t *lat, int32_t *status,
+                  void *stream);
+
+/* Name of a DPC_ERR_* code (static string, never NULL). */
+const char *dpc_status_string(int code);
+
+/*
+ * Tuning knob for measurements: selects the stage-2 kernel family.
+ *   0  automatic (default)
+ *   1  row-at-a-time kernels reading M from global memory (one launch per row)
+ *   2  persistent LDS-tiled kernel
+ * Returns the previous value, or DPC_ERR_SHAPE for an unknown one.  Results
+ * are bit-identical for every choice.  Process-wide, not thread-safe.
+ */
+int dpc_set_stage2_variant(int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPC_H */

@@ -1,0 +1,169 @@
+"""Thin Python binding over libdpc.so (see include/dpc.h for the contract).
+
+Argument marshalling only: torch provides device memory and streams, every
+step of the method runs in the HIP kernels behind the C ABI.  There is no CPU
+fallback: if the library is not built, or a tensor is not on the GPU, the call
+raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdpc.so")
+
+DPC_INF = 0x3FFFFFFF
+DPC_NOARG = 0xFF
+DPC_MAX_L = 255
+DPC_OK = 0
+
+EXPORTS = (
+    "dpc_stage1_minplus", "dpc_stage2_workspace_bytes", "dpc_stage2_knapsack",
+    "dpc_stage2_check", "dpc_backtrack", "dpc_status_string",
+    "dpc_set_stage2_variant",
+)
+
+_lib = None
+
+
+class DpcError(RuntimeError):
+    pass
+
+
+def load():
+    """Load libdpc.so and declare its signatures.  Raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise DpcError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2301_12187_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i32, vp, sz = ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+    lib.dpc_stage1_minplus.argtypes = [i32, i32, vp, vp, vp, vp]
+    lib.dpc_stage1_minplus.restype = ctypes.c_int
+    lib.dpc_stage2_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.dpc_stage2_workspace_bytes.restype = sz
+    lib.dpc_stage2_knapsack.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.dpc_stage2_knapsack.restype = ctypes.c_int
+    lib.dpc_stage2_check.argtypes = [vp, vp]
+    lib.dpc_stage2_check.restype = ctypes.c_int
+    lib.dpc_backtrack.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp,
+                                  vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.dpc_backtrack.restype = ctypes.c_int
+    lib.dpc_status_string.argtypes = [ctypes.c_int]
+    lib.dpc_status_string.restype = ctypes.c_char_p
+    lib.dpc_set_stage2_variant.argtypes = [ctypes.c_int]
+    lib.dpc_set_stage2_variant.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(code):
+    if code != DPC_OK:
+        raise DpcError(load().dpc_status_string(code).decode())
+
+
+def _dev(t, dtype, shape, name):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise DpcError(f"{name}: expected a GPU tensor (no CPU fallback)")
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+        raise DpcError(f"{name}: expected contiguous {dtype} {tuple(shape)}, "
+                       f"got {t.dtype} {tuple(t.shape)}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def dpc_stage1_minplus(T, Topt, split, stream=None):
+    """T int32 [B][L+1][L+1] -> Topt int32, split uint8 (same shape), in place."""
+    B, ld, _ = T.shape
+    shp = (B, ld, ld)
+    _check(load().dpc_stage1_minplus(
+        B, ld - 1, _dev(T, torch.int32, shp, "T"), _dev(Topt, torch.int32, shp, "Topt"),
+        _dev(split, torch.uint8, shp, "split"), _stream(stream)))
+
+
+def dpc_stage2_workspace_bytes(B, L, P):
+    return int(load().dpc_stage2_workspace_bytes(B, L, P))
+
+
+def dpc_stage2_knapsack(Topt, I, M, K, workspace, stream=None):
+    """Topt int32, I float32 [B][L+1][L+1] -> M float32, K uint8 or None [B][L+1][P]."""
+    B, ld, _ = Topt.shape
+    P = M.shape[2]
+    if not (isinstance(workspace, torch.Tensor) and workspace.is_cuda
+            and workspace.dtype == torch.uint8 and workspace.is_contiguous()):
+        raise DpcError("workspace: expected a contiguous uint8 GPU tensor")
+    _check(load().dpc_stage2_knapsack(
+        B, ld - 1, P, _dev(Topt, torch.int32, (B, ld, ld), "Topt"),
+        _dev(I, torch.float32, (B, ld, ld), "I"), _dev(M, torch.float32, (B, ld, P), "M"),
+        None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"),
+        ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+
+
+def dpc_stage2_check(workspace, stream=None):
+    _check(load().dpc_stage2_check(ctypes.c_void_p(workspace.data_ptr()), _stream(stream)))
+
+
+def dpc_backtrack(Topt, split, I, M, K, q_inst, q_T0, A, A_len, S, S_len, obj, lat,
+                  status, stream=None):
+    B, ld, _ = Topt.shape
+    L = ld - 1
+    P = M.shape[2]
+    Q = q_inst.shape[0]
+    if Q == 0:
+        return
+    _check(load().dpc_backtrack(
+        B, L, P, _dev(Topt, torch.int32, (B, ld, ld), "Topt"),
+        _dev(split, torch.uint8, (B, ld, ld), "split"),
+        _dev(I, torch.float32, (B, ld, ld), "I"), _dev(M, torch.float32, (B, ld, P), "M"),
+        None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"), Q,
+        _dev(q_inst, torch.int32, (Q,), "q_inst"), _dev(q_T0, torch.int32, (Q,), "q_T0"),
+        _dev(A, torch.int32, (Q, L), "A"), _dev(A_len, torch.int32, (Q,), "A_len"),
+        _dev(S, torch.int32, (Q, L), "S"), _dev(S_len, torch.int32, (Q,), "S_len"),
+        _dev(obj, torch.float32, (Q,), "obj"), _dev(lat, torch.int32, (Q,), "lat"),
+        _dev(status, torch.int32, (Q,), "status"), _stream(stream)))
+
+
+def dpc_set_stage2_variant(variant):
+    prev = load().dpc_set_stage2_variant(int(variant))
+    if prev < 0:
+        _check(prev)
+    return prev
+
+
+class Buffers:
+    """Device buffers for one problem shape, allocated once and reused."""
+
+    def __init__(self, B, L, P, Q, store_K=True, device="cuda:0"):
+        self.B, self.L, self.P, self.Q = B, L, P, Q
+        ld = L + 1
+        dev = torch.device(device)
+        self.Topt = torch.empty((B, ld, ld), dtype=torch.int32, device=dev)
+        self.split = torch.empty((B, ld, ld), dtype=torch.uint8, device=dev)
+        self.M = torch.empty((B, ld, P), dtype=torch.float32, device=dev)
+        self.K = torch.empty((B, ld, P), dtype=torch.uint8, device=dev) if store_K else None
+        self.workspace = torch.empty(max(dpc_stage2_workspace_bytes(B, L, P), 256),
+                                     dtype=torch.uint8, device=dev)
+        self.A = torch.empty((Q, L), dtype=torch.int32, device=dev)
+        self.S = torch.empty((Q, L), dtype=torch.int32, device=dev)
+        self.A_len = torch.empty((Q,), dtype=torch.int32, device=dev)
+        self.S_len = torch.empty((Q,), dtype=torch.int32, device=dev)
+        self.obj = torch.empty((Q,), dtype=torch.float32, device=dev)
+        self.lat = torch.empty((Q,), dtype=torch.int32, device=dev)
+        self.status = torch.empty((Q,), dtype=torch.int32, device=dev)
+
+
+def solve(T, I, q_inst, q_T0, buf: Buffers, stream=None):
+    """The whole path on device tensors: stage 1, stage 2, set recovery.
+    Queues the three calls on `stream` and returns without waiting."""
+    dpc_stage1_minplus(T, buf.Topt, buf.split, stream)
+    dpc_stage2_knapsack(buf.Topt, I, buf.M, buf.K, buf.workspace, stream)
+    dpc_backtrack(buf.Topt, buf.split, I, buf.M, buf.K, q_inst, q_T0, buf.A, buf.A_len,
+                  buf.S, buf.S_len, buf.obj, buf.lat, buf.status, stream)

@@ -1,0 +1,90 @@
+// C-ABI entry points of libdpc.so: argument checks and kernel launches.
+#include "dpc_internal.h"
+
+namespace {
+
+int g_stage2_variant = 0;
+
+bool shape_ok(int B, int L, int P)
+{
+    return B >= 1 && L >= 1 && L <= DPC_MAX_L && P >= 1 &&
+           (int64_t)B * (L + 1) * (int64_t)P < ((int64_t)1 << 40);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dpc_status_string(int code)
+{
+    switch (code) {
+        case DPC_OK: return "DPC_OK";
+        case DPC_ERR_NULL: return "DPC_ERR_NULL: a required pointer is NULL";
+        case DPC_ERR_SHAPE: return "DPC_ERR_SHAPE: B, L, P or Q outside the supported range";
+        case DPC_ERR_WORKSPACE: return "DPC_ERR_WORKSPACE: workspace too small or misaligned";
+        case DPC_ERR_HIP: return "DPC_ERR_HIP: a HIP runtime call failed";
+        case DPC_ERR_TIMEOUT: return "DPC_ERR_TIMEOUT: a bounded in-kernel wait ran out";
+        default: return "unknown libdpc status";
+    }
+}
+
+int dpc_set_stage2_variant(int variant)
+{
+    if (variant < 0 || variant > 2) return DPC_ERR_SHAPE;
+    int prev = g_stage2_variant;
+    g_stage2_variant = variant;
+    return prev;
+}
+
+int dpc_stage1_minplus(int32_t B, int32_t L, const int32_t* T, int32_t* Topt, uint8_t* split,
+                       void* stream)
+{
+    if (!T || !Topt || !split) return DPC_ERR_NULL;
+    if (!shape_ok(B, L, 1)) return DPC_ERR_SHAPE;
+    hipError_t e = dpc::launch_stage1(B, L, T, Topt, split, (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+size_t dpc_stage2_workspace_bytes(int32_t B, int32_t L, int32_t P)
+{
+    if (!shape_ok(B, L, P)) return 0;
+    return 256;
+}
+
+int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const float* I,
+                        float* M, uint8_t* K, void* workspace, size_t workspace_bytes,
+                        void* stream)
+{
+    if (!Topt || !I || !M || !workspace) return DPC_ERR_NULL;
+    if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
+    if (workspace_bytes < dpc_stage2_workspace_bytes(B, L, P) || ((uintptr_t)workspace & 255))
+        return DPC_ERR_WORKSPACE;
+    hipError_t e = dpc::launch_stage2_rows(B, L, P, Topt, I, M, K, (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+int dpc_stage2_check(const void* workspace, void* stream)
+{
+    if (!workspace) return DPC_ERR_NULL;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DPC_ERR_HIP;
+    return DPC_OK;
+}
+
+int dpc_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const uint8_t* split,
+                  const float* I, const float* M, const uint8_t* K, int32_t Q,
+                  const int32_t* q_inst, const int32_t* q_T0, int32_t* A, int32_t* A_len,
+                  int32_t* S, int32_t* S_len, float* obj, int32_t* lat, int32_t* status,
+                  void* stream)
+{
+    if (Q < 0) return DPC_ERR_SHAPE;
+    if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
+    if (Q == 0) return DPC_OK;
+    if (!Topt || !split || !I || !M || !q_inst || !q_T0 || !A || !A_len || !S || !S_len || !obj ||
+        !lat || !status)
+        return DPC_ERR_NULL;
+    hipError_t e = dpc::launch_backtrack(B, L, P, Topt, split, I, M, K, Q, q_inst, q_T0, A, A_len,
+                                         S, S_len, obj, lat, status, (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+}  // extern "C"

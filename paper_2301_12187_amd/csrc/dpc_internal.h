@@ -1,0 +1,20 @@
+// Internal declarations shared by the translation units of libdpc.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "dpc.h"
+
+namespace dpc {
+
+// kernel launchers; each returns a hipError_t from the launch
+hipError_t launch_stage1(int B, int L, const int32_t* T, int32_t* Topt, uint8_t* split,
+                         hipStream_t st);
+hipError_t launch_stage2_rows(int B, int L, int P, const int32_t* Topt, const float* I,
+                              float* M, uint8_t* K, hipStream_t st);
+hipError_t launch_backtrack(int B, int L, int P, const int32_t* Topt, const uint8_t* split,
+                            const float* I, const float* M, const uint8_t* K, int Q,
+                            const int32_t* q_inst, const int32_t* q_T0, int32_t* A,
+                            int32_t* A_len, int32_t* S, int32_t* S_len, float* obj,
+                            int32_t* lat, int32_t* status, hipStream_t st);
+
+}  // namespace dpc

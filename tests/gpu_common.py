@@ -1,0 +1,76 @@
+"""Helpers of the GPU parity tests: run the HIP path through the binding and
+the oracle on the same arrays, compare element by element."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2301_12187_amd import api
+from helpers import bits
+
+
+def run_gpu(T, I, P, q_inst, q_T0, store_K=True, variant=0):
+    """numpy in -> dict of numpy outputs from the HIP path."""
+    B, ld, _ = T.shape
+    L = ld - 1
+    dev = torch.device("cuda:0")
+    Td = torch.from_numpy(T).to(dev)
+    Id = torch.from_numpy(I).to(dev)
+    qi = torch.from_numpy(np.ascontiguousarray(q_inst, dtype=np.int32)).to(dev)
+    qt = torch.from_numpy(np.ascontiguousarray(q_T0, dtype=np.int32)).to(dev)
+    buf = api.Buffers(B, L, P, len(q_inst), store_K=store_K)
+    # poison the outputs so that an unwritten cell cannot pass by accident
+    buf.M.fill_(float("nan"))
+    if buf.K is not None:
+        buf.K.fill_(0xEE)
+    buf.Topt.fill_(-7)
+    buf.split.fill_(0xEE)
+    buf.A.fill_(-9)
+    buf.S.fill_(-9)
+    prev = api.dpc_set_stage2_variant(variant)
+    try:
+        api.solve(Td, Id, qi, qt, buf)
+        api.dpc_stage2_check(buf.workspace)
+    finally:
+        api.dpc_set_stage2_variant(prev)
+    torch.cuda.synchronize()
+    out = dict(Topt=buf.Topt.cpu().numpy(), split=buf.split.cpu().numpy(),
+               M=buf.M.cpu().numpy(), K=None if buf.K is None else buf.K.cpu().numpy(),
+               A=buf.A.cpu().numpy(), S=buf.S.cpu().numpy(), A_len=buf.A_len.cpu().numpy(),
+               S_len=buf.S_len.cpu().numpy(), obj=buf.obj.cpu().numpy(),
+               lat=buf.lat.cpu().numpy(), status=buf.status.cpu().numpy())
+    return out
+
+
+def run_oracle(T, I, P, q_inst, q_T0, threads=8):
+    Topt, split, M, K = oracle.solve_batch(T, I, P, want_K=True, threads=threads)
+    res = [oracle.backtrack(Topt[b], split[b], I[b], M[b], K[b], int(t))
+           for b, t in zip(q_inst, q_T0)]
+    return dict(Topt=Topt, split=split, M=M, K=K, queries=res)
+
+
+def first_diff(a, b):
+    bad = np.argwhere(a != b)
+    return None if bad.size == 0 else tuple(int(x) for x in bad[0])
+
+
+def compare(gpu, ref, L, what=""):
+    """Bit-exact comparison of every output (tolerance 0: each candidate is a
+    single binary32 add followed by exact comparisons)."""
+    ii, jj = np.triu_indices(L + 1, k=1)
+    d = first_diff(gpu["Topt"], ref["Topt"])
+    assert d is None, (what, "Topt", d)
+    d = first_diff(gpu["split"], ref["split"])
+    assert d is None, (what, "split", d)
+    d = first_diff(bits(gpu["M"]), bits(ref["M"]))
+    assert d is None, (what, "M", d, gpu["M"][d], ref["M"][d])
+    if gpu["K"] is not None:
+        d = first_diff(gpu["K"], ref["K"])
+        assert d is None, (what, "K", d, gpu["K"][d], ref["K"][d])
+    for q, r in enumerate(ref["queries"]):
+        assert gpu["status"][q] == r["status"], (what, q)
+        assert gpu["A_len"][q] == r["A_len"] and gpu["S_len"][q] == r["S_len"], (what, q)
+        assert gpu["lat"][q] == r["lat"], (what, q)
+        assert bits(gpu["obj"][q:q + 1])[0] == bits(np.array([r["obj"]]))[0], (what, q)
+        if r["status"] == 0:
+            assert list(gpu["A"][q][:r["A_len"]]) == list(r["A"]), (what, q)
+            assert list(gpu["S"][q][:r["S_len"]]) == list(r["S"]), (what, q)

@@ -1,0 +1,195 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element
+by element, tolerance 0 (integers, indices and binary32 bit patterns)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2301_12187_amd import api, inputs
+from helpers import rand_tables, DPC_INF
+from gpu_common import compare, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = [1, 2]
+
+
+def _all_budgets(B, P, step=1):
+    qi = np.repeat(np.arange(B, dtype=np.int32), len(range(0, P, step)))
+    qt = np.tile(np.arange(0, P, step, dtype=np.int32), B)
+    return qi, qt
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("cid", [1, 2])
+def test_config_single_instance(cid, variant):
+    cfg = inputs.CONFIGS[cid]
+    T, I, base = inputs.make_batch(cfg, seed=0)
+    qi, qt = _all_budgets(1, cfg.P)             # cfg2 sweeps every budget; do it for cfg1 too
+    g = run_gpu(T, I, cfg.P, qi, qt, variant=variant)
+    r = run_oracle(T, I, cfg.P, qi, qt)
+    compare(g, r, cfg.L, cfg.name)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("seed", range(6))
+def test_tiny_tie_rich_instances(seed, variant):
+    rng = np.random.default_rng(1000 + seed)
+    B = 7
+    L = int(rng.integers(1, 20))
+    P = int(rng.integers(1, 140))
+    Ts, Is = [], []
+    for b in range(B):
+        T, I = rand_tables(rng, L, tmax=5, inf_frac=0.2, ikind=("int", "mixed", "neg")[b % 3],
+                           tmin=0 if b == 3 else 1)
+        if b == 5 and L >= 3:
+            I[0, L] = -np.inf
+        Ts.append(T)
+        Is.append(I)
+    T, I = np.stack(Ts), np.stack(Is)
+    qi, qt = _all_budgets(B, P)
+    g = run_gpu(T, I, P, qi, qt, variant=variant)
+    r = run_oracle(T, I, P, qi, qt)
+    compare(g, r, L, f"tiny seed {seed} L={L} P={P}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_ragged_shapes_span_several_tiles(variant):
+    """Sizes that are not multiples of any tile: several t-tiles with a ragged
+    tail, row counts that leave a partial row block."""
+    rng = np.random.default_rng(77)
+    for (B, L, P, tmax) in ((3, 37, 2333, 60), (2, 70, 1025, 9), (5, 9, 4099, 700),
+                            (1, 255, 515, 6)):
+        Ts, Is = [], []
+        for b in range(B):
+            T, I = rand_tables(rng, L, tmax=tmax, inf_frac=0.3, ikind="neg", span=min(L, 11))
+            Ts.append(T)
+            Is.append(I)
+        T, I = np.stack(Ts), np.stack(Is)
+        qi, qt = _all_budgets(B, P, step=max(1, P // 50))
+        g = run_gpu(T, I, P, qi, qt, variant=variant)
+        r = run_oracle(T, I, P, qi, qt)
+        compare(g, r, L, f"ragged B={B} L={L} P={P}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_wide_shift_spread_and_infeasible_blocks(variant):
+    """Adversarial latencies: shifts that differ wildly between neighbouring
+    columns of Topt, latencies beyond P, whole instances that are infeasible."""
+    rng = np.random.default_rng(78)
+    B, L, P = 4, 40, 3000
+    Ts, Is = [], []
+    for b in range(B):
+        T, I = rand_tables(rng, L, tmax=5, ikind="mixed")
+        ii, jj = np.triu_indices(L + 1, k=1)
+        jump = rng.random(ii.size) < 0.3
+        T[ii[jump], jj[jump]] = rng.integers(0, 4000, size=int(jump.sum()))
+        if b == 2:
+            T[0, 1:] = DPC_INF              # no block starts at layer 0: nothing is feasible
+        Ts.append(T)
+        Is.append(I)
+    T, I = np.stack(Ts), np.stack(Is)
+    qi, qt = _all_budgets(B, P, step=37)
+    # stage 2 is fed the oracle-independent GPU Topt, as in the real path
+    g = run_gpu(T, I, P, qi, qt, variant=variant)
+    r = run_oracle(T, I, P, qi, qt)
+    compare(g, r, L, "wide shifts")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_denormals_and_signed_zero(variant):
+    """binary32 adds must keep denormals and the sign rules of +-0."""
+    rng = np.random.default_rng(79)
+    B, L, P = 2, 12, 300
+    T, I = zip(*[rand_tables(rng, L, tmax=20, ikind="mixed") for _ in range(B)])
+    T, I = np.stack(T), np.stack(I)
+    I[0] = (I[0] * np.float32(1e-39)).astype(np.float32)      # denormal importances
+    I[1][np.triu_indices(L + 1, k=1)] = np.float32(-0.0)
+    qi, qt = _all_budgets(B, P, step=7)
+    g = run_gpu(T, I, P, qi, qt, variant=variant)
+    r = run_oracle(T, I, P, qi, qt)
+    assert np.any((np.abs(r["M"][0]) > 0) & (np.abs(r["M"][0]) < 1.1754944e-38))
+    compare(g, r, L, "denormals / zeros")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_without_stored_backpointers(variant):
+    cfg = inputs.CONFIGS[2]
+    T, I, base = inputs.make_batch(cfg, seed=3)
+    qi, qt = _all_budgets(1, cfg.P, step=9)
+    g = run_gpu(T, I, cfg.P, qi, qt, store_K=False, variant=variant)
+    r = run_oracle(T, I, cfg.P, qi, qt)
+    compare(g, r, cfg.L, "K == NULL")
+
+
+def test_bad_queries_and_empty_query_list():
+    cfg = inputs.CONFIGS[1]
+    T, I, _ = inputs.make_batch(cfg, seed=0)
+    qi = np.array([0, 1, -1, 0, 0], np.int32)
+    qt = np.array([250, 250, 5, cfg.P, -1], np.int32)
+    g = run_gpu(T, I, cfg.P, qi, qt)
+    assert list(g["status"]) == [0, 2, 2, 2, 2]
+    assert list(g["A_len"][1:]) == [-1] * 4 and list(g["lat"][1:]) == [-1] * 4
+    assert np.isneginf(g["obj"][1:]).all()
+    g = run_gpu(T, I, cfg.P, np.zeros(0, np.int32), np.zeros(0, np.int32))
+    assert g["M"].shape == (1, cfg.L + 1, cfg.P)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_config3_batch(variant):
+    cfg = inputs.CONFIGS[3]
+    T, I, base = inputs.make_batch(cfg, seed=0)
+    qi, qt = inputs.budgets(cfg, base)
+    g = run_gpu(T, I, cfg.P, qi, qt, variant=variant)
+    r = run_oracle(T, I, cfg.P, qi, qt, threads=16)
+    compare(g, r, cfg.L, cfg.name)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_config4_batch(variant):
+    cfg = inputs.CONFIGS[4]
+    T, I, base = inputs.make_batch(cfg, seed=0)
+    qi, qt = inputs.budgets(cfg, base)
+    g = run_gpu(T, I, cfg.P, qi, qt, variant=variant)
+    # the oracle on a sample of instances (full table each)
+    sample = np.arange(0, cfg.B, 8)
+    sel = np.isin(qi, sample)
+    r = run_oracle(T[sample], I[sample], cfg.P, np.searchsorted(sample, qi[sel]), qt[sel],
+                   threads=16)
+    gs = {k: (v[sample] if k in ("Topt", "split", "M", "K") else v[sel]) for k, v in g.items()}
+    compare(gs, r, cfg.L, cfg.name)
+
+
+def test_config5_full_size_sampled_instances():
+    """The launch configuration bench.py times (all 64 instances, default
+    kernel choice); the oracle recomputes a sample of whole instances."""
+    cfg = inputs.CONFIGS[5]
+    T, I, base = inputs.make_batch(cfg, seed=0)
+    qi, qt = inputs.budgets(cfg, base)
+    g = run_gpu(T, I, cfg.P, qi, qt, variant=0)
+    sample = np.array([0, 9, 18, 27, 36, 45, 54, 63])
+    sel = np.isin(qi, sample)
+    r = run_oracle(T[sample], I[sample], cfg.P, np.searchsorted(sample, qi[sel]), qt[sel],
+                   threads=16)
+    gs = {k: (v[sample] if k in ("Topt", "split", "M", "K") else v[sel]) for k, v in g.items()}
+    compare(gs, r, cfg.L, cfg.name)
+    # properties that hold for every instance at any size
+    M = g["M"]
+    assert not np.isnan(M).any()
+    fin = np.isfinite(M[:, cfg.L, :])
+    for b in range(cfg.B):
+        row = M[b, cfg.L]
+        first = int(g["Topt"][b, 0, cfg.L])
+        assert np.isneginf(row[:first]).all() and np.isfinite(row[first:]).all()
+        assert (np.diff(row[first:]) >= 0).all()
+    ok = g["status"] == 0
+    assert (g["lat"][ok] <= qt[ok]).all()
+
+
+def test_repeated_runs_are_bitwise_identical():
+    cfg = inputs.CONFIGS[4]
+    T, I, base = inputs.make_batch(cfg, seed=5, B=32)
+    qi, qt = inputs.budgets(cfg, base)
+    outs = [run_gpu(T, I, cfg.P, qi, qt) for _ in range(3)]
+    for o in outs[1:]:
+        assert (o["M"].view(np.uint32) == outs[0]["M"].view(np.uint32)).all()
+        assert (o["K"] == outs[0]["K"]).all() and (o["S"][o["S"] >= 0] == outs[0]["S"][outs[0]["S"] >= 0]).all()

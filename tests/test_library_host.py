@@ -1,0 +1,61 @@
+"""Host-side checks of libdpc.so that need no GPU: the library loads, exports
+every function include/dpc.h declares, and rejects bad arguments before any
+device work is queued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2301_12187_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "dpc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dpc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported():
+    names = _declared_functions()
+    assert set(names) == set(api.EXPORTS), names
+    lib = api.load()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    lib = api.load()
+    p = ctypes.c_void_p(256)          # never dereferenced: checks fail first
+    NULL, SHAPE, WS = -1, -2, -3
+    assert lib.dpc_stage1_minplus(1, 4, None, p, p, None) == NULL
+    assert lib.dpc_stage1_minplus(1, 4, p, None, p, None) == NULL
+    assert lib.dpc_stage1_minplus(0, 4, p, p, p, None) == SHAPE
+    assert lib.dpc_stage1_minplus(1, 0, p, p, p, None) == SHAPE
+    assert lib.dpc_stage1_minplus(1, 256, p, p, p, None) == SHAPE
+    assert lib.dpc_stage2_knapsack(1, 4, 8, None, p, p, p, p, 256, None) == NULL
+    assert lib.dpc_stage2_knapsack(1, 4, 8, p, p, p, None, None, 256, None) == NULL
+    assert lib.dpc_stage2_knapsack(1, 4, 0, p, p, p, p, p, 256, None) == SHAPE
+    assert lib.dpc_stage2_knapsack(1, 300, 8, p, p, p, p, p, 256, None) == SHAPE
+    need = lib.dpc_stage2_workspace_bytes(4, 50, 1000)
+    assert need >= 1
+    assert lib.dpc_stage2_knapsack(4, 50, 1000, p, p, p, p, p, need - 1, None) == WS
+    assert lib.dpc_stage2_knapsack(4, 50, 1000, p, p, p, p, ctypes.c_void_p(264), need, None) == WS
+    assert lib.dpc_stage2_workspace_bytes(0, 50, 1000) == 0
+    args = [p] * 10
+    assert lib.dpc_backtrack(1, 4, 8, p, p, p, p, p, -1, *args, None) == SHAPE
+    assert lib.dpc_backtrack(1, 4, 8, p, p, p, p, p, 0, *args, None) == 0     # nothing to do
+    assert lib.dpc_backtrack(1, 4, 8, None, p, p, p, p, 3, *args, None) == NULL
+    assert lib.dpc_backtrack(1, 4, 8, p, p, p, p, None, 3, p, None, *([p] * 8), None) == NULL
+    assert lib.dpc_set_stage2_variant(7) == SHAPE
+    assert b"DPC_ERR_NULL" in lib.dpc_status_string(NULL)
+    assert lib.dpc_status_string(12345)
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    T = torch.zeros((1, 5, 5), dtype=torch.int32)
+    with pytest.raises(api.DpcError):
+        api.dpc_stage1_minplus(T, T.clone(), torch.zeros((1, 5, 5), dtype=torch.uint8))
