@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the two-stage depth-compression DP on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--variant 0]
+
+One step = one pass of the whole hot path over one batch of synthetic input
+that is already resident in HBM: dpc_stage1_minplus, dpc_stage2_knapsack,
+dpc_backtrack, queued on one stream.  The default workload is the stress
+configuration (B=64, L=200, P=16000, dense feasibility, M and K stored, set
+recovery at every budget that is a multiple of 100), the one the throughput
+target is quoted on.  Prints ONE JSON line.
+
+  value        nominal relax-ops per second, B*L^2*P / step time, as the metric
+               is named; `exact_relax_ops_per_s` counts the candidates that
+               exist, B*P*L(L+1)/2, and is what the roofline uses.
+  roofline     stage-2 kernel(s): plain-VALU bound.  One relax = 1 add,
+               1 compare, 2 selects = 4 lane-ops (2 when K is not stored);
+               peak = 256 CU x 64 lanes/clk x 2.4 GHz = 39.3 T lane-ops/s
+               (the 157.3 TFLOP/s fp32 vector figure without the FMA and
+               packed factors of 2).  Duration from HIP events on the launch
+               stream around dpc_stage2_knapsack in every timed step.
+  cpu_baseline the CPU oracle, as it stands, on a bounded sample of instances
+               of the same workload, one instance per host thread.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "DP relax-ops/sec (B·L²·P) + batch solve latency ms, 1×MI355X"
+VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9        # 39.3e12
+# HBM bytes per stage-2 launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/), keyed by (config, variant actually run); None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5)
+    ap.add_argument("--variant", type=int, default=0, help="stage-2 kernel family (0 auto)")
+    ap.add_argument("--no-K", action="store_true", help="do not store back-pointers")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the instances shard trivially over "
+              "GPUs with no exchange, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2301_12187_amd import api, inputs
+
+    cfg = inputs.CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    T, I, base = inputs.make_batch(cfg, seed=args.seed)
+    qi, qt = inputs.budgets(cfg, base)
+    Td, Id = torch.from_numpy(T).to(dev), torch.from_numpy(I).to(dev)
+    qid, qtd = torch.from_numpy(qi).to(dev), torch.from_numpy(qt).to(dev)
+    buf = api.Buffers(cfg.B, cfg.L, cfg.P, len(qi), store_K=not args.no_K)
+    api.dpc_set_stage2_variant(args.variant)
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record(stream)
+        api.dpc_stage1_minplus(Td, buf.Topt, buf.split)
+        if ev:
+            ev[1].record(stream)
+        api.dpc_stage2_knapsack(buf.Topt, Id, buf.M, buf.K, buf.workspace)
+        if ev:
+            ev[2].record(stream)
+        api.dpc_backtrack(buf.Topt, buf.split, Id, buf.M, buf.K, qid, qtd, buf.A, buf.A_len,
+                          buf.S, buf.S_len, buf.obj, buf.lat, buf.status)
+        if ev:
+            ev[3].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    api.dpc_stage2_check(buf.workspace)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    api.dpc_stage2_check(buf.workspace)
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    s1 = [e[0].elapsed_time(e[1]) for e in evs]
+    s2 = [e[1].elapsed_time(e[2]) for e in evs]
+    s3 = [e[2].elapsed_time(e[3]) for e in evs]
+    exact = inputs.relax_ops_exact(cfg.B, cfg.L, cfg.P)
+    nominal = inputs.relax_ops_nominal(cfg.B, cfg.L, cfg.P)
+    s2_avg = float(np.mean(s2))
+    ops_per_relax = 2 if args.no_K else 4
+    achieved = ops_per_relax * exact / (s2_avg * 1e-3)
+    n_ok = int((buf.status == 0).sum().item())
+
+    out = {
+        "metric": METRIC,
+        "value": nominal / (ms_step * 1e-3),
+        "unit": "relax-ops/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "L": cfg.L, "P": cfg.P,
+                   "queries": int(len(qi)), "store_K": not args.no_K,
+                   "stage2_variant": args.variant, "seed": args.seed},
+        "exact_relax_ops_per_s": exact / (ms_step * 1e-3),
+        "stage2_exact_relax_ops_per_s": exact / (s2_avg * 1e-3),
+        "stage_ms": {"stage1": float(np.mean(s1)), "stage2": s2_avg,
+                     "stage2_min": float(np.min(s2)), "backtrack": float(np.mean(s3))},
+        "feasible_queries": n_ok,
+        "roofline": {
+            "bound": "alu", "kernel": "stage 2 (dpc_stage2_knapsack)",
+            "achieved": achieved / 1e12, "peak": VALU_PEAK_LANE_OPS / 1e12,
+            "unit": "TOP/s", "frac": achieved / VALU_PEAK_LANE_OPS,
+            "ops_per_relax": ops_per_relax,
+            "traffic": MEASURED_TRAFFIC.get((args.config, args.variant)),
+        },
+    }
+
+    if not args.no_cpu:
+        import oracle
+        cores = min(16, os.cpu_count() or 1)
+        nb = min(cfg.B, cores)
+        # about 10-30 s of CPU work: whole instances, one per thread
+        per_inst = inputs.relax_ops_exact(1, cfg.L, cfg.P)
+        while nb * per_inst < 4e9 and nb < cfg.B and nb < 8 * cores:
+            nb += cores
+        nb = min(nb, cfg.B)
+        sel = qi < nb
+        tc0 = time.perf_counter()
+        To, sp, Mo, Ko = oracle.solve_batch(T[:nb], I[:nb], cfg.P, want_K=not args.no_K,
+                                            threads=cores)
+        for b, t in zip(qi[sel], qt[sel]):
+            oracle.backtrack(To[b], sp[b], I[b], Mo[b], None if Ko is None else Ko[b], int(t))
+        tc1 = time.perf_counter()
+        out["cpu_baseline"] = {
+            "value": inputs.relax_ops_nominal(nb, cfg.L, cfg.P) / (tc1 - tc0),
+            "unit": "relax-ops/s", "cores": min(cores, nb), "kind": "oracle",
+            "sample": f"{nb} of {cfg.B} instances of {cfg.name}, all stages, "
+                      f"{tc1 - tc0:.2f} s wall",
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

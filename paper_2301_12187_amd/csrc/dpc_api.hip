@@ -5,6 +5,21 @@ namespace {
 
 int g_stage2_variant = 0;
 
+int num_compute_units()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            n <= 0)
+            return -1;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 bool shape_ok(int B, int L, int P)
 {
     return B >= 1 && L >= 1 && L <= DPC_MAX_L && P >= 1 &&
@@ -48,7 +63,7 @@ int dpc_stage1_minplus(int32_t B, int32_t L, const int32_t* T, int32_t* Topt, ui
 size_t dpc_stage2_workspace_bytes(int32_t B, int32_t L, int32_t P)
 {
     if (!shape_ok(B, L, P)) return 0;
-    return 256;
+    return dpc::stage2_tiled_workspace_bytes(B, L, P);
 }
 
 int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const float* I,
@@ -59,15 +74,30 @@ int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, co
     if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
     if (workspace_bytes < dpc_stage2_workspace_bytes(B, L, P) || ((uintptr_t)workspace & 255))
         return DPC_ERR_WORKSPACE;
-    hipError_t e = dpc::launch_stage2_rows(B, L, P, Topt, I, M, K, (hipStream_t)stream);
+    hipError_t e;
+    if (g_stage2_variant == 1) {
+        // the row family uses no workspace; clear the header so that a later
+        // dpc_stage2_check reads "no error"
+        e = dpc::launch_clear_words(workspace, 2, (hipStream_t)stream);
+        if (e == hipSuccess)
+            e = dpc::launch_stage2_rows(B, L, P, Topt, I, M, K, (hipStream_t)stream);
+    } else {
+        const int ncu = num_compute_units();
+        if (ncu <= 0) return DPC_ERR_HIP;
+        e = dpc::launch_stage2_tiled(B, L, P, Topt, I, M, K, workspace, ncu, (hipStream_t)stream);
+    }
     return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
 }
 
 int dpc_stage2_check(const void* workspace, void* stream)
 {
     if (!workspace) return DPC_ERR_NULL;
+    uint32_t head[2] = {0, 0};
+    if (hipMemcpyAsync(head, workspace, sizeof(head), hipMemcpyDeviceToHost,
+                       (hipStream_t)stream) != hipSuccess)
+        return DPC_ERR_HIP;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DPC_ERR_HIP;
-    return DPC_OK;
+    return dpc::stage2_tiled_error(head) ? DPC_ERR_TIMEOUT : DPC_OK;
 }
 
 int dpc_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const uint8_t* split,

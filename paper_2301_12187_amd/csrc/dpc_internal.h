@@ -11,6 +11,13 @@ hipError_t launch_stage1(int B, int L, const int32_t* T, int32_t* Topt, uint8_t*
                          hipStream_t st);
 hipError_t launch_stage2_rows(int B, int L, int P, const int32_t* Topt, const float* I,
                               float* M, uint8_t* K, hipStream_t st);
+// zero `nwords` 32-bit words with a small kernel (safe to record into a HIP graph)
+hipError_t launch_clear_words(void* p, int nwords, hipStream_t st);
+size_t stage2_tiled_workspace_bytes(int B, int L, int P);
+hipError_t launch_stage2_tiled(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
+                               uint8_t* K, void* workspace, int num_cu, hipStream_t st);
+// reads the error word out of a host copy of the first 8 workspace bytes
+int stage2_tiled_error(const void* workspace_host_copy);
 hipError_t launch_backtrack(int B, int L, int P, const int32_t* Topt, const uint8_t* split,
                             const float* I, const float* M, const uint8_t* K, int Q,
                             const int32_t* q_inst, const int32_t* q_T0, int32_t* A,
