@@ -154,7 +154,9 @@ const char *dpc_status_string(int code);
  * Tuning knob for measurements: selects the stage-2 kernel family.
  *   0  automatic (default)
  *   1  row-at-a-time kernels reading M from global memory (one launch per row)
- *   2  persistent LDS-tiled kernel
+ *   2  persistent LDS-tiled kernel, strip shape chosen from the problem size
+ *   21..25  persistent LDS-tiled kernel with a fixed strip shape: 256, 512,
+ *       1024, 2048 or 4096 budgets per workgroup
  * Returns the previous value, or DPC_ERR_SHAPE for an unknown one.  Results
  * are bit-identical for every choice.  Process-wide, not thread-safe.
  */

@@ -52,8 +52,8 @@ struct S2Header {
 };
 
 struct __attribute__((aligned(64))) S2Rec {
-    int32_t w[S2_R];               // shift Topt[i][j0+rr]; -1 = no candidate
-    float imp[S2_R];               // I[i][j0+rr]; -inf where w = -1
+    int32_t off[S2_R];             // maxs - Topt[i][j0+rr]; 0 where there is no candidate
+    float imp[S2_R];               // I[i][j0+rr]; -inf where there is no candidate
 };
 
 struct S2Info {
@@ -94,7 +94,10 @@ hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
 
 // One record per (instance b, row block r, predecessor i): the candidates that
 // row i offers to the rows j0..j0+R-1 of block r (j0 = 1 + r*R).  A candidate
-// exists when i < j, j <= L and 0 <= Topt[i][j] < P.
+// exists when i < j, j <= L and 0 <= Topt[i][j] < P.  Shifts are stored as
+// offsets below the largest shift of the record, the position of the candidate
+// inside the LDS window of row i; a missing candidate has importance -inf and
+// so never wins whatever it is added to.
 __global__ __launch_bounds__(256) void stage2_pack_kernel(
     int L, int P, int NR, const int32_t* __restrict__ Topt, const float* __restrict__ I,
     S2Rec* __restrict__ recs, S2Info* __restrict__ infos)
@@ -108,6 +111,7 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     const int32_t* To = Topt + (size_t)b * ld * ld;
     const float* Ib = I + (size_t)b * ld * ld;
     S2Rec rec;
+    int wv[S2_R];
     int mins = 0x7FFFFFFF, maxs = -1;
 #pragma unroll
     for (int rr = 0; rr < S2_R; ++rr) {
@@ -123,14 +127,27 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
                 maxs = max(maxs, w);
             }
         }
-        rec.w[rr] = w;
+        wv[rr] = w;
         rec.imp[rr] = imp;
     }
+#pragma unroll
+    for (int rr = 0; rr < S2_R; ++rr) rec.off[rr] = wv[rr] < 0 ? 0 : maxs - wv[rr];
     const size_t idx = ((size_t)b * NR + r) * ld + i;
     recs[idx] = rec;
     infos[idx].mins = mins;
     infos[idx].maxs = maxs;
 }
+
+// Optional phase timers (build with -DDPC_S2_TIMERS): thread 0 of every
+// workgroup accumulates wall-clock ticks (100 MHz) per phase and adds them to
+// the spare words of the workspace header.
+#ifdef DPC_S2_TIMERS
+#define TMARK(var) const long long var = wall_clock64()
+#define TACC(slot, a, b) do { if (tid == 0) tacc[slot] += (b) - (a); } while (0)
+#else
+#define TMARK(var) do {} while (0)
+#define TACC(slot, a, b) do {} while (0)
+#endif
 
 __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
 {
@@ -144,16 +161,19 @@ __device__ __forceinline__ void wait_lds_loads()
 }
 
 // Copy the window tp in [lo, lo + n) of a row of M into slot[0..n): -inf for
-// tp < 0, nothing for tp >= tlimit.  16-byte groups that lie inside
-// [0, tlimit) go global -> LDS without passing registers (the lanes of a wave
-// fill consecutive 16-byte cells from a wave-uniform LDS base); the groups at
-// the edges are written element by element.  `row0`: the row is the base case
-// M[0][t] = +0, not read from memory.
+// tp < 0, nothing for tp >= tlimit.  The window is cut into 16-byte groups, one
+// per lane and pass.  A group inside [0, tlimit) goes global -> LDS without
+// passing registers (the lanes of a wave fill consecutive 16-byte cells from a
+// wave-uniform LDS base); a group entirely below 0 is one 16-byte store of
+// -inf; the at most two groups that straddle 0 or tlimit are written element
+// by element.  `row0`: the row is the base case M[0][t] = +0, not read from
+// memory.
 template <int NT, int SLOTW>
 __device__ __forceinline__ void stage_window(float* slot, const float* row, int lo, int n,
                                              int tlimit, bool row0, int tid, int wave_base)
 {
     constexpr int NGK = (SLOTW / 4 + NT - 1) / NT;
+    constexpr float NINF = -INFINITY;
 #pragma unroll
     for (int k = 0; k < NGK; ++k) {
         const int x = 4 * (tid + NT * k);
@@ -163,12 +183,16 @@ __device__ __forceinline__ void stage_window(float* slot, const float* row, int 
                 __builtin_amdgcn_global_load_lds(row + tp,
                                                  (lds_void*)(slot + 4 * (wave_base + NT * k)), 16,
                                                  0, 0);
+            } else if (tp + 3 < 0) {
+                *(float4*)(slot + x) = make_float4(NINF, NINF, NINF, NINF);
+            } else if (row0 && tp >= 0) {
+                *(float4*)(slot + x) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int tpe = tp + e;
                     if (tpe < tlimit) {
-                        float v = -INFINITY;
+                        float v = NINF;
                         if (tpe >= 0) v = row0 ? 0.0f : row[tpe];
                         slot[x + e] = v;
                     }
@@ -178,8 +202,8 @@ __device__ __forceinline__ void stage_window(float* slot, const float* row, int 
     }
 }
 
-template <int NT, int U, int CH, int DMAX, bool STORE_K>
-__global__ __launch_bounds__(NT) void stage2_tiled_kernel(
+template <int NT, int U, int CH, int DMAX, int WPE, bool STORE_K>
+__global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
     int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* progress,
     const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos, int NS, int total,
     long long wait_limit)
@@ -198,11 +222,23 @@ __global__ __launch_bounds__(NT) void stage2_tiled_kernel(
     const int ld = L + 1;
     const int NR = (L + R - 1) / R;
 
+#ifdef DPC_S2_TIMERS
+    long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const long long tkernel0 = wall_clock64();
+#endif
     for (;;) {
         if (tid == 0) sh_word = (int)atomicAdd(&hdr->ticket, 1u);
         __syncthreads();
         const int ticket = __builtin_amdgcn_readfirstlane(sh_word);
         __syncthreads();
+#ifdef DPC_S2_TIMERS
+        if (ticket >= total && tid == 0) {
+            tacc[7] = wall_clock64() - tkernel0;
+            for (int q = 0; q < 8; ++q)
+                atomicAdd((unsigned long long*)&hdr->pad[2 + 2 * q], (unsigned long long)tacc[q]);
+            atomicAdd(&hdr->pad[20], 1u);
+        }
+#endif
         if (ticket >= total) return;
         const int s = ticket / B;
         const int b = ticket - s * B;
@@ -236,12 +272,12 @@ __global__ __launch_bounds__(NT) void stage2_tiled_kernel(
                 for (int u = 0; u < U; ++u) { best[rr][u] = NINF; arg[rr][u] = DPC_NOARG; }
 
             // stage the windows of rows [i0, i0+CH) into `buf` (asynchronous)
-            auto stage_chunk = [&](float (*buf)[SLOTW], int i0) {
-                const int nrow = min(CH, j0 - i0);
-                for (int c = 0; c < nrow; ++c) {
+            auto stage_chunk = [&](float (*buf)[SLOTW], int i0, const S2Info (&inf)[CH]) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
                     const int i = i0 + c;
-                    const int mins = binfo[i].mins, maxs = binfo[i].maxs;
-                    if (maxs >= 0 && maxs - mins <= DMAX && mins <= tmax) {
+                    const int mins = inf[c].mins, maxs = inf[c].maxs;
+                    if (i < j0 && maxs >= 0 && maxs - mins <= DMAX && mins <= tmax) {
                         const int lo = t0 - maxs;
                         const int n = tend - mins - lo;
                         stage_window<NT, SLOTW>(buf[c], Mb + (size_t)i * P, lo, n, P, i == 0, tid,
@@ -251,40 +287,58 @@ __global__ __launch_bounds__(NT) void stage2_tiled_kernel(
             };
 
             // relax the block's rows from the rows [i0, i0+CH) held in `buf`
-            auto relax_chunk = [&](const float (*buf)[SLOTW], int i0) {
-                const int nrow = min(CH, j0 - i0);
-                for (int c = 0; c < nrow; ++c) {
-                    const int i = i0 + c;
-                    const S2Rec rec = brec[i];
-                    const int mins = binfo[i].mins, maxs = binfo[i].maxs;
-                    if (maxs < 0 || mins > tmax) continue;     // nothing reaches this strip
-                    if (maxs - mins <= DMAX) {
+            auto relax_chunk = [&](const float (*buf)[SLOTW], int i0, const S2Rec (&rec)[CH],
+                                   const S2Info (&inf)[CH]) {
 #pragma unroll
-                        for (int rr = 0; rr < R; ++rr) {
-                            const bool ok = (unsigned)rec.w[rr] <= (unsigned)tmax;
-                            const int off = ok ? maxs - rec.w[rr] : 0;
-                            // select on the bit pattern: keeps the choice on the scalar unit
-                            const float imp = __int_as_float(
-                                ok ? __float_as_int(rec.imp[rr]) : (int)0xFF800000);
+                for (int c = 0; c < CH; ++c) {
+                    const int i = i0 + c;
+                    const int mins = inf[c].mins, maxs = inf[c].maxs;
+                    if (i >= j0 || maxs < 0 || mins > tmax) continue;   // nothing reaches this strip
+                    const int thr = maxs - tmax;       // candidate rr is in reach iff off >= thr
+                    if (maxs - mins <= DMAX) {
+                        // LDS reads run one row of the block ahead of the arithmetic
+                        float mcur[U], mnxt[U];
+                        auto fetch = [&](float (&m)[U], int rr) {
+                            const bool ok = rec[c].off[rr] >= thr;
+                            const int off = ok ? rec[c].off[rr] : 0;
                             const float* sp = &buf[c][off + tid];
 #pragma unroll
+                            for (int u = 0; u < U; ++u) m[u] = sp[NT * u];
+                        };
+                        fetch(mcur, 0);
+#pragma unroll
+                        for (int rr = 0; rr < R; ++rr) {
+                            if (rr + 1 < R) fetch(mnxt, rr + 1);
+                            const bool ok = rec[c].off[rr] >= thr;
+                            // select on the bit pattern: keeps the choice on the scalar unit
+                            const float imp = __int_as_float(
+                                ok ? __float_as_int(rec[c].imp[rr]) : (int)0xFF800000);
+                            float cand[U];
+                            bool win[U];
+#pragma unroll
+                            for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
+#pragma unroll
+                            for (int u = 0; u < U; ++u) win[u] = cand[u] > best[rr][u];
+#pragma unroll
                             for (int u = 0; u < U; ++u) {
-                                const float cand = sp[NT * u] + imp;
-                                if (cand > best[rr][u]) { best[rr][u] = cand; arg[rr][u] = i; }
+                                best[rr][u] = win[u] ? cand[u] : best[rr][u];
+                                arg[rr][u] = win[u] ? i : arg[rr][u];
                             }
+#pragma unroll
+                            for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
                         }
                     } else {
                         const float* row = Mb + (size_t)i * P;
 #pragma unroll
                         for (int rr = 0; rr < R; ++rr) {
-                            const int w = rec.w[rr];
-                            if ((unsigned)w > (unsigned)tmax) continue;
+                            const int w = maxs - rec[c].off[rr];
+                            if (w > tmax) continue;
 #pragma unroll
                             for (int u = 0; u < U; ++u) {
                                 const int t = t0 + tid + NT * u;
                                 if (t < P && t >= w) {
                                     const float m = (i == 0) ? 0.0f : row[t - w];
-                                    const float cand = m + rec.imp[rr];
+                                    const float cand = m + rec[c].imp[rr];
                                     if (cand > best[rr][u]) { best[rr][u] = cand; arg[rr][u] = i; }
                                 }
                             }
@@ -293,25 +347,47 @@ __global__ __launch_bounds__(NT) void stage2_tiled_kernel(
                 }
             };
 
+            // one chunk: fetch its records and the next chunk's window extents (one
+            // batch of scalar loads, in flight across the barrier), start the next
+            // chunk's window copies, relax this chunk
+            S2Info inf_cur[CH], inf_nxt[CH];
+            auto load_infos = [&](S2Info (&inf)[CH], int i0) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c) inf[c] = binfo[min(i0 + c, L)];
+            };
+            auto chunk_step = [&](float (*cur)[SLOTW], float (*nxt)[SLOTW], int i0) {
+                S2Rec rec[CH];
+#pragma unroll
+                for (int c = 0; c < CH; ++c) rec[c] = brec[min(i0 + c, L)];
+                load_infos(inf_nxt, i0 + CH);
+                TMARK(ta);
+                wait_lds_loads();
+                __syncthreads();                       // `cur` filled, `nxt` free
+                TMARK(tb);
+                if (i0 + CH < j0) stage_chunk(nxt, i0 + CH, inf_nxt);
+                TMARK(tc);
+                relax_chunk(cur, i0, rec, inf_cur);
+                TMARK(td);
+                TACC(0, ta, tb);
+                TACC(1, tb, tc);
+                TACC(2, tc, td);
+#pragma unroll
+                for (int c = 0; c < CH; ++c) inf_cur[c] = inf_nxt[c];
+            };
+
             // ---------------- off-diagonal part: rows i < j0 ----------------
             // (the barrier that ended the previous block's diagonal part, or the
             //  ticket barrier, has freed both buffers)
-            stage_chunk(bufA, 0);
+            load_infos(inf_cur, 0);
+            stage_chunk(bufA, 0, inf_cur);
             for (int i0 = 0; i0 < j0; i0 += 2 * CH) {
-                wait_lds_loads();
-                __syncthreads();                       // bufA filled, bufB free
-                if (i0 + CH < j0) stage_chunk(bufB, i0 + CH);
-                relax_chunk(bufA, i0);
-                if (i0 + CH < j0) {
-                    wait_lds_loads();
-                    __syncthreads();                   // bufB filled, bufA free
-                    if (i0 + 2 * CH < j0) stage_chunk(bufA, i0 + 2 * CH);
-                    relax_chunk(bufB, i0 + CH);
-                }
+                chunk_step(bufA, bufB, i0);
+                if (i0 + CH < j0) chunk_step(bufB, bufA, i0 + CH);
             }
 
             // ---------------- diagonal part: rows inside the block ----------------
             // the strips to the left must have finished this block
+            TMARK(te);
             if (s > 0) {
                 if (tid == 0) {
                     const uint32_t* flag = &progress[(size_t)b * NS + s - 1];
@@ -335,6 +411,8 @@ __global__ __launch_bounds__(NT) void stage2_tiled_kernel(
                 if (!ok) return;                       // uniform: every thread leaves
             }
             __syncthreads();                           // off-diagonal readers done; sh_word free
+            TMARK(tf);
+            TACC(3, te, tf);
 
             // halo [t0 - hd, t0) of every row of the block that feeds a later row
             int hd[R];
@@ -384,11 +462,11 @@ __global__ __launch_bounds__(NT) void stage2_tiled_kernel(
                         const float* row = Mb + (size_t)j * P;
 #pragma unroll
                         for (int r2 = rr + 1; r2 < R; ++r2) {
-                            const int w = rec.w[r2];
+                            const int w = hd[rr] - rec.off[r2];
                             const float imp = rec.imp[r2];
-                            if ((unsigned)w > (unsigned)tmax) continue;
+                            if (w > tmax) continue;
                             if (in_lds) {
-                                const float* sp = &slot[hd[rr] - w + tid];
+                                const float* sp = &slot[rec.off[r2] + tid];
 #pragma unroll
                                 for (int u = 0; u < U; ++u) {
                                     const float cand = sp[NT * u] + imp;
@@ -410,6 +488,8 @@ __global__ __launch_bounds__(NT) void stage2_tiled_kernel(
             }
 
             // publish: this strip has finished block r
+            TMARK(tg);
+            TACC(4, tf, tg);
             if (s + 1 < NS) {
                 __threadfence();
                 __syncthreads();
@@ -419,11 +499,13 @@ __global__ __launch_bounds__(NT) void stage2_tiled_kernel(
             } else {
                 __syncthreads();                       // both buffers free for the next block
             }
+            TMARK(th);
+            TACC(5, tg, th);
         }
     }
 }
 
-template <int NT, int U, int CH, int DMAX>
+template <int NT, int U, int CH, int DMAX, int WPE>
 static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                              uint8_t* K, void* workspace, int num_cu, hipStream_t st)
 {
@@ -447,26 +529,45 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    const int wg_per_cu = 3;
+    // resident workgroups per compute unit: WPE waves per SIMD, 4 SIMDs
+    constexpr int wg_per_cu = (WPE * 4 * 64) / NT;
+    static_assert(wg_per_cu >= 1, "a workgroup must fit one compute unit");
     const int grid = (int)std::min<long long>(total, (long long)num_cu * wg_per_cu);
     const long long wait_limit = 500000000LL;      // 5 s of the 100 MHz wall clock
     if (K)
-        hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, true>), dim3(grid), dim3(NT), 0,
-                           st, B, L, P, M, K, hdr, progress, recs, infos, NS, (int)total,
+        hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, true>), dim3(grid), dim3(NT),
+                           0, st, B, L, P, M, K, hdr, progress, recs, infos, NS, (int)total,
                            wait_limit);
     else
-        hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, false>), dim3(grid), dim3(NT), 0,
-                           st, B, L, P, M, K, hdr, progress, recs, infos, NS, (int)total,
-                           wait_limit);
+        hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, false>), dim3(grid),
+                           dim3(NT), 0, st, B, L, P, M, K, hdr, progress, recs, infos, NS,
+                           (int)total, wait_limit);
     return hipGetLastError();
 }
+
+int g_s2_shape = 0;     // tuning override, see launch_stage2_tiled
 
 hipError_t launch_stage2_tiled(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                                uint8_t* K, void* workspace, int num_cu, hipStream_t st)
 {
-    if (P <= 256) return launch_cfg<256, 1, 4, 256>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-    if (P <= 512) return launch_cfg<256, 2, 4, 256>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-    return launch_cfg<256, 4, 4, 256>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+    // strip width W = NT*U.  Narrow tables take the narrowest strip that covers
+    // them; wide ones take the strip that gives about one workgroup-sized task
+    // per resident slot, so that the strips of an instance run as one shallow
+    // pipeline.
+    int shape = g_s2_shape;
+    if (shape == 0) {
+        if (P <= 256) shape = 1;
+        else if (P <= 512) shape = 2;
+        else shape = 4;
+    }
+    switch (shape) {
+        case 1: return launch_cfg<256, 1, 4, 240, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 2: return launch_cfg<256, 2, 4, 240, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 3: return launch_cfg<256, 4, 4, 256, 3>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 4: return launch_cfg<512, 2, 4, 256, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 5: return launch_cfg<1024, 2, 4, 256, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 int stage2_tiled_error(const void* workspace_host_copy)
