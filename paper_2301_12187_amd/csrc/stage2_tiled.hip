@@ -1,41 +1,48 @@
 // Stage 2, persistent LDS-tiled family (Algorithm 2 / recurrence Eq. 7 of the
 // paper): M[j][t] = max_i fl32(M[i][t - Topt[i][j]] + I[i][j]), lowest arg-max.
 //
-// Decomposition.  The budget axis of one instance is cut into strips of W
-// columns; the rows 1..L into blocks of R rows.  One workgroup owns a strip
-// and walks its row blocks from top to bottom, keeping the R x W running
-// (maximum, arg-max) pairs of the block in registers: lane `tid` owns the
-// columns t0 + tid + NT*u, u < U, of every row of the block.
+// Tasks.  The rows 1..L of an instance are cut into groups of R = 8 rows, the
+// budget axis into strips.  One task = (instance, row group, strip); it reads
+// only rows below its group from global memory and writes its own rows, so it
+// carries no state from task to task.  A workgroup keeps the R x WCAP running
+// (maximum, arg-max) pairs of a task in registers: lane `tid` owns the columns
+// tS + tid + NT*u, u < U, of every row of the group.
 //
-//   off-diagonal part  predecessors i below the block.  Row i is read through
-//     a window [t0 - maxshift_i, t0 + W - minshift_i) copied once into an LDS
+//   off-diagonal part  predecessors i below the group.  Row i is read through a
+//     window [tS - maxshift_i, tS + WCAP - minshift_i) copied once into an LDS
 //     slot (global -> LDS loads that bypass the registers, 16 bytes per lane)
-//     and then used by all R rows of the block, each at its own wave-uniform
+//     and then used by all R rows of the group, each at its own wave-uniform
 //     offset; consecutive lanes read consecutive LDS words.  The slots form
 //     two buffers of CH rows: while one chunk of rows is relaxed the next is
 //     in flight.
-//   diagonal part      predecessors inside the block, one row after the other:
-//     a finished row is written to global memory and, together with a halo
-//     fetched from the strips to its left, to an LDS slot from which the rows
-//     below it in the block are relaxed.
+//   diagonal part      predecessors inside the group, one row after the other:
+//     a finished row goes to an LDS slot from which the rows below it in the
+//     group are relaxed.
 //
-// Topt and I are first repacked per (instance, row block, predecessor i) into
-// 64-byte records {shift[R], importance[R]} plus the minimum and maximum shift,
-// so that the wave-uniform operands of a whole row arrive with one scalar load.
+// Ghost columns.  Inside a group, row j needs row i of the same group at
+// t - Topt[i][j], which for the first columns of a strip lies in the strip to
+// the left.  Instead of waiting for that strip the task recomputes those
+// columns itself: it starts g columns to the left of the columns it stores,
+// g = the longest chain of shifts inside the group, so every stored cell only
+// depends on cells the task computed correctly.  Tasks of one group are then
+// independent of each other.
 //
-// Dependencies point to lower rows and to lower-or-equal t only, so strip s
-// needs, from the strips to its left, rows that are complete through the
-// current block.  Strips are handed out as tickets in strip-major order by an
-// atomic counter; a workgroup publishes "blocks completed" per (instance,
-// strip) with release semantics and its right neighbour acquires it before
-// the diagonal part of the same block.  Every ticket only waits on a lower
-// ticket, which a running workgroup already owns, so the scheme cannot
-// deadlock whatever the number of resident workgroups; the waits are
-// time-bounded and a time-out makes every workgroup leave.
+// Order.  Tasks are handed out as tickets by an atomic counter, level by level
+// (level = row group), instance by instance, strip by strip.  A task waits for
+// the completion counter of the previous level of its instance (release /
+// acquire at agent scope); that level's tickets were all handed out one whole
+// level earlier, so the wait is normally over before it starts, and it can
+// never deadlock because it only ever waits on lower tickets.  Waits are
+// time-bounded; a time-out makes every workgroup leave.
 //
-// A row whose shifts into the block spread over more than DMAX columns does
-// not fit a slot; its candidates are read straight from global memory instead
-// (same arithmetic, same order).
+// Fallback.  If the shifts of some predecessor into a group spread over more
+// than DMAX columns, or the ghost width of the group exceeds its limit, the
+// group is run as R levels of one row each (spread 0, no ghost columns).
+//
+// Topt and I are first repacked per (instance, row group, predecessor i) into
+// 64-byte records {offset[R], importance[R]} plus the minimum and maximum
+// shift, so that the wave-uniform operands of a row arrive with one scalar
+// load; a second small kernel lays out the task table.
 #include <algorithm>
 #include "dpc_internal.h"
 
@@ -43,12 +50,13 @@ namespace dpc {
 
 typedef __attribute__((address_space(3))) void lds_void;
 
-constexpr int S2_R = 8;            // rows per block (record layout depends on it)
+constexpr int S2_R = 8;            // rows per group (record layout depends on it)
 
 struct S2Header {
     uint32_t ticket;
     uint32_t error;
-    uint32_t pad[62];
+    uint32_t total;                // number of tasks, written by the layout kernel
+    uint32_t pad[61];
 };
 
 struct __attribute__((aligned(64))) S2Rec {
@@ -60,20 +68,32 @@ struct S2Info {
     int32_t mins, maxs;            // over the valid shifts of the record; maxs = -1: none
 };
 
+// one entry per (level, instance); level = group * R + row-in-group
+struct S2Entry {
+    int32_t tstart;                // first ticket of the entry
+    int32_t cnt;                   // number of strips (tasks)
+    int32_t prev;                  // entry that must be complete first, -1: none
+    int32_t g;                     // >= 0: whole group, ghost width; -1: one row
+};
+
 struct S2Layout {
-    size_t progress_off, rec_off, info_off, total;
+    size_t done_off, entry_off, group_off, rec_off, info_off, total;
+    long long nentries;
 };
 
 static S2Layout s2_layout(int B, int L, int P)
 {
+    (void)P;
     S2Layout l;
-    const size_t ns = ((size_t)P + 255) / 256;      // upper bound over every strip width used
-    const size_t nr = ((size_t)L + S2_R - 1) / S2_R;
+    const size_t nq = ((size_t)L + S2_R - 1) / S2_R;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-    l.progress_off = sizeof(S2Header);
-    l.rec_off = up(l.progress_off + 4 * (size_t)B * ns);
-    l.info_off = up(l.rec_off + sizeof(S2Rec) * (size_t)B * nr * (L + 1));
-    l.total = up(l.info_off + sizeof(S2Info) * (size_t)B * nr * (L + 1));
+    l.nentries = (long long)nq * S2_R * B;
+    l.done_off = sizeof(S2Header);
+    l.entry_off = up(l.done_off + 4 * (size_t)l.nentries);
+    l.group_off = up(l.entry_off + sizeof(S2Entry) * ((size_t)l.nentries + 1));
+    l.rec_off = up(l.group_off + 4 * (size_t)B * nq);
+    l.info_off = up(l.rec_off + sizeof(S2Rec) * (size_t)B * nq * (L + 1));
+    l.total = up(l.info_off + sizeof(S2Info) * (size_t)B * nq * (L + 1));
     return l;
 }
 
@@ -92,24 +112,30 @@ hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
     return hipGetLastError();
 }
 
-// One record per (instance b, row block r, predecessor i): the candidates that
-// row i offers to the rows j0..j0+R-1 of block r (j0 = 1 + r*R).  A candidate
+// One record per (instance b, row group q, predecessor i): the candidates that
+// row i offers to the rows j0..j0+R-1 of the group (j0 = 1 + q*R).  A candidate
 // exists when i < j, j <= L and 0 <= Topt[i][j] < P.  Shifts are stored as
 // offsets below the largest shift of the record, the position of the candidate
 // inside the LDS window of row i; a missing candidate has importance -inf and
-// so never wins whatever it is added to.
+// so never wins whatever it is added to.  The workgroup also decides how the
+// group runs: groups[b][q] = ghost width g if every spread and every shift
+// inside the group fits dmax and g <= gmax, else -1 (row by row).
 __global__ __launch_bounds__(256) void stage2_pack_kernel(
-    int L, int P, int NR, const int32_t* __restrict__ Topt, const float* __restrict__ I,
-    S2Rec* __restrict__ recs, S2Info* __restrict__ infos)
+    int L, int P, int NQ, const int32_t* __restrict__ Topt, const float* __restrict__ I,
+    S2Rec* __restrict__ recs, S2Info* __restrict__ infos, int32_t* __restrict__ groups, int gmax,
+    int dmax, int wcap)
 {
+    __shared__ int wd[S2_R][S2_R];
+    __shared__ int viol;
     const int ld = L + 1;
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    const int r = blockIdx.y;
-    const int b = blockIdx.z;
-    if (i >= ld) return;
-    const int j0 = 1 + r * S2_R;
+    const int i = threadIdx.x;             // L <= 255: one thread per predecessor
+    const int q = blockIdx.x;
+    const int b = blockIdx.y;
+    const int j0 = 1 + q * S2_R;
     const int32_t* To = Topt + (size_t)b * ld * ld;
     const float* Ib = I + (size_t)b * ld * ld;
+    if (i == 0) viol = 0;
+    __syncthreads();
     S2Rec rec;
     int wv[S2_R];
     int mins = 0x7FFFFFFF, maxs = -1;
@@ -118,7 +144,7 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
         const int j = j0 + rr;
         int w = -1;
         float imp = -INFINITY;
-        if (j <= L && i < j) {
+        if (i < ld && j <= L && i < j) {
             const int v = To[i * ld + j];
             if (v >= 0 && v < P) {
                 w = v;
@@ -132,10 +158,99 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     }
 #pragma unroll
     for (int rr = 0; rr < S2_R; ++rr) rec.off[rr] = wv[rr] < 0 ? 0 : maxs - wv[rr];
-    const size_t idx = ((size_t)b * NR + r) * ld + i;
-    recs[idx] = rec;
-    infos[idx].mins = mins;
-    infos[idx].maxs = maxs;
+    if (i < ld) {
+        const size_t idx = ((size_t)b * NQ + q) * ld + i;
+        recs[idx] = rec;
+        infos[idx].mins = mins;
+        infos[idx].maxs = maxs;
+    }
+    if (i < j0 && maxs >= 0 && maxs - mins > dmax) viol = 1;
+    if (i >= j0 && i < j0 + S2_R) {
+#pragma unroll
+        for (int rr = 0; rr < S2_R; ++rr) wd[i - j0][rr] = wv[rr];
+    }
+    __syncthreads();
+    if (i == 0) {
+        // how far to the left of its stored columns each row must be correct
+        int need[S2_R];
+        int g = 0, hmax = 0;
+        for (int rr = S2_R - 1; rr >= 0; --rr) {
+            int n = 0;
+            for (int r2 = rr + 1; r2 < S2_R; ++r2)
+                if (wd[rr][r2] >= 0) {
+                    n = max(n, wd[rr][r2] + need[r2]);
+                    hmax = max(hmax, wd[rr][r2]);
+                }
+            need[rr] = n;
+            g = max(g, n);
+        }
+        // a table that fits one task has no strip to its left: no ghost columns
+        const bool bad = viol || hmax > dmax || (P > wcap && g > gmax);
+        groups[(size_t)b * NQ + q] = bad ? -1 : g;
+    }
+}
+
+// Task table: entries in ticket order (level-major, then instance), their
+// first tickets (exclusive prefix sum of the strip counts) and the total.
+__global__ __launch_bounds__(1024) void stage2_layout_kernel(
+    int B, int L, int P, int NQ, int wcap, const int32_t* __restrict__ groups,
+    S2Entry* __restrict__ entries, S2Header* hdr)
+{
+    __shared__ int part[1024];
+    const int tid = threadIdx.x;
+    const int N = NQ * S2_R * B;
+    const int per = (N + 1023) / 1024;
+    const int e0 = min(tid * per, N), e1 = min(e0 + per, N);
+    auto count = [&](int e, int& g) {
+        const int level = e / B, b = e - level * B;
+        const int q = level / S2_R, sub = level - q * S2_R;
+        const int hq = min(S2_R, L - q * S2_R);
+        const int grp = groups[(size_t)b * NQ + q];
+        g = grp >= 0 && sub == 0 ? grp : -1;
+        // the first strip starts at t = 0 and has no ghost columns
+        if (grp >= 0)
+            return sub != 0 ? 0 : P <= wcap ? 1 : 1 + (P - wcap + (wcap - grp) - 1) / (wcap - grp);
+        return sub < hq ? (P + wcap - 1) / wcap : 0;
+    };
+    int sum = 0;
+    for (int e = e0; e < e1; ++e) { int g; sum += count(e, g); }
+    part[tid] = sum;
+    __syncthreads();
+    // inclusive scan over the 1024 partial sums
+    for (int d = 1; d < 1024; d <<= 1) {
+        int v = tid >= d ? part[tid - d] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    int run = part[tid] - sum;
+    for (int e = e0; e < e1; ++e) {
+        int g;
+        const int c = count(e, g);
+        const int level = e / B, b = e - level * B;
+        const int q = level / S2_R, sub = level - q * S2_R;
+        int prev;
+        if (sub > 0) prev = e - B;
+        else if (q == 0) prev = -1;
+        else prev = groups[(size_t)b * NQ + q - 1] >= 0 ? ((q - 1) * S2_R) * B + b
+                                                        : ((q - 1) * S2_R + S2_R - 1) * B + b;
+        S2Entry en;
+        en.tstart = run;
+        en.cnt = c;
+        en.prev = prev;
+        en.g = g;
+        entries[e] = en;
+        run += c;
+    }
+    if (tid == 1023) {
+        S2Entry en;
+        en.tstart = part[1023];
+        en.cnt = 0;
+        en.prev = -1;
+        en.g = -1;
+        entries[N] = en;
+        hdr->total = (uint32_t)part[1023];
+    }
 }
 
 // Optional phase timers (build with -DDPC_S2_TIMERS): thread 0 of every
@@ -154,10 +269,54 @@ __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// wait until every global -> LDS load this wave has issued has landed
-__device__ __forceinline__ void wait_lds_loads()
+// M and K travel between workgroups on different compute units (and L2
+// slices): they are written with agent-scope stores, which go through to the
+// level every compute unit sees, and read back with agent-scope loads, which
+// do not use a copy cached before the write.  A task counts as complete once
+// the vector-memory counter of every wave has drained (the stores have been
+// acknowledged) and the completion counter has then been incremented.
+__device__ __forceinline__ void st_agent(float* p, float v)
 {
-    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0), expcnt and lgkmcnt untouched
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(uint8_t* p, uint8_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Workgroup barrier that orders LDS accesses only.  The vector-memory counter
+// is left alone, so global -> LDS copies for later chunks stay in flight
+// across it; the copies a barrier must cover are waited for explicitly
+// (wait_vm) before it.
+// (Written as assembly because the compiler otherwise drains every counter in
+// front of a barrier instruction.)
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+constexpr int DMA_AGENT_SCOPE = 16;        // cache-policy bit sc1 of the global -> LDS load
+
+// Wait until at most `later` of the vector-memory operations this wave has
+// issued are still outstanding.  They complete in order, so this waits for
+// everything issued before the last `later` ones.  A smaller number only waits
+// longer, so the count is clamped to what the instruction can encode here.
+__device__ __forceinline__ void wait_vm(int later)
+{
+    // s_waitcnt immediates: vmcnt in bits 3:0 (and 15:14), expcnt 6:4 and lgkmcnt 11:8 left alone
+    switch (later) {
+        case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+        case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
+        case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
+        case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
+        case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+        case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
+        case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+        case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
+        default: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+    }
 }
 
 // Copy the window tp in [lo, lo + n) of a row of M into slot[0..n): -inf for
@@ -169,20 +328,37 @@ __device__ __forceinline__ void wait_lds_loads()
 // by element.  `row0`: the row is the base case M[0][t] = +0, not read from
 // memory.
 template <int NT, int SLOTW>
-__device__ __forceinline__ void stage_window(float* slot, const float* row, int lo, int n,
-                                             int tlimit, bool row0, int tid, int wave_base)
+__device__ __forceinline__ int stage_window(float* slot, const float* row, int lo, int n,
+                                            int tlimit, bool row0, int tid, int wave_base)
 {
     constexpr int NGK = (SLOTW / 4 + NT - 1) / NT;
     constexpr float NINF = -INFINITY;
+    int issued = 0;      // global -> LDS loads this wave issued with at least one lane
+    if (!row0 && lo >= 0 && lo + ((n + 3) & ~3) <= tlimit) {
+        // the common case: every group is inside the row
+#pragma unroll
+        for (int k = 0; k < NGK; ++k) {
+            const int x = 4 * (tid + NT * k);
+            const bool go = x < n;
+            if (__ballot(go) != 0) ++issued;
+            if (go)
+                __builtin_amdgcn_global_load_lds(row + lo + x,
+                                                 (lds_void*)(slot + 4 * (wave_base + NT * k)), 16,
+                                                 0, DMA_AGENT_SCOPE);
+        }
+        return issued;
+    }
 #pragma unroll
     for (int k = 0; k < NGK; ++k) {
         const int x = 4 * (tid + NT * k);
         const int tp = lo + x;
+        const bool go = x < n && !row0 && tp >= 0 && tp + 3 < tlimit;
+        if (__ballot(go) != 0) ++issued;
         if (x < n) {
-            if (!row0 && tp >= 0 && tp + 3 < tlimit) {
+            if (go) {
                 __builtin_amdgcn_global_load_lds(row + tp,
                                                  (lds_void*)(slot + 4 * (wave_base + NT * k)), 16,
-                                                 0, 0);
+                                                 0, DMA_AGENT_SCOPE);
             } else if (tp + 3 < 0) {
                 *(float4*)(slot + x) = make_float4(NINF, NINF, NINF, NINF);
             } else if (row0 && tp >= 0) {
@@ -193,315 +369,351 @@ __device__ __forceinline__ void stage_window(float* slot, const float* row, int 
                     const int tpe = tp + e;
                     if (tpe < tlimit) {
                         float v = NINF;
-                        if (tpe >= 0) v = row0 ? 0.0f : row[tpe];
+                        if (tpe >= 0) v = row0 ? 0.0f : ld_agent(row + tpe);
                         slot[x + e] = v;
                     }
                 }
             }
         }
     }
+    return issued;
 }
 
 template <int NT, int U, int CH, int DMAX, int WPE, bool STORE_K>
 __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
-    int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* progress,
-    const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos, int NS, int total,
-    long long wait_limit)
+    int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* done,
+    const S2Entry* __restrict__ entries, const S2Rec* __restrict__ recs,
+    const S2Info* __restrict__ infos, int NQ, int nentries, long long wait_limit)
 {
     constexpr int R = S2_R;
-    constexpr int W = NT * U;
-    constexpr int SLOTW = W + DMAX + 4;     // multiple of 4
+    constexpr int WCAP = NT * U;
+    constexpr int SLOTW = WCAP + DMAX + 4;  // multiple of 4
     constexpr float NINF = -INFINITY;
     static_assert(2 * CH >= R - 1, "the diagonal part needs R-1 slots");
     __shared__ __attribute__((aligned(16))) float bufA[CH][SLOTW];
     __shared__ __attribute__((aligned(16))) float bufB[CH][SLOTW];
-    __shared__ int sh_word;
+    __shared__ __attribute__((aligned(16))) float bufC[CH][SLOTW];
+    __shared__ int sh_word[2];
 
     const int tid = threadIdx.x;
     const int wave_base = __builtin_amdgcn_readfirstlane(tid & ~63);
     const int ld = L + 1;
-    const int NR = (L + R - 1) / R;
 
 #ifdef DPC_S2_TIMERS
     long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const long long tkernel0 = wall_clock64();
 #endif
     for (;;) {
-        if (tid == 0) sh_word = (int)atomicAdd(&hdr->ticket, 1u);
+        TMARK(t_a);
+        // ---- next ticket and the entry it falls in (wave 0 searches the table)
+        if (tid < 64) {
+            int ticket = 0;
+            if (tid == 0) ticket = (int)atomicAdd(&hdr->ticket, 1u);
+            ticket = __builtin_amdgcn_readfirstlane(ticket);
+            const int total = (int)hdr->total;
+            int lo = 0, hi = nentries;
+            if (ticket < total) {
+                while (hi - lo > 1) {
+                    const int step = (hi - lo + 63) >> 6;
+                    const int p = lo + tid * step;
+                    const bool ok = p < hi && entries[p].tstart <= ticket;
+                    const int c = __popcll(__ballot(ok));
+                    lo = lo + (c - 1) * step;
+                    hi = min(hi, lo + step);
+                }
+            } else {
+                lo = -1;
+            }
+            if (tid == 0) { sh_word[0] = lo; sh_word[1] = ticket; }
+        }
         __syncthreads();
-        const int ticket = __builtin_amdgcn_readfirstlane(sh_word);
+        const int e = __builtin_amdgcn_readfirstlane(sh_word[0]);
+        const int ticket = __builtin_amdgcn_readfirstlane(sh_word[1]);
         __syncthreads();
 #ifdef DPC_S2_TIMERS
-        if (ticket >= total && tid == 0) {
+        if (e < 0 && tid == 0) {
             tacc[7] = wall_clock64() - tkernel0;
             for (int q = 0; q < 8; ++q)
-                atomicAdd((unsigned long long*)&hdr->pad[2 + 2 * q], (unsigned long long)tacc[q]);
-            atomicAdd(&hdr->pad[20], 1u);
+                atomicAdd((unsigned long long*)&hdr->pad[1 + 2 * q], (unsigned long long)tacc[q]);
+            atomicAdd(&hdr->pad[21], 1u);
         }
 #endif
-        if (ticket >= total) return;
-        const int s = ticket / B;
-        const int b = ticket - s * B;
-        const int t0 = s * W;
-        const int tend = min(t0 + W, P);
+        if (e < 0) return;
+        const S2Entry ent = entries[e];
+        const int s = ticket - ent.tstart;
+        const int level = e / B;
+        const int b = e - level * B;
+        const int q = level / R;
+        const int sub = level - q * R;
+        const bool full = ent.g >= 0;
+        const int g = full && s > 0 ? ent.g : 0;   // the first strip has nothing to its left
+        const int j0 = 1 + q * R;
+        const int hq = min(R, ld - j0);
+        const int rlo = full ? 0 : sub;            // rows of the group this task computes
+        const int rhi = full ? hq : sub + 1;
+        const int ilimit = j0 + rlo;               // rows below come from global memory
+        const int weff = WCAP - g;
+        const int t0 = s == 0 ? 0 : WCAP + (s - 1) * weff;   // first stored column
+        const int tS = t0 - g;                     // first computed column
+        const int tend = min(tS + WCAP, P);
         const int tmax = tend - 1;
+        const int tstore_end = min(t0 + weff, P);
         float* Mb = M + (size_t)b * ld * P;
         uint8_t* Kb = STORE_K ? K + (size_t)b * ld * P : nullptr;
-        uint32_t* my_flag = &progress[(size_t)b * NS + s];
+        const S2Rec* brec = recs + ((size_t)b * NQ + q) * ld;
+        const S2Info* binfo = infos + ((size_t)b * NQ + q) * ld;
 
-        // row 0: the base case
+        // ---- the previous level of this instance must be complete
+        if (ent.prev >= 0) {
+            if (tid == 0) {
+                const uint32_t need = (uint32_t)entries[ent.prev].cnt;
+                const uint32_t* flag = &done[ent.prev];
+                const long long start = wall_clock64();
+                int ok = 1;
+                while (ld_relaxed(flag) < need) {
+                    if (ld_relaxed(&hdr->error) != 0) { ok = 0; break; }
+                    if (wall_clock64() - start > wait_limit) {
+                        __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                        ok = 0;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+                sh_word[0] = ok;
+            }
+            __syncthreads();
+            const int ok = __builtin_amdgcn_readfirstlane(sh_word[0]);
+            if (!ok) return;                       // uniform: every thread leaves
+        }
+        TMARK(t_b);
+        TACC(3, t_a, t_b);
+
+        // row 0, the base case, is written by the first level
+        if (q == 0 && rlo == 0) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int t = t0 + tid + NT * u;
-            if (t < P) {
-                Mb[t] = 0.0f;
-                if (STORE_K) Kb[t] = DPC_NOARG;
+            for (int u = 0; u < U; ++u) {
+                const int t = tS + tid + NT * u;
+                if (t >= t0 && t < tstore_end) {
+                    st_agent(Mb + t, 0.0f);
+                    if (STORE_K) st_agent(Kb + t, (uint8_t)DPC_NOARG);
+                }
             }
         }
 
-        for (int r = 0; r < NR; ++r) {
-            const int j0 = 1 + r * R;
-            const int rcur = min(R, ld - j0);
-            const S2Rec* brec = recs + ((size_t)b * NR + r) * ld;
-            const S2Info* binfo = infos + ((size_t)b * NR + r) * ld;
-            float best[R][U];
-            int arg[R][U];
+        float best[R][U];
+        int arg[R][U];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+            for (int u = 0; u < U; ++u) { best[rr][u] = NINF; arg[rr][u] = DPC_NOARG; }
+
+        // a one-row task keeps only row `sub` of a record: its window is that
+        // row's own shift, every other row of the group gets "no candidate"
+        auto fix_one_row = [&](S2Rec& rec, S2Info& inf) {
+            int w = -1;
+            float imp = NINF;
 #pragma unroll
             for (int rr = 0; rr < R; ++rr)
-#pragma unroll
-                for (int u = 0; u < U; ++u) { best[rr][u] = NINF; arg[rr][u] = DPC_NOARG; }
-
-            // stage the windows of rows [i0, i0+CH) into `buf` (asynchronous)
-            auto stage_chunk = [&](float (*buf)[SLOTW], int i0, const S2Info (&inf)[CH]) {
-#pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    const int i = i0 + c;
-                    const int mins = inf[c].mins, maxs = inf[c].maxs;
-                    if (i < j0 && maxs >= 0 && maxs - mins <= DMAX && mins <= tmax) {
-                        const int lo = t0 - maxs;
-                        const int n = tend - mins - lo;
-                        stage_window<NT, SLOTW>(buf[c], Mb + (size_t)i * P, lo, n, P, i == 0, tid,
-                                                wave_base);
-                    }
-                }
-            };
-
-            // relax the block's rows from the rows [i0, i0+CH) held in `buf`
-            auto relax_chunk = [&](const float (*buf)[SLOTW], int i0, const S2Rec (&rec)[CH],
-                                   const S2Info (&inf)[CH]) {
-#pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    const int i = i0 + c;
-                    const int mins = inf[c].mins, maxs = inf[c].maxs;
-                    if (i >= j0 || maxs < 0 || mins > tmax) continue;   // nothing reaches this strip
-                    const int thr = maxs - tmax;       // candidate rr is in reach iff off >= thr
-                    if (maxs - mins <= DMAX) {
-                        // LDS reads run one row of the block ahead of the arithmetic
-                        float mcur[U], mnxt[U];
-                        auto fetch = [&](float (&m)[U], int rr) {
-                            const bool ok = rec[c].off[rr] >= thr;
-                            const int off = ok ? rec[c].off[rr] : 0;
-                            const float* sp = &buf[c][off + tid];
-#pragma unroll
-                            for (int u = 0; u < U; ++u) m[u] = sp[NT * u];
-                        };
-                        fetch(mcur, 0);
-#pragma unroll
-                        for (int rr = 0; rr < R; ++rr) {
-                            if (rr + 1 < R) fetch(mnxt, rr + 1);
-                            const bool ok = rec[c].off[rr] >= thr;
-                            // select on the bit pattern: keeps the choice on the scalar unit
-                            const float imp = __int_as_float(
-                                ok ? __float_as_int(rec[c].imp[rr]) : (int)0xFF800000);
-                            float cand[U];
-                            bool win[U];
-#pragma unroll
-                            for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
-#pragma unroll
-                            for (int u = 0; u < U; ++u) win[u] = cand[u] > best[rr][u];
-#pragma unroll
-                            for (int u = 0; u < U; ++u) {
-                                best[rr][u] = win[u] ? cand[u] : best[rr][u];
-                                arg[rr][u] = win[u] ? i : arg[rr][u];
-                            }
-#pragma unroll
-                            for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
-                        }
-                    } else {
-                        const float* row = Mb + (size_t)i * P;
-#pragma unroll
-                        for (int rr = 0; rr < R; ++rr) {
-                            const int w = maxs - rec[c].off[rr];
-                            if (w > tmax) continue;
-#pragma unroll
-                            for (int u = 0; u < U; ++u) {
-                                const int t = t0 + tid + NT * u;
-                                if (t < P && t >= w) {
-                                    const float m = (i == 0) ? 0.0f : row[t - w];
-                                    const float cand = m + rec[c].imp[rr];
-                                    if (cand > best[rr][u]) { best[rr][u] = cand; arg[rr][u] = i; }
-                                }
-                            }
-                        }
-                    }
-                }
-            };
-
-            // one chunk: fetch its records and the next chunk's window extents (one
-            // batch of scalar loads, in flight across the barrier), start the next
-            // chunk's window copies, relax this chunk
-            S2Info inf_cur[CH], inf_nxt[CH];
-            auto load_infos = [&](S2Info (&inf)[CH], int i0) {
-#pragma unroll
-                for (int c = 0; c < CH; ++c) inf[c] = binfo[min(i0 + c, L)];
-            };
-            auto chunk_step = [&](float (*cur)[SLOTW], float (*nxt)[SLOTW], int i0) {
-                S2Rec rec[CH];
-#pragma unroll
-                for (int c = 0; c < CH; ++c) rec[c] = brec[min(i0 + c, L)];
-                load_infos(inf_nxt, i0 + CH);
-                TMARK(ta);
-                wait_lds_loads();
-                __syncthreads();                       // `cur` filled, `nxt` free
-                TMARK(tb);
-                if (i0 + CH < j0) stage_chunk(nxt, i0 + CH, inf_nxt);
-                TMARK(tc);
-                relax_chunk(cur, i0, rec, inf_cur);
-                TMARK(td);
-                TACC(0, ta, tb);
-                TACC(1, tb, tc);
-                TACC(2, tc, td);
-#pragma unroll
-                for (int c = 0; c < CH; ++c) inf_cur[c] = inf_nxt[c];
-            };
-
-            // ---------------- off-diagonal part: rows i < j0 ----------------
-            // (the barrier that ended the previous block's diagonal part, or the
-            //  ticket barrier, has freed both buffers)
-            load_infos(inf_cur, 0);
-            stage_chunk(bufA, 0, inf_cur);
-            for (int i0 = 0; i0 < j0; i0 += 2 * CH) {
-                chunk_step(bufA, bufB, i0);
-                if (i0 + CH < j0) chunk_step(bufB, bufA, i0 + CH);
-            }
-
-            // ---------------- diagonal part: rows inside the block ----------------
-            // the strips to the left must have finished this block
-            TMARK(te);
-            if (s > 0) {
-                if (tid == 0) {
-                    const uint32_t* flag = &progress[(size_t)b * NS + s - 1];
-                    const long long start = wall_clock64();
-                    int ok = 1;
-                    while (ld_relaxed(flag) < (uint32_t)(r + 1)) {
-                        if (ld_relaxed(&hdr->error) != 0) { ok = 0; break; }
-                        if (wall_clock64() - start > wait_limit) {
-                            __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
-                            ok = 0;
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(4);
-                    }
-                    sh_word = ok;
-                }
-                __syncthreads();
-                const int ok = __builtin_amdgcn_readfirstlane(sh_word);
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-                if (!ok) return;                       // uniform: every thread leaves
-            }
-            __syncthreads();                           // off-diagonal readers done; sh_word free
-            TMARK(tf);
-            TACC(3, te, tf);
-
-            // halo [t0 - hd, t0) of every row of the block that feeds a later row
-            int hd[R];
-#pragma unroll
-            for (int rr = 0; rr < R - 1; ++rr) {
-                hd[rr] = -1;
-                if (rr + 1 < rcur) {
-                    const int j = j0 + rr;
-                    const int mins = binfo[j].mins, maxs = binfo[j].maxs;
-                    if (maxs >= 0 && mins <= tmax) {
-                        hd[rr] = maxs;
-                        if (maxs <= DMAX) {
-                            float* slot = rr < CH ? bufA[rr] : bufB[rr - CH];
-                            stage_window<NT, SLOTW>(slot, Mb + (size_t)j * P, t0 - maxs, maxs, t0,
-                                                    false, tid, wave_base);
-                        }
-                    }
-                }
-            }
-            hd[R - 1] = -1;
-            wait_lds_loads();
-
+                if (rr == sub && rec.imp[rr] != NINF) { w = inf.maxs - rec.off[rr]; imp = rec.imp[rr]; }
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) {
-                const int j = j0 + rr;
-                if (rr < rcur) {
+                rec.off[rr] = 0;
+                rec.imp[rr] = rr == sub ? imp : NINF;
+            }
+            inf.mins = w < 0 ? 0x7FFFFFFF : w;
+            inf.maxs = w;
+        };
+
+        // stage the windows of rows [i0, i0+CH) into `buf` (asynchronous)
+        auto stage_chunk = [&](float (*buf)[SLOTW], int i0, const S2Info (&inf)[CH]) {
+            int issued = 0;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int i = i0 + c;
+                const int mins = inf[c].mins, maxs = inf[c].maxs;
+                if (i < ilimit && maxs >= 0 && mins <= tmax) {
+                    const int lo = tS - maxs;
+                    const int n = tend - mins - lo;
+                    issued += stage_window<NT, SLOTW>(buf[c], Mb + (size_t)i * P, lo, n, P, i == 0,
+                                                      tid, wave_base);
+                }
+            }
+            return issued;
+        };
+
+        // relax the group's rows from the rows [i0, i0+CH) held in `buf`
+        auto relax_chunk = [&](const float (*buf)[SLOTW], int i0, const S2Rec (&rec)[CH],
+                               const S2Info (&inf)[CH]) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int i = i0 + c;
+                const int mins = inf[c].mins, maxs = inf[c].maxs;
+                if (i >= ilimit || maxs < 0 || mins > tmax) continue;   // nothing reaches the task
+                const int thr = maxs - tmax;           // candidate rr is in reach iff off >= thr
+                // LDS reads run one row of the group ahead of the arithmetic
+                float mcur[U], mnxt[U];
+                auto fetch = [&](float (&m)[U], int rr) {
+                    const bool ok = rec[c].off[rr] >= thr;
+                    const int off = ok ? rec[c].off[rr] : 0;
+                    const float* sp = &buf[c][off + tid];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) m[u] = sp[NT * u];
+                };
+                fetch(mcur, 0);
+#pragma unroll
+                for (int rr = 0; rr < R; ++rr) {
+                    if (rr + 1 < R) fetch(mnxt, rr + 1);
+                    const bool ok = rec[c].off[rr] >= thr;
+                    // select on the bit pattern: keeps the choice on the scalar unit
+                    const float imp =
+                        __int_as_float(ok ? __float_as_int(rec[c].imp[rr]) : (int)0xFF800000);
+                    float cand[U];
+                    bool win[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) win[u] = cand[u] > best[rr][u];
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const int t = t0 + tid + NT * u;
-                        if (t < P) {
-                            Mb[(size_t)j * P + t] = best[rr][u];
-                            if (STORE_K) Kb[(size_t)j * P + t] = (uint8_t)arg[rr][u];
-                        }
+                        best[rr][u] = win[u] ? cand[u] : best[rr][u];
+                        arg[rr][u] = win[u] ? i : arg[rr][u];
                     }
-                    if (rr < R - 1 && hd[rr] >= 0 && hd[rr] <= DMAX) {
-                        float* slot = rr < CH ? bufA[rr] : bufB[rr - CH];
 #pragma unroll
-                        for (int u = 0; u < U; ++u) slot[hd[rr] + tid + NT * u] = best[rr][u];
+                    for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
+                }
+            }
+        };
+
+        // One chunk step: fetch the chunk's records and the window extents of the
+        // chunk two ahead (one batch of scalar loads, in flight across the
+        // barrier), wait for this chunk's window copies (the copies of the next
+        // chunk, `later` instructions, may stay in flight), start the copies of
+        // the chunk two ahead into the buffer that was relaxed last, relax.
+        auto load_infos = [&](S2Info (&inf)[CH], int i0) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) inf[c] = binfo[min(i0 + c, L)];
+            if (!full) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    S2Rec tmp = brec[min(i0 + c, L)];
+                    fix_one_row(tmp, inf[c]);
+                }
+            }
+        };
+        int later = 0;         // copies in flight for the chunk after the current one
+        auto chunk_step = [&](float (*cur)[SLOTW], float (*free2)[SLOTW], int i0) {
+            S2Rec rec[CH];
+            S2Info inf[CH], inf2[CH];
+#pragma unroll
+            for (int c = 0; c < CH; ++c) rec[c] = brec[min(i0 + c, L)];
+#pragma unroll
+            for (int c = 0; c < CH; ++c) inf[c] = binfo[min(i0 + c, L)];
+            if (!full) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c) fix_one_row(rec[c], inf[c]);
+            }
+            load_infos(inf2, i0 + 2 * CH);
+            TMARK(ta);
+            wait_vm(later);
+            lds_barrier();                             // `cur` filled, `free2` no longer read
+            TMARK(tb);
+            later = 0;
+            int fresh = 0;
+            if (i0 + 2 * CH < ilimit) fresh = stage_chunk(free2, i0 + 2 * CH, inf2);
+            TMARK(tc);
+            relax_chunk(cur, i0, rec, inf);
+            TMARK(td);
+            TACC(0, ta, tb);
+            TACC(1, tb, tc);
+            TACC(2, tc, td);
+            return fresh;
+        };
+
+        // ---------------- off-diagonal part: rows i < ilimit ----------------
+        // (the barrier that ended the previous task has freed all buffers)
+        {
+            S2Info inf0[CH];
+            load_infos(inf0, 0);
+            stage_chunk(bufA, 0, inf0);
+            if (CH < ilimit) {
+                load_infos(inf0, CH);
+                later = stage_chunk(bufB, CH, inf0);
+            }
+        }
+        for (int i0 = 0; i0 < ilimit; i0 += 3 * CH) {
+            // `later` = copies issued for the chunk after the one being waited for
+            int f = chunk_step(bufA, bufC, i0);
+            later = f;
+            if (i0 + CH < ilimit) { f = chunk_step(bufB, bufA, i0 + CH); later = f; }
+            if (i0 + 2 * CH < ilimit) { f = chunk_step(bufC, bufB, i0 + 2 * CH); later = f; }
+        }
+        TMARK(t_c);
+        __syncthreads();                               // off-diagonal readers done
+        if (full && tS == 0) {
+            // first strip: what lies to the left of column 0 does not exist
+            for (int x = tid; x < (R - 1) * DMAX; x += NT) {
+                const int rr = x / DMAX;
+                float* slot = rr < CH ? bufA[rr] : bufB[rr - CH];
+                slot[x - rr * DMAX] = NINF;
+            }
+        }
+
+        // ---------------- diagonal part and output ----------------
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            const int j = j0 + rr;
+            if (rr >= rlo && rr < rhi) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int t = tS + tid + NT * u;
+                    if (t >= t0 && t < tstore_end) {
+                        st_agent(Mb + (size_t)j * P + t, best[rr][u]);
+                        if (STORE_K) st_agent(Kb + (size_t)j * P + t, (uint8_t)arg[rr][u]);
                     }
                 }
-                if (rr + 1 < R) {
-                    __syncthreads();                   // row j visible: LDS slot and global
-                    if (hd[rr] >= 0) {
-                        const S2Rec rec = brec[j];
-                        const bool in_lds = hd[rr] <= DMAX;
-                        const float* slot = rr < CH ? bufA[rr] : bufB[rr - CH];
-                        const float* row = Mb + (size_t)j * P;
+            }
+            if (rr + 1 < R) {
+                // row j of a whole-group task feeds the rows below it through an LDS
+                // slot: own column t at slot position DMAX + (t - tS)
+                const bool feeds = full && rr + 1 < rhi;
+                float* slot = rr < CH ? bufA[rr] : bufB[rr - CH];
+                if (feeds) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) slot[DMAX + tid + NT * u] = best[rr][u];
+                }
+                __syncthreads();
+                if (feeds) {
+                    const S2Rec rec = brec[j];
+                    const int maxs = binfo[j].maxs;
+                    if (maxs >= 0) {
 #pragma unroll
                         for (int r2 = rr + 1; r2 < R; ++r2) {
-                            const int w = hd[rr] - rec.off[r2];
-                            const float imp = rec.imp[r2];
-                            if (w > tmax) continue;
-                            if (in_lds) {
-                                const float* sp = &slot[rec.off[r2] + tid];
+                            const int w = maxs - rec.off[r2];
+                            const bool ok = w <= tmax;
+                            const float imp = __int_as_float(
+                                ok ? __float_as_int(rec.imp[r2]) : (int)0xFF800000);
+                            const float* sp = &slot[(ok ? DMAX - w : 0) + tid];
 #pragma unroll
-                                for (int u = 0; u < U; ++u) {
-                                    const float cand = sp[NT * u] + imp;
-                                    if (cand > best[r2][u]) { best[r2][u] = cand; arg[r2][u] = j; }
-                                }
-                            } else {
-#pragma unroll
-                                for (int u = 0; u < U; ++u) {
-                                    const int t = t0 + tid + NT * u;
-                                    if (t < P && t >= w) {
-                                        const float cand = row[t - w] + imp;
-                                        if (cand > best[r2][u]) { best[r2][u] = cand; arg[r2][u] = j; }
-                                    }
-                                }
+                            for (int u = 0; u < U; ++u) {
+                                const float cand = sp[NT * u] + imp;
+                                if (cand > best[r2][u]) { best[r2][u] = cand; arg[r2][u] = j; }
                             }
                         }
                     }
                 }
             }
-
-            // publish: this strip has finished block r
-            TMARK(tg);
-            TACC(4, tf, tg);
-            if (s + 1 < NS) {
-                __threadfence();
-                __syncthreads();
-                if (tid == 0)
-                    __hip_atomic_store(my_flag, (uint32_t)(r + 1), __ATOMIC_RELEASE,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-                __syncthreads();                       // both buffers free for the next block
-            }
-            TMARK(th);
-            TACC(5, tg, th);
         }
+        TMARK(t_d);
+        TACC(4, t_c, t_d);
+
+        // ---- publish: one more task of this entry is complete
+        wait_vm(0);                                    // this wave's stores are acknowledged
+        __syncthreads();                               // ... every wave's; also frees the buffers
+        if (tid == 0)
+            __hip_atomic_fetch_add(&done[e], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        TMARK(t_e);
+        TACC(5, t_d, t_e);
     }
 }
 
@@ -509,39 +721,46 @@ template <int NT, int U, int CH, int DMAX, int WPE>
 static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                              uint8_t* K, void* workspace, int num_cu, hipStream_t st)
 {
-    constexpr int W = NT * U;
-    const int NS = (P + W - 1) / W;
-    const int NR = (L + S2_R - 1) / S2_R;
-    const long long total = (long long)B * NS;
-    if (total > 0x7FFFFFF0LL) return hipErrorInvalidValue;
+    constexpr int WCAP = NT * U;
+    const int NQ = (L + S2_R - 1) / S2_R;
     const S2Layout lay = s2_layout(B, L, P);
+    if (lay.nentries > 0x3FFFFFF0LL) return hipErrorInvalidValue;
+    const int N = (int)lay.nentries;
     char* base = (char*)workspace;
     S2Header* hdr = (S2Header*)base;
-    uint32_t* progress = (uint32_t*)(base + lay.progress_off);
+    uint32_t* done = (uint32_t*)(base + lay.done_off);
+    S2Entry* entries = (S2Entry*)(base + lay.entry_off);
+    int32_t* groups = (int32_t*)(base + lay.group_off);
     S2Rec* recs = (S2Rec*)(base + lay.rec_off);
     S2Info* infos = (S2Info*)(base + lay.info_off);
 
-    const int nwords = (int)(sizeof(S2Header) / 4) + B * NS;
-    hipError_t e = launch_clear_words(workspace, nwords, st);
+    hipError_t e = launch_clear_words(workspace, (int)(sizeof(S2Header) / 4) + N, st);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(stage2_pack_kernel, dim3((L + 1 + 255) / 256, NR, B), dim3(256), 0, st, L, P,
-                       NR, Topt, I, recs, infos);
+    // ghost columns cost recomputation: at most a quarter of a task, and the
+    // chain of shifts must fit the pad in front of a diagonal slot
+    const int gmax = std::min(DMAX, WCAP / 4);
+    hipLaunchKernelGGL(stage2_pack_kernel, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I, recs,
+                       infos, groups, gmax, DMAX, WCAP);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(stage2_layout_kernel, dim3(1), dim3(1024), 0, st, B, L, P, NQ, WCAP, groups,
+                       entries, hdr);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
 
     // resident workgroups per compute unit: WPE waves per SIMD, 4 SIMDs
     constexpr int wg_per_cu = (WPE * 4 * 64) / NT;
     static_assert(wg_per_cu >= 1, "a workgroup must fit one compute unit");
-    const int grid = (int)std::min<long long>(total, (long long)num_cu * wg_per_cu);
+    const int grid = num_cu * wg_per_cu;
     const long long wait_limit = 500000000LL;      // 5 s of the 100 MHz wall clock
     if (K)
         hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, true>), dim3(grid), dim3(NT),
-                           0, st, B, L, P, M, K, hdr, progress, recs, infos, NS, (int)total,
+                           0, st, B, L, P, M, K, hdr, done, entries, recs, infos, NQ, N,
                            wait_limit);
     else
         hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, false>), dim3(grid),
-                           dim3(NT), 0, st, B, L, P, M, K, hdr, progress, recs, infos, NS,
-                           (int)total, wait_limit);
+                           dim3(NT), 0, st, B, L, P, M, K, hdr, done, entries, recs, infos, NQ, N,
+                           wait_limit);
     return hipGetLastError();
 }
 
@@ -550,10 +769,8 @@ int g_s2_shape = 0;     // tuning override, see launch_stage2_tiled
 hipError_t launch_stage2_tiled(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                                uint8_t* K, void* workspace, int num_cu, hipStream_t st)
 {
-    // strip width W = NT*U.  Narrow tables take the narrowest strip that covers
-    // them; wide ones take the strip that gives about one workgroup-sized task
-    // per resident slot, so that the strips of an instance run as one shallow
-    // pipeline.
+    // WCAP = NT*U columns per task.  Narrow tables take the narrowest shape that
+    // covers them.
     int shape = g_s2_shape;
     if (shape == 0) {
         if (P <= 256) shape = 1;
@@ -563,7 +780,7 @@ hipError_t launch_stage2_tiled(int B, int L, int P, const int32_t* Topt, const f
     switch (shape) {
         case 1: return launch_cfg<256, 1, 4, 240, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         case 2: return launch_cfg<256, 2, 4, 240, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 3: return launch_cfg<256, 4, 4, 256, 3>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 3: return launch_cfg<256, 4, 4, 256, 2>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         case 4: return launch_cfg<512, 2, 4, 256, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         case 5: return launch_cfg<1024, 2, 4, 256, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         default: return hipErrorInvalidValue;
