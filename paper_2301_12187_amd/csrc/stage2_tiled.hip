@@ -319,46 +319,47 @@ __device__ __forceinline__ void wait_vm(int later)
     }
 }
 
-// Copy the window tp in [lo, lo + n) of a row of M into slot[0..n): -inf for
-// tp < 0, nothing for tp >= tlimit.  The window is cut into 16-byte groups, one
-// per lane and pass.  A group inside [0, tlimit) goes global -> LDS without
-// passing registers (the lanes of a wave fill consecutive 16-byte cells from a
-// wave-uniform LDS base); a group entirely below 0 is one 16-byte store of
-// -inf; the at most two groups that straddle 0 or tlimit are written element
-// by element.  `row0`: the row is the base case M[0][t] = +0, not read from
-// memory.
-template <int NT, int SLOTW>
+// Copy the part x in [x0, x0 + 256*NGK) of the window tp in [lo, lo + n) of a
+// row of M into slot[0..n): -inf for tp < 0, nothing for tp >= tlimit.  Run by
+// one wave; the window is cut into 16-byte groups, one per lane and pass.  A
+// group inside [0, tlimit) goes global -> LDS without passing registers (the
+// lanes fill consecutive 16-byte cells from a wave-uniform LDS base); a group
+// entirely below 0 is one 16-byte store of -inf; the at most two groups that
+// straddle 0 or tlimit are written element by element.  `row0`: the row is the
+// base case M[0][t] = +0, not read from memory.  Returns the number of
+// global -> LDS loads issued with at least one lane.
+template <int NGK>
 __device__ __forceinline__ int stage_window(float* slot, const float* row, int lo, int n,
-                                            int tlimit, bool row0, int tid, int wave_base)
+                                            int tlimit, bool row0, int x0, int lane)
 {
-    constexpr int NGK = (SLOTW / 4 + NT - 1) / NT;
     constexpr float NINF = -INFINITY;
-    int issued = 0;      // global -> LDS loads this wave issued with at least one lane
+    int issued = 0;
     if (!row0 && lo >= 0 && lo + ((n + 3) & ~3) <= tlimit) {
         // the common case: every group is inside the row
 #pragma unroll
         for (int k = 0; k < NGK; ++k) {
-            const int x = 4 * (tid + NT * k);
-            const bool go = x < n;
-            if (__ballot(go) != 0) ++issued;
-            if (go)
-                __builtin_amdgcn_global_load_lds(row + lo + x,
-                                                 (lds_void*)(slot + 4 * (wave_base + NT * k)), 16,
-                                                 0, DMA_AGENT_SCOPE);
+            const int xb = x0 + 256 * k;           // wave-uniform
+            const int x = xb + 4 * lane;
+            if (xb < n) {
+                ++issued;
+                if (x < n)
+                    __builtin_amdgcn_global_load_lds(row + lo + x, (lds_void*)(slot + xb), 16, 0,
+                                                     DMA_AGENT_SCOPE);
+            }
         }
         return issued;
     }
 #pragma unroll
     for (int k = 0; k < NGK; ++k) {
-        const int x = 4 * (tid + NT * k);
+        const int xb = x0 + 256 * k;
+        const int x = xb + 4 * lane;
         const int tp = lo + x;
         const bool go = x < n && !row0 && tp >= 0 && tp + 3 < tlimit;
         if (__ballot(go) != 0) ++issued;
         if (x < n) {
             if (go) {
-                __builtin_amdgcn_global_load_lds(row + tp,
-                                                 (lds_void*)(slot + 4 * (wave_base + NT * k)), 16,
-                                                 0, DMA_AGENT_SCOPE);
+                __builtin_amdgcn_global_load_lds(row + tp, (lds_void*)(slot + xb), 16, 0,
+                                                 DMA_AGENT_SCOPE);
             } else if (tp + 3 < 0) {
                 *(float4*)(slot + x) = make_float4(NINF, NINF, NINF, NINF);
             } else if (row0 && tp >= 0) {
@@ -396,8 +397,18 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
     __shared__ int sh_word[2];
 
     const int tid = threadIdx.x;
-    const int wave_base = __builtin_amdgcn_readfirstlane(tid & ~63);
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ld = L + 1;
+    // columns: a wave owns U*64 consecutive columns, lane + 64*u inside them
+    const int tl0 = wave * (64 * U) + lane;
+    // window copies: WPR waves share a row of a chunk, each a run of 16-byte groups
+    constexpr int NW = NT / 64;
+    static_assert(NW % CH == 0, "waves must divide evenly over the rows of a chunk");
+    constexpr int WPR = NW / CH;
+    constexpr int NGK = (SLOTW / 4 + WPR * 64 - 1) / (WPR * 64);   // passes per wave
+    const int st_row = wave / WPR;                  // row of the chunk this wave copies
+    const int st_x0 = (wave - st_row * WPR) * (256 * NGK);
 
 #ifdef DPC_S2_TIMERS
     long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -493,7 +504,7 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
         if (q == 0 && rlo == 0) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int t = tS + tid + NT * u;
+                const int t = tS + tl0 + 64 * u;
                 if (t >= t0 && t < tstore_end) {
                     st_agent(Mb + t, 0.0f);
                     if (STORE_K) st_agent(Kb + t, (uint8_t)DPC_NOARG);
@@ -525,21 +536,25 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
             inf.maxs = w;
         };
 
-        // stage the windows of rows [i0, i0+CH) into `buf` (asynchronous)
-        auto stage_chunk = [&](float (*buf)[SLOTW], int i0, const S2Info (&inf)[CH]) {
-            int issued = 0;
-#pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                const int i = i0 + c;
-                const int mins = inf[c].mins, maxs = inf[c].maxs;
-                if (i < ilimit && maxs >= 0 && mins <= tmax) {
-                    const int lo = tS - maxs;
-                    const int n = tend - mins - lo;
-                    issued += stage_window<NT, SLOTW>(buf[c], Mb + (size_t)i * P, lo, n, P, i == 0,
-                                                      tid, wave_base);
-                }
+        // a wave whose columns all lie beyond the table has nothing to relax
+        const bool wave_idle = tS + wave * (64 * U) >= tend;
+
+        // start the copy of this wave's part of the window of row i0 + st_row
+        // into `buf` (asynchronous); returns the number of loads issued
+        auto stage_chunk = [&](float (*buf)[SLOTW], int i0) {
+            const int i = i0 + st_row;
+            if (i >= ilimit) return 0;
+            S2Info inf = binfo[i];
+            if (!full) {
+                S2Rec tmp = brec[i];
+                fix_one_row(tmp, inf);
             }
-            return issued;
+            if (inf.maxs < 0 || inf.mins > tmax) return 0;
+            const int lo = tS - inf.maxs;
+            const int n = tend - inf.mins - lo;
+            if (st_x0 >= n) return 0;
+            return stage_window<NGK>(buf[st_row], Mb + (size_t)i * P, lo, n, P, i == 0, st_x0,
+                                     lane);
         };
 
         // relax the group's rows from the rows [i0, i0+CH) held in `buf`
@@ -551,78 +566,77 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
                 const int mins = inf[c].mins, maxs = inf[c].maxs;
                 if (i >= ilimit || maxs < 0 || mins > tmax) continue;   // nothing reaches the task
                 const int thr = maxs - tmax;           // candidate rr is in reach iff off >= thr
+                const float* base = &buf[c][tl0];
                 // LDS reads run one row of the group ahead of the arithmetic
                 float mcur[U], mnxt[U];
-                auto fetch = [&](float (&m)[U], int rr) {
-                    const bool ok = rec[c].off[rr] >= thr;
-                    const int off = ok ? rec[c].off[rr] : 0;
-                    const float* sp = &buf[c][off + tid];
+                if (thr <= 0) {
+                    // every candidate of the row is in reach of every column
 #pragma unroll
-                    for (int u = 0; u < U; ++u) m[u] = sp[NT * u];
-                };
-                fetch(mcur, 0);
+                    for (int u = 0; u < U; ++u) mcur[u] = base[rec[c].off[0] + 64 * u];
 #pragma unroll
-                for (int rr = 0; rr < R; ++rr) {
-                    if (rr + 1 < R) fetch(mnxt, rr + 1);
-                    const bool ok = rec[c].off[rr] >= thr;
-                    // select on the bit pattern: keeps the choice on the scalar unit
-                    const float imp =
-                        __int_as_float(ok ? __float_as_int(rec[c].imp[rr]) : (int)0xFF800000);
-                    float cand[U];
-                    bool win[U];
+                    for (int rr = 0; rr < R; ++rr) {
+                        if (rr + 1 < R) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
+                            for (int u = 0; u < U; ++u) mnxt[u] = base[rec[c].off[rr + 1] + 64 * u];
+                        }
+                        const float imp = rec[c].imp[rr];
+                        float cand[U];
+                        bool win[U];
 #pragma unroll
-                    for (int u = 0; u < U; ++u) win[u] = cand[u] > best[rr][u];
+                        for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        best[rr][u] = win[u] ? cand[u] : best[rr][u];
-                        arg[rr][u] = win[u] ? i : arg[rr][u];
+                        for (int u = 0; u < U; ++u) win[u] = cand[u] > best[rr][u];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            best[rr][u] = win[u] ? cand[u] : best[rr][u];
+                            arg[rr][u] = win[u] ? i : arg[rr][u];
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
                     }
+                } else {
+                    // first strips: some shifts reach below column 0 of the table
 #pragma unroll
-                    for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
+                    for (int rr = 0; rr < R; ++rr) {
+                        const bool ok = rec[c].off[rr] >= thr;
+                        const int off = ok ? rec[c].off[rr] : 0;
+                        const float imp = ok ? rec[c].imp[rr] : NINF;
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const float cand = base[off + 64 * u] + imp;
+                            if (cand > best[rr][u]) { best[rr][u] = cand; arg[rr][u] = i; }
+                        }
+                    }
                 }
             }
         };
 
-        // One chunk step: fetch the chunk's records and the window extents of the
-        // chunk two ahead (one batch of scalar loads, in flight across the
-        // barrier), wait for this chunk's window copies (the copies of the next
-        // chunk, `later` instructions, may stay in flight), start the copies of
-        // the chunk two ahead into the buffer that was relaxed last, relax.
-        auto load_infos = [&](S2Info (&inf)[CH], int i0) {
-#pragma unroll
-            for (int c = 0; c < CH; ++c) inf[c] = binfo[min(i0 + c, L)];
-            if (!full) {
-#pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    S2Rec tmp = brec[min(i0 + c, L)];
-                    fix_one_row(tmp, inf[c]);
-                }
-            }
-        };
+        // One chunk step: fetch the chunk's records (one batch of scalar loads,
+        // in flight across the barrier), wait for this chunk's window copies
+        // (the copies of the next chunk, `later` instructions, may stay in
+        // flight), start the copies of the chunk two ahead into the buffer that
+        // was relaxed last, relax.
         int later = 0;         // copies in flight for the chunk after the current one
         auto chunk_step = [&](float (*cur)[SLOTW], float (*free2)[SLOTW], int i0) {
             S2Rec rec[CH];
-            S2Info inf[CH], inf2[CH];
+            S2Info inf[CH];
+            if (!wave_idle) {
 #pragma unroll
-            for (int c = 0; c < CH; ++c) rec[c] = brec[min(i0 + c, L)];
+                for (int c = 0; c < CH; ++c) rec[c] = brec[min(i0 + c, L)];
 #pragma unroll
-            for (int c = 0; c < CH; ++c) inf[c] = binfo[min(i0 + c, L)];
-            if (!full) {
+                for (int c = 0; c < CH; ++c) inf[c] = binfo[min(i0 + c, L)];
+                if (!full) {
 #pragma unroll
-                for (int c = 0; c < CH; ++c) fix_one_row(rec[c], inf[c]);
+                    for (int c = 0; c < CH; ++c) fix_one_row(rec[c], inf[c]);
+                }
             }
-            load_infos(inf2, i0 + 2 * CH);
             TMARK(ta);
             wait_vm(later);
             lds_barrier();                             // `cur` filled, `free2` no longer read
             TMARK(tb);
-            later = 0;
-            int fresh = 0;
-            if (i0 + 2 * CH < ilimit) fresh = stage_chunk(free2, i0 + 2 * CH, inf2);
+            const int fresh = stage_chunk(free2, i0 + 2 * CH);
             TMARK(tc);
-            relax_chunk(cur, i0, rec, inf);
+            if (!wave_idle) relax_chunk(cur, i0, rec, inf);
             TMARK(td);
             TACC(0, ta, tb);
             TACC(1, tb, tc);
@@ -632,21 +646,12 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
 
         // ---------------- off-diagonal part: rows i < ilimit ----------------
         // (the barrier that ended the previous task has freed all buffers)
-        {
-            S2Info inf0[CH];
-            load_infos(inf0, 0);
-            stage_chunk(bufA, 0, inf0);
-            if (CH < ilimit) {
-                load_infos(inf0, CH);
-                later = stage_chunk(bufB, CH, inf0);
-            }
-        }
+        stage_chunk(bufA, 0);
+        later = stage_chunk(bufB, CH);
         for (int i0 = 0; i0 < ilimit; i0 += 3 * CH) {
-            // `later` = copies issued for the chunk after the one being waited for
-            int f = chunk_step(bufA, bufC, i0);
-            later = f;
-            if (i0 + CH < ilimit) { f = chunk_step(bufB, bufA, i0 + CH); later = f; }
-            if (i0 + 2 * CH < ilimit) { f = chunk_step(bufC, bufB, i0 + 2 * CH); later = f; }
+            later = chunk_step(bufA, bufC, i0);
+            if (i0 + CH < ilimit) later = chunk_step(bufB, bufA, i0 + CH);
+            if (i0 + 2 * CH < ilimit) later = chunk_step(bufC, bufB, i0 + 2 * CH);
         }
         TMARK(t_c);
         __syncthreads();                               // off-diagonal readers done
@@ -666,7 +671,7 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
             if (rr >= rlo && rr < rhi) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const int t = tS + tid + NT * u;
+                    const int t = tS + tl0 + 64 * u;
                     if (t >= t0 && t < tstore_end) {
                         st_agent(Mb + (size_t)j * P + t, best[rr][u]);
                         if (STORE_K) st_agent(Kb + (size_t)j * P + t, (uint8_t)arg[rr][u]);
@@ -680,10 +685,10 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
                 float* slot = rr < CH ? bufA[rr] : bufB[rr - CH];
                 if (feeds) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u) slot[DMAX + tid + NT * u] = best[rr][u];
+                    for (int u = 0; u < U; ++u) slot[DMAX + tl0 + 64 * u] = best[rr][u];
                 }
                 __syncthreads();
-                if (feeds) {
+                if (feeds && !wave_idle) {
                     const S2Rec rec = brec[j];
                     const int maxs = binfo[j].maxs;
                     if (maxs >= 0) {
@@ -693,10 +698,10 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
                             const bool ok = w <= tmax;
                             const float imp = __int_as_float(
                                 ok ? __float_as_int(rec.imp[r2]) : (int)0xFF800000);
-                            const float* sp = &slot[(ok ? DMAX - w : 0) + tid];
+                            const float* sp = &slot[(ok ? DMAX - w : 0) + tl0];
 #pragma unroll
                             for (int u = 0; u < U; ++u) {
-                                const float cand = sp[NT * u] + imp;
+                                const float cand = sp[64 * u] + imp;
                                 if (cand > best[r2][u]) { best[r2][u] = cand; arg[r2][u] = j; }
                             }
                         }
