@@ -565,48 +565,35 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
                 const int i = i0 + c;
                 const int mins = inf[c].mins, maxs = inf[c].maxs;
                 if (i >= ilimit || maxs < 0 || mins > tmax) continue;   // nothing reaches the task
-                const int thr = maxs - tmax;           // candidate rr is in reach iff off >= thr
+                // A candidate whose shift exceeds every column of the task reads
+                // the part of the window that lies below column 0, which was
+                // filled with -inf; a missing candidate adds -inf: neither needs
+                // a test here.
                 const float* base = &buf[c][tl0];
                 // LDS reads run one row of the group ahead of the arithmetic
                 float mcur[U], mnxt[U];
-                if (thr <= 0) {
-                    // every candidate of the row is in reach of every column
 #pragma unroll
-                    for (int u = 0; u < U; ++u) mcur[u] = base[rec[c].off[0] + 64 * u];
+                for (int u = 0; u < U; ++u) mcur[u] = base[rec[c].off[0] + 64 * u];
 #pragma unroll
-                    for (int rr = 0; rr < R; ++rr) {
-                        if (rr + 1 < R) {
+                for (int rr = 0; rr < R; ++rr) {
+                    if (rr + 1 < R) {
 #pragma unroll
-                            for (int u = 0; u < U; ++u) mnxt[u] = base[rec[c].off[rr + 1] + 64 * u];
-                        }
-                        const float imp = rec[c].imp[rr];
-                        float cand[U];
-                        bool win[U];
-#pragma unroll
-                        for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
-#pragma unroll
-                        for (int u = 0; u < U; ++u) win[u] = cand[u] > best[rr][u];
-#pragma unroll
-                        for (int u = 0; u < U; ++u) {
-                            best[rr][u] = win[u] ? cand[u] : best[rr][u];
-                            arg[rr][u] = win[u] ? i : arg[rr][u];
-                        }
-#pragma unroll
-                        for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
+                        for (int u = 0; u < U; ++u) mnxt[u] = base[rec[c].off[rr + 1] + 64 * u];
                     }
-                } else {
-                    // first strips: some shifts reach below column 0 of the table
+                    const float imp = rec[c].imp[rr];
+                    float cand[U];
+                    bool win[U];
 #pragma unroll
-                    for (int rr = 0; rr < R; ++rr) {
-                        const bool ok = rec[c].off[rr] >= thr;
-                        const int off = ok ? rec[c].off[rr] : 0;
-                        const float imp = ok ? rec[c].imp[rr] : NINF;
+                    for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
 #pragma unroll
-                        for (int u = 0; u < U; ++u) {
-                            const float cand = base[off + 64 * u] + imp;
-                            if (cand > best[rr][u]) { best[rr][u] = cand; arg[rr][u] = i; }
-                        }
+                    for (int u = 0; u < U; ++u) win[u] = cand[u] > best[rr][u];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        best[rr][u] = win[u] ? cand[u] : best[rr][u];
+                        arg[rr][u] = win[u] ? i : arg[rr][u];
                     }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
                 }
             }
         };
