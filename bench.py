@@ -34,9 +34,10 @@ if ROOT not in sys.path:
 
 METRIC = "DP relax-ops/sec (B·L²·P) + batch solve latency ms, 1×MI355X"
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9        # 39.3e12
-# HBM bytes per stage-2 launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), keyed by (config, variant actually run); None until measured.
-MEASURED_TRAFFIC = {}
+# HBM bytes (read + written) per stage-2 launch from the rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs summarised in profiles/stage2_tiled_kernel_cfg5.md, keyed by
+# (config, variant); None where not measured.
+MEASURED_TRAFFIC = {(5, 0): 10.58e9 + 1.197e9}
 
 
 def main():
@@ -49,6 +50,9 @@ def main():
     ap.add_argument("--no-K", action="store_true", help="do not store back-pointers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy (reference point for the "
+                         "FETCH_SIZE / WRITE_SIZE counters), print its size and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the instances shard trivially over "
@@ -58,6 +62,17 @@ def main():
     import numpy as np
     import torch
     from paper_2301_12187_amd import api, inputs
+
+    if args.copy_calibration:
+        n = 1 << 28                                   # 2^28 floats = 1 GiB read + 1 GiB written
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 4 * n, "copy_calibration_bytes_written": 4 * n,
+                          "launches": 3}))
+        return
 
     cfg = inputs.CONFIGS[args.config]
     dev = torch.device("cuda:0")
@@ -143,7 +158,7 @@ def main():
         nb = min(cfg.B, cores)
         # about 10-30 s of CPU work: whole instances, one per thread
         per_inst = inputs.relax_ops_exact(1, cfg.L, cfg.P)
-        while nb * per_inst < 4e9 and nb < cfg.B and nb < 8 * cores:
+        while nb * per_inst < 2e10 and nb < cfg.B:
             nb += cores
         nb = min(nb, cfg.B)
         sel = qi < nb
