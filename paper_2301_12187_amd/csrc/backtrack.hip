@@ -2,10 +2,10 @@
 // the paper) rebuilt from the stored arg-max pointers K and, inside every
 // block (i, j) of the chain, the arg-min pointers of Algorithm 1.  One lane per
 // query; at most L pointer steps plus at most L split steps, all integer.
-// The walk visits indices from high to low, so it first counts the two set
-// sizes and then walks again writing each member at its final ascending slot.
-// Members strictly decrease along the walk (i < m < l <= j is enforced), so
-// both sets hold at most L-1 entries whatever the tables contain.
+// The walk visits indices from high to low; the members are written in that
+// order and each list is then reversed in place.  Members strictly decrease
+// along the walk (i < m < l <= j is enforced), so both sets hold at most L-1
+// entries whatever the tables contain.
 #include "dpc_internal.h"
 
 namespace dpc {
@@ -31,7 +31,7 @@ __global__ __launch_bounds__(64) void backtrack_kernel(
     int B, int L, int P, const int32_t* __restrict__ Topt, const uint8_t* __restrict__ split,
     const float* __restrict__ I, const float* __restrict__ M, const uint8_t* __restrict__ K,
     int Q, const int32_t* __restrict__ q_inst, const int32_t* __restrict__ q_T0,
-    int32_t* __restrict__ A, int32_t* __restrict__ A_len, int32_t* __restrict__ S,
+    int32_t* A, int32_t* __restrict__ A_len, int32_t* S,
     int32_t* __restrict__ S_len, float* __restrict__ obj, int32_t* __restrict__ lat,
     int32_t* __restrict__ status)
 {
@@ -61,49 +61,37 @@ __global__ __launch_bounds__(64) void backtrack_kernel(
         A_len[q] = -1; S_len[q] = -1; obj[q] = -INFINITY; lat[q] = -1; status[q] = st;
         return;
     }
-    // pass 1: sizes and latency
+    // one walk: members come out from high to low and are written in that order,
+    // then each list is reversed in place by the same lane
     int na = 0, ns = 0, total = 0;
+    int32_t* Aq = A + (size_t)q * L;
+    int32_t* Sq = S + (size_t)q * L;
     {
         int j = L, t = T0;
         while (j > 0) {
             const int i = argmax_of_cell(L, P, To, Ib, Mb, Kb, j, t);
-            if (i >= j) break;          // defensive: never true for stage-2 output
+            if (i >= j) break;              // defensive: never true for stage-2 output
             int l = j;
             for (;;) {
                 const int m = Sp[i * ld + l];
                 if (m <= i || m >= l) break;   // m == i ends S_opt[i,j]; the rest is defensive
-                ++ns; l = m;
+                Sq[ns++] = m;
+                l = m;
             }
-            if (i > 0) { ++na; ++ns; }
+            if (i > 0) {
+                Aq[na++] = i;
+                Sq[ns++] = i;
+            }
             const int32_t w = To[i * ld + j];
             if (w > t) break;               // defensive: never true for stage-2 output
             total += w; t -= w; j = i;
         }
     }
-    // pass 2: same walk, members written from the back
-    {
-        int32_t* Aq = A + (size_t)q * L;
-        int32_t* Sq = S + (size_t)q * L;
-        int pa = na, ps = ns;
-        int j = L, t = T0;
-        while (j > 0) {
-            const int i = argmax_of_cell(L, P, To, Ib, Mb, Kb, j, t);
-            if (i >= j) break;
-            int l = j;
-            for (;;) {
-                const int m = Sp[i * ld + l];
-                if (m <= i || m >= l) break;
-                Sq[--ps] = m;
-                l = m;
-            }
-            if (i > 0) {
-                Aq[--pa] = i;
-                Sq[--ps] = i;
-            }
-            const int32_t w = To[i * ld + j];
-            if (w > t) break;
-            t -= w; j = i;
-        }
+    for (int a = 0, b2 = na - 1; a < b2; ++a, --b2) {
+        const int32_t x = Aq[a]; Aq[a] = Aq[b2]; Aq[b2] = x;
+    }
+    for (int a = 0, b2 = ns - 1; a < b2; ++a, --b2) {
+        const int32_t x = Sq[a]; Sq[a] = Sq[b2]; Sq[b2] = x;
     }
     A_len[q] = na; S_len[q] = ns; obj[q] = top; lat[q] = total; status[q] = DPC_Q_OK;
 }

@@ -17,6 +17,7 @@ namespace dpc {
 
 constexpr int S1_WAVES = 4;       // waves per workgroup
 constexpr int S1_U = 4;           // targets per lane: L <= 255
+constexpr int S1_AHEAD = 8;       // source rows fetched per batch
 
 __global__ __launch_bounds__(64 * S1_WAVES) void stage1_kernel(
     int L, const int32_t* __restrict__ T, int32_t* __restrict__ Topt,
@@ -35,23 +36,40 @@ __global__ __launch_bounds__(64 * S1_WAVES) void stage1_kernel(
 #pragma unroll
     for (int u = 0; u < S1_U; ++u) { cur[u] = DPC_INF; arg[u] = k; }
 
-    for (int m = k; m < L; ++m) {
-        // final Topt[k][m]: 0 for m == k, else the owner lane's minimum
-        int32_t own = cur[0];
-        const int um = m >> 6;
+    // The loads of T do not depend on the recurrence: fetch S1_AHEAD source rows
+    // at once, then run their dependent steps from registers.
+    for (int m0 = k; m0 < L; m0 += S1_AHEAD) {
+        int32_t tv[S1_AHEAD][S1_U];
 #pragma unroll
-        for (int u = 1; u < S1_U; ++u) own = (um == u) ? cur[u] : own;
-        int32_t tm = __shfl(own, m & 63, 64);
-        if (m == k) tm = 0;
-        const int32_t* Trow = Tb + (size_t)m * ld;
+        for (int a = 0; a < S1_AHEAD; ++a) {
+            const int m = min(m0 + a, L - 1);
+            const int32_t* Trow = Tb + (size_t)m * ld;
 #pragma unroll
-        for (int u = 0; u < S1_U; ++u) {
-            const int l = lane + 64 * u;
-            if (l > m && l <= L) {
-                // both terms are <= DPC_INF = 2^30 - 1: the sum fits int32
-                int32_t c = tm + Trow[l];
-                c = c > DPC_INF ? DPC_INF : c;
-                if (c < cur[u]) { cur[u] = c; arg[u] = m; }
+            for (int u = 0; u < S1_U; ++u) {
+                const int l = lane + 64 * u;
+                tv[a][u] = (l > m && l <= L) ? Trow[l] : DPC_INF;
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < S1_AHEAD; ++a) {
+            const int m = m0 + a;
+            if (m >= L) break;
+            // final Topt[k][m]: 0 for m == k, else the owner lane's minimum
+            int32_t own = cur[0];
+            const int um = m >> 6;
+#pragma unroll
+            for (int u = 1; u < S1_U; ++u) own = (um == u) ? cur[u] : own;
+            int32_t tm = __shfl(own, m & 63, 64);
+            if (m == k) tm = 0;
+#pragma unroll
+            for (int u = 0; u < S1_U; ++u) {
+                const int l = lane + 64 * u;
+                if (l > m && l <= L) {
+                    // both terms are <= DPC_INF = 2^30 - 1: the sum fits int32
+                    int32_t c = tm + tv[a][u];
+                    c = c > DPC_INF ? DPC_INF : c;
+                    if (c < cur[u]) { cur[u] = c; arg[u] = m; }
+                }
             }
         }
     }
