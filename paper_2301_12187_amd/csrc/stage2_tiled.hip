@@ -70,28 +70,34 @@ struct S2Info {
 
 // one entry per (level, instance); level = group * R + row-in-group
 struct S2Entry {
-    int32_t tstart;                // first ticket of the entry
     int32_t cnt;                   // number of strips (tasks)
     int32_t prev;                  // entry that must be complete first, -1: none
+    int32_t prev_cnt;              // number of tasks of that entry
     int32_t g;                     // >= 0: whole group, ghost width; -1: one row
 };
 
+struct S2Task {
+    int32_t entry, strip;          // in ticket order
+};
+
 struct S2Layout {
-    size_t done_off, entry_off, group_off, rec_off, info_off, total;
-    long long nentries;
+    size_t done_off, entry_off, group_off, task_off, rec_off, info_off, total;
+    long long nentries, maxtasks;
 };
 
 static S2Layout s2_layout(int B, int L, int P)
 {
-    (void)P;
     S2Layout l;
     const size_t nq = ((size_t)L + S2_R - 1) / S2_R;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     l.nentries = (long long)nq * S2_R * B;
+    // most tasks arise when every group runs row by row with the narrowest strips
+    l.maxtasks = l.nentries * (((long long)P + 255) / 256);
     l.done_off = sizeof(S2Header);
     l.entry_off = up(l.done_off + 4 * (size_t)l.nentries);
     l.group_off = up(l.entry_off + sizeof(S2Entry) * ((size_t)l.nentries + 1));
-    l.rec_off = up(l.group_off + 4 * (size_t)B * nq);
+    l.task_off = up(l.group_off + 4 * (size_t)B * nq);
+    l.rec_off = up(l.task_off + sizeof(S2Task) * (size_t)l.maxtasks);
     l.info_off = up(l.rec_off + sizeof(S2Rec) * (size_t)B * nq * (L + 1));
     l.total = up(l.info_off + sizeof(S2Info) * (size_t)B * nq * (L + 1));
     return l;
@@ -190,30 +196,41 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     }
 }
 
-// Task table: entries in ticket order (level-major, then instance), their
-// first tickets (exclusive prefix sum of the strip counts) and the total.
+// Task table: entries in ticket order (level-major, then instance), the task
+// list (entry and strip of every ticket) and the total.  One workgroup; the
+// per-group decisions are first brought into LDS when they fit.
+constexpr int S2_LAYOUT_CACHE = 12288;
 __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     int B, int L, int P, int NQ, int wcap, const int32_t* __restrict__ groups,
-    S2Entry* __restrict__ entries, S2Header* hdr)
+    S2Entry* __restrict__ entries, S2Task* __restrict__ tasks, S2Header* hdr)
 {
     __shared__ int part[1024];
+    __shared__ int gcache[S2_LAYOUT_CACHE];
     const int tid = threadIdx.x;
     const int N = NQ * S2_R * B;
+    const bool cached = B * NQ <= S2_LAYOUT_CACHE;
+    if (cached)
+        for (int x = tid; x < B * NQ; x += 1024) gcache[x] = groups[x];
+    __syncthreads();
+    auto group_of = [&](int b, int q) { return cached ? gcache[b * NQ + q] : groups[(size_t)b * NQ + q]; };
     const int per = (N + 1023) / 1024;
     const int e0 = min(tid * per, N), e1 = min(e0 + per, N);
-    auto count = [&](int e, int& g) {
-        const int level = e / B, b = e - level * B;
-        const int q = level / S2_R, sub = level - q * S2_R;
+    auto count = [&](int b, int q, int sub) {
         const int hq = min(S2_R, L - q * S2_R);
-        const int grp = groups[(size_t)b * NQ + q];
-        g = grp >= 0 && sub == 0 ? grp : -1;
+        const int grp = group_of(b, q);
         // the first strip starts at t = 0 and has no ghost columns
         if (grp >= 0)
             return sub != 0 ? 0 : P <= wcap ? 1 : 1 + (P - wcap + (wcap - grp) - 1) / (wcap - grp);
         return sub < hq ? (P + wcap - 1) / wcap : 0;
     };
     int sum = 0;
-    for (int e = e0; e < e1; ++e) { int g; sum += count(e, g); }
+    {
+        int level = e0 / max(B, 1), b = e0 - level * B;
+        for (int e = e0; e < e1; ++e) {
+            sum += count(b, level / S2_R, level % S2_R);
+            if (++b == B) { b = 0; ++level; }
+        }
+    }
     part[tid] = sum;
     __syncthreads();
     // inclusive scan over the 1024 partial sums
@@ -224,33 +241,40 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
         __syncthreads();
     }
     int run = part[tid] - sum;
-    for (int e = e0; e < e1; ++e) {
-        int g;
-        const int c = count(e, g);
-        const int level = e / B, b = e - level * B;
-        const int q = level / S2_R, sub = level - q * S2_R;
-        int prev;
-        if (sub > 0) prev = e - B;
-        else if (q == 0) prev = -1;
-        else prev = groups[(size_t)b * NQ + q - 1] >= 0 ? ((q - 1) * S2_R) * B + b
-                                                        : ((q - 1) * S2_R + S2_R - 1) * B + b;
-        S2Entry en;
-        en.tstart = run;
-        en.cnt = c;
-        en.prev = prev;
-        en.g = g;
-        entries[e] = en;
-        run += c;
+    {
+        int level = e0 / max(B, 1), b = e0 - level * B;
+        for (int e = e0; e < e1; ++e) {
+            const int q = level / S2_R, sub = level % S2_R;
+            const int c = count(b, q, sub);
+            const int grp = group_of(b, q);
+            int prev, prev_cnt = 0;
+            if (sub > 0) {
+                prev = e - B;
+                prev_cnt = count(b, q, sub - 1);
+            } else if (q == 0) {
+                prev = -1;
+            } else {
+                const int psub = group_of(b, q - 1) >= 0 ? 0 : S2_R - 1;
+                prev = ((q - 1) * S2_R + psub) * B + b;
+                prev_cnt = count(b, q - 1, psub);
+            }
+            S2Entry en;
+            en.cnt = c;
+            en.prev = prev;
+            en.prev_cnt = prev_cnt;
+            en.g = grp >= 0 && sub == 0 ? grp : -1;
+            entries[e] = en;
+            for (int x = 0; x < c; ++x) {
+                S2Task t;
+                t.entry = e;
+                t.strip = x;
+                tasks[run + x] = t;
+            }
+            run += c;
+            if (++b == B) { b = 0; ++level; }
+        }
     }
-    if (tid == 1023) {
-        S2Entry en;
-        en.tstart = part[1023];
-        en.cnt = 0;
-        en.prev = -1;
-        en.g = -1;
-        entries[N] = en;
-        hdr->total = (uint32_t)part[1023];
-    }
+    if (tid == 1023) hdr->total = (uint32_t)part[1023];
 }
 
 // Optional phase timers (build with -DDPC_S2_TIMERS): thread 0 of every
@@ -383,8 +407,9 @@ __device__ __forceinline__ int stage_window(float* slot, const float* row, int l
 template <int NT, int U, int CH, int DMAX, int WPE, bool STORE_K>
 __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
     int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* done,
-    const S2Entry* __restrict__ entries, const S2Rec* __restrict__ recs,
-    const S2Info* __restrict__ infos, int NQ, int nentries, long long wait_limit)
+    const S2Entry* __restrict__ entries, const S2Task* __restrict__ tasks,
+    const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos, int NQ,
+    long long wait_limit)
 {
     constexpr int R = S2_R;
     constexpr int WCAP = NT * U;
@@ -394,7 +419,7 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
     __shared__ __attribute__((aligned(16))) float bufA[CH][SLOTW];
     __shared__ __attribute__((aligned(16))) float bufB[CH][SLOTW];
     __shared__ __attribute__((aligned(16))) float bufC[CH][SLOTW];
-    __shared__ int sh_word[2];
+    __shared__ int sh_word[4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -410,36 +435,48 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
     const int st_row = wave / WPR;                  // row of the chunk this wave copies
     const int st_x0 = (wave - st_row * WPR) * (256 * NGK);
 
+    const int total = (int)hdr->total;
 #ifdef DPC_S2_TIMERS
     long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const long long tkernel0 = wall_clock64();
 #endif
     for (;;) {
         TMARK(t_a);
-        // ---- next ticket and the entry it falls in (wave 0 searches the table)
-        if (tid < 64) {
-            int ticket = 0;
-            if (tid == 0) ticket = (int)atomicAdd(&hdr->ticket, 1u);
-            ticket = __builtin_amdgcn_readfirstlane(ticket);
-            const int total = (int)hdr->total;
-            int lo = 0, hi = nentries;
+        // ---- next ticket, its task, and the wait for the previous level of the
+        //      instance (all by one lane; the rest of the workgroup waits at the barrier)
+        if (tid == 0) {
+            const int ticket = (int)atomicAdd(&hdr->ticket, 1u);
+            int e = -1, strip = 0, g = -1, ok = 1;
             if (ticket < total) {
-                while (hi - lo > 1) {
-                    const int step = (hi - lo + 63) >> 6;
-                    const int p = lo + tid * step;
-                    const bool ok = p < hi && entries[p].tstart <= ticket;
-                    const int c = __popcll(__ballot(ok));
-                    lo = lo + (c - 1) * step;
-                    hi = min(hi, lo + step);
+                const S2Task tk = tasks[ticket];
+                const S2Entry ent = entries[tk.entry];
+                e = tk.entry;
+                strip = tk.strip;
+                g = ent.g;
+                if (ent.prev >= 0) {
+                    const uint32_t need = (uint32_t)ent.prev_cnt;
+                    const uint32_t* flag = &done[ent.prev];
+                    const long long start = wall_clock64();
+                    while (ld_relaxed(flag) < need) {
+                        if (ld_relaxed(&hdr->error) != 0) { ok = 0; break; }
+                        if (wall_clock64() - start > wait_limit) {
+                            __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                            ok = 0;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(2);
+                    }
                 }
-            } else {
-                lo = -1;
             }
-            if (tid == 0) { sh_word[0] = lo; sh_word[1] = ticket; }
+            sh_word[0] = ok ? e : -1;
+            sh_word[1] = strip;
+            sh_word[2] = g;
         }
         __syncthreads();
         const int e = __builtin_amdgcn_readfirstlane(sh_word[0]);
-        const int ticket = __builtin_amdgcn_readfirstlane(sh_word[1]);
+        const int s = __builtin_amdgcn_readfirstlane(sh_word[1]);
+        const int entg = __builtin_amdgcn_readfirstlane(sh_word[2]);
         __syncthreads();
 #ifdef DPC_S2_TIMERS
         if (e < 0 && tid == 0) {
@@ -449,15 +486,13 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
             atomicAdd(&hdr->pad[21], 1u);
         }
 #endif
-        if (e < 0) return;
-        const S2Entry ent = entries[e];
-        const int s = ticket - ent.tstart;
+        if (e < 0) return;                         // no ticket left, or a wait ran out: all leave
         const int level = e / B;
         const int b = e - level * B;
         const int q = level / R;
         const int sub = level - q * R;
-        const bool full = ent.g >= 0;
-        const int g = full && s > 0 ? ent.g : 0;   // the first strip has nothing to its left
+        const bool full = entg >= 0;
+        const int g = full && s > 0 ? entg : 0;    // the first strip has nothing to its left
         const int j0 = 1 + q * R;
         const int hq = min(R, ld - j0);
         const int rlo = full ? 0 : sub;            // rows of the group this task computes
@@ -473,30 +508,6 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
         uint8_t* Kb = STORE_K ? K + (size_t)b * ld * P : nullptr;
         const S2Rec* brec = recs + ((size_t)b * NQ + q) * ld;
         const S2Info* binfo = infos + ((size_t)b * NQ + q) * ld;
-
-        // ---- the previous level of this instance must be complete
-        if (ent.prev >= 0) {
-            if (tid == 0) {
-                const uint32_t need = (uint32_t)entries[ent.prev].cnt;
-                const uint32_t* flag = &done[ent.prev];
-                const long long start = wall_clock64();
-                int ok = 1;
-                while (ld_relaxed(flag) < need) {
-                    if (ld_relaxed(&hdr->error) != 0) { ok = 0; break; }
-                    if (wall_clock64() - start > wait_limit) {
-                        __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-                        ok = 0;
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(2);
-                }
-                sh_word[0] = ok;
-            }
-            __syncthreads();
-            const int ok = __builtin_amdgcn_readfirstlane(sh_word[0]);
-            if (!ok) return;                       // uniform: every thread leaves
-        }
         TMARK(t_b);
         TACC(3, t_a, t_b);
 
@@ -652,6 +663,17 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
         }
 
         // ---------------- diagonal part and output ----------------
+        // records of the group's own rows, fetched four at a time
+        S2Rec drec[4];
+        int dmaxs[4];
+        auto load_diag = [&](int first) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                drec[c] = brec[min(j0 + first + c, L)];
+                dmaxs[c] = binfo[min(j0 + first + c, L)].maxs;
+            }
+        };
+        if (full && !wave_idle) load_diag(0);
 #pragma unroll
         for (int rr = 0; rr < R; ++rr) {
             const int j = j0 + rr;
@@ -676,16 +698,17 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
                 }
                 __syncthreads();
                 if (feeds && !wave_idle) {
-                    const S2Rec rec = brec[j];
-                    const int maxs = binfo[j].maxs;
+                    const S2Rec& rec = drec[rr & 3];
+                    const int maxs = dmaxs[rr & 3];
                     if (maxs >= 0) {
 #pragma unroll
                         for (int r2 = rr + 1; r2 < R; ++r2) {
+                            // shifts inside a group are at most DMAX: a shift beyond
+                            // the task's last column can only occur in the first
+                            // strip, whose pad holds -inf
                             const int w = maxs - rec.off[r2];
-                            const bool ok = w <= tmax;
-                            const float imp = __int_as_float(
-                                ok ? __float_as_int(rec.imp[r2]) : (int)0xFF800000);
-                            const float* sp = &slot[(ok ? DMAX - w : 0) + tl0];
+                            const float imp = rec.imp[r2];
+                            const float* sp = &slot[DMAX - w + tl0];
 #pragma unroll
                             for (int u = 0; u < U; ++u) {
                                 const float cand = sp[64 * u] + imp;
@@ -693,6 +716,7 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
                             }
                         }
                     }
+                    if (rr == 3) load_diag(4);
                 }
             }
         }
@@ -716,12 +740,13 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     constexpr int WCAP = NT * U;
     const int NQ = (L + S2_R - 1) / S2_R;
     const S2Layout lay = s2_layout(B, L, P);
-    if (lay.nentries > 0x3FFFFFF0LL) return hipErrorInvalidValue;
+    if (lay.nentries > 0x3FFFFFF0LL || lay.maxtasks > 0x3FFFFFF0LL) return hipErrorInvalidValue;
     const int N = (int)lay.nentries;
     char* base = (char*)workspace;
     S2Header* hdr = (S2Header*)base;
     uint32_t* done = (uint32_t*)(base + lay.done_off);
     S2Entry* entries = (S2Entry*)(base + lay.entry_off);
+    S2Task* tasks = (S2Task*)(base + lay.task_off);
     int32_t* groups = (int32_t*)(base + lay.group_off);
     S2Rec* recs = (S2Rec*)(base + lay.rec_off);
     S2Info* infos = (S2Info*)(base + lay.info_off);
@@ -736,7 +761,7 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(stage2_layout_kernel, dim3(1), dim3(1024), 0, st, B, L, P, NQ, WCAP, groups,
-                       entries, hdr);
+                       entries, tasks, hdr);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -747,12 +772,12 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     const long long wait_limit = 500000000LL;      // 5 s of the 100 MHz wall clock
     if (K)
         hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, true>), dim3(grid), dim3(NT),
-                           0, st, B, L, P, M, K, hdr, done, entries, recs, infos, NQ, N,
+                           0, st, B, L, P, M, K, hdr, done, entries, tasks, recs, infos, NQ,
                            wait_limit);
     else
         hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, false>), dim3(grid),
-                           dim3(NT), 0, st, B, L, P, M, K, hdr, done, entries, recs, infos, NQ, N,
-                           wait_limit);
+                           dim3(NT), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs, infos,
+                           NQ, wait_limit);
     return hipGetLastError();
 }
 
