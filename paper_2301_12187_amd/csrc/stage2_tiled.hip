@@ -44,6 +44,7 @@
 // shift, so that the wave-uniform operands of a row arrive with one scalar
 // load; a second small kernel lays out the task table.
 #include <algorithm>
+#include <type_traits>
 #include "dpc_internal.h"
 
 namespace dpc {
@@ -60,9 +61,22 @@ struct S2Header {
 };
 
 struct __attribute__((aligned(64))) S2Rec {
-    int32_t off[S2_R];             // maxs - Topt[i][j0+rr]; 0 where there is no candidate
+    uint32_t offp[S2_R / 2];       // 4 * (maxs - Topt[i][j0+rr]) as 16-bit halves (rr even: low),
+                                   // the byte offset of the candidate in the LDS window of row
+                                   // i; 0 where there is no candidate
     float imp[S2_R];               // I[i][j0+rr]; -inf where there is no candidate
+    uint32_t pad[S2_R / 2];
 };
+
+// byte offset of candidate rr inside the window of its row
+__device__ __forceinline__ int rec_off4(const S2Rec& r, int rr)
+{
+    return (rr & 1) ? (int)(r.offp[rr >> 1] >> 16) : (int)(r.offp[rr >> 1] & 0xFFFFu);
+}
+
+struct S2Shift {
+    int32_t w[S2_R];               // Topt[i][j0+rr] itself, -1 where there is no candidate
+};                                 // (read by the row-by-row path only)
 
 struct S2Info {
     int32_t mins, maxs;            // over the valid shifts of the record; maxs = -1: none
@@ -81,7 +95,7 @@ struct S2Task {
 };
 
 struct S2Layout {
-    size_t done_off, entry_off, group_off, task_off, rec_off, info_off, total;
+    size_t done_off, entry_off, group_off, task_off, rec_off, info_off, shift_off, total;
     long long nentries, maxtasks;
 };
 
@@ -99,7 +113,8 @@ static S2Layout s2_layout(int B, int L, int P)
     l.task_off = up(l.group_off + 4 * (size_t)B * nq);
     l.rec_off = up(l.task_off + sizeof(S2Task) * (size_t)l.maxtasks);
     l.info_off = up(l.rec_off + sizeof(S2Rec) * (size_t)B * nq * (L + 1));
-    l.total = up(l.info_off + sizeof(S2Info) * (size_t)B * nq * (L + 1));
+    l.shift_off = up(l.info_off + sizeof(S2Info) * (size_t)B * nq * (L + 1));
+    l.total = up(l.shift_off + sizeof(S2Shift) * (size_t)B * nq * (L + 1));
     return l;
 }
 
@@ -128,8 +143,8 @@ hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
 // inside the group fits dmax and g <= gmax, else -1 (row by row).
 __global__ __launch_bounds__(256) void stage2_pack_kernel(
     int L, int P, int NQ, const int32_t* __restrict__ Topt, const float* __restrict__ I,
-    S2Rec* __restrict__ recs, S2Info* __restrict__ infos, int32_t* __restrict__ groups, int gmax,
-    int dmax, int wcap)
+    S2Rec* __restrict__ recs, S2Info* __restrict__ infos, S2Shift* __restrict__ shifts,
+    int32_t* __restrict__ groups, int gmax, int dmax, int wcap)
 {
     __shared__ int wd[S2_R][S2_R];
     __shared__ int viol;
@@ -163,12 +178,21 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
         rec.imp[rr] = imp;
     }
 #pragma unroll
-    for (int rr = 0; rr < S2_R; ++rr) rec.off[rr] = wv[rr] < 0 ? 0 : maxs - wv[rr];
+    for (int rr = 0; rr < S2_R / 2; ++rr) {
+        // a spread beyond dmax sends the group to the row-by-row path, which does
+        // not use these offsets: clamp so that the halves cannot overflow
+        const uint32_t lo = wv[2 * rr] < 0 ? 0u : (uint32_t)min(maxs - wv[2 * rr], 16383) * 4u;
+        const uint32_t hi = wv[2 * rr + 1] < 0 ? 0u : (uint32_t)min(maxs - wv[2 * rr + 1], 16383) * 4u;
+        rec.offp[rr] = lo | (hi << 16);
+        rec.pad[rr] = 0;
+    }
     if (i < ld) {
         const size_t idx = ((size_t)b * NQ + q) * ld + i;
         recs[idx] = rec;
         infos[idx].mins = mins;
         infos[idx].maxs = maxs;
+#pragma unroll
+        for (int rr = 0; rr < S2_R; ++rr) shifts[idx].w[rr] = wv[rr];
     }
     if (i < j0 && maxs >= 0 && maxs - mins > dmax) viol = 1;
     if (i >= j0 && i < j0 + S2_R) {
@@ -408,8 +432,8 @@ template <int NT, int U, int CH, int DMAX, int WPE, bool STORE_K>
 __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
     int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* done,
     const S2Entry* __restrict__ entries, const S2Task* __restrict__ tasks,
-    const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos, int NQ,
-    long long wait_limit)
+    const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos,
+    const S2Shift* __restrict__ shifts, int NQ, long long wait_limit)
 {
     constexpr int R = S2_R;
     constexpr int WCAP = NT * U;
@@ -502,12 +526,12 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
         const int t0 = s == 0 ? 0 : WCAP + (s - 1) * weff;   // first stored column
         const int tS = t0 - g;                     // first computed column
         const int tend = min(tS + WCAP, P);
-        const int tmax = tend - 1;
         const int tstore_end = min(t0 + weff, P);
         float* Mb = M + (size_t)b * ld * P;
         uint8_t* Kb = STORE_K ? K + (size_t)b * ld * P : nullptr;
         const S2Rec* brec = recs + ((size_t)b * NQ + q) * ld;
         const S2Info* binfo = infos + ((size_t)b * NQ + q) * ld;
+        const S2Shift* bshift = shifts + ((size_t)b * NQ + q) * ld;
         TMARK(t_b);
         TACC(3, t_a, t_b);
 
@@ -530,21 +554,16 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
 #pragma unroll
             for (int u = 0; u < U; ++u) { best[rr][u] = NINF; arg[rr][u] = DPC_NOARG; }
 
-        // a one-row task keeps only row `sub` of a record: its window is that
-        // row's own shift, every other row of the group gets "no candidate"
-        auto fix_one_row = [&](S2Rec& rec, S2Info& inf) {
-            int w = -1;
-            float imp = NINF;
+        // a one-row task uses only row `sub` of a predecessor: its shift (-1: no
+        // candidate) and importance
+        auto one_row_of = [&](int i, int& w, float& imp) __attribute__((always_inline)) {
+            const S2Shift sh = bshift[i];
+            const S2Rec rec = brec[i];
+            w = -1;
+            imp = NINF;
 #pragma unroll
             for (int rr = 0; rr < R; ++rr)
-                if (rr == sub && rec.imp[rr] != NINF) { w = inf.maxs - rec.off[rr]; imp = rec.imp[rr]; }
-#pragma unroll
-            for (int rr = 0; rr < R; ++rr) {
-                rec.off[rr] = 0;
-                rec.imp[rr] = rr == sub ? imp : NINF;
-            }
-            inf.mins = w < 0 ? 0x7FFFFFFF : w;
-            inf.maxs = w;
+                if (rr == sub) { w = sh.w[rr]; imp = rec.imp[rr]; }
         };
 
         // a wave whose columns all lie beyond the table has nothing to relax
@@ -552,15 +571,19 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
 
         // start the copy of this wave's part of the window of row i0 + st_row
         // into `buf` (asynchronous); returns the number of loads issued
-        auto stage_chunk = [&](float (*buf)[SLOTW], int i0) {
+        auto stage_chunk = [&](float (*buf)[SLOTW], int i0) __attribute__((always_inline)) {
             const int i = i0 + st_row;
             if (i >= ilimit) return 0;
             S2Info inf = binfo[i];
             if (!full) {
-                S2Rec tmp = brec[i];
-                fix_one_row(tmp, inf);
+                int w;
+                float imp;
+                one_row_of(i, w, imp);
+                inf.mins = inf.maxs = w;
             }
-            if (inf.maxs < 0 || inf.mins > tmax) return 0;
+            // (a row none of whose shifts reaches the task is copied all the same:
+            //  its window is then the -inf that lies below column 0)
+            if (inf.maxs < 0) return 0;
             const int lo = tS - inf.maxs;
             const int n = tend - inf.mins - lo;
             if (st_x0 >= n) return 0;
@@ -568,28 +591,29 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
                                      lane);
         };
 
-        // relax the group's rows from the rows [i0, i0+CH) held in `buf`
-        auto relax_chunk = [&](const float (*buf)[SLOTW], int i0, const S2Rec (&rec)[CH],
-                               const S2Info (&inf)[CH]) {
+        // relax the group's rows from the rows [i0, i0+CH) held in `buf`.
+        // A candidate whose shift exceeds every column of the task reads the
+        // part of the window that lies below column 0, which was filled with
+        // -inf; a missing candidate adds -inf to whatever the slot holds: neither
+        // needs a test here.
+        auto relax_chunk = [&](const float (*buf)[SLOTW], int i0, const S2Rec (&rec)[CH])
+                               __attribute__((always_inline)) {
 #pragma unroll
             for (int c = 0; c < CH; ++c) {
                 const int i = i0 + c;
-                const int mins = inf[c].mins, maxs = inf[c].maxs;
-                if (i >= ilimit || maxs < 0 || mins > tmax) continue;   // nothing reaches the task
-                // A candidate whose shift exceeds every column of the task reads
-                // the part of the window that lies below column 0, which was
-                // filled with -inf; a missing candidate adds -inf: neither needs
-                // a test here.
-                const float* base = &buf[c][tl0];
+                if (i >= ilimit) continue;
+                const char* base = (const char*)&buf[c][tl0];
                 // LDS reads run one row of the group ahead of the arithmetic
                 float mcur[U], mnxt[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) mcur[u] = base[rec[c].off[0] + 64 * u];
+                for (int u = 0; u < U; ++u)
+                    mcur[u] = *(const float*)(base + rec_off4(rec[c], 0) + 256 * u);
 #pragma unroll
                 for (int rr = 0; rr < R; ++rr) {
                     if (rr + 1 < R) {
 #pragma unroll
-                        for (int u = 0; u < U; ++u) mnxt[u] = base[rec[c].off[rr + 1] + 64 * u];
+                        for (int u = 0; u < U; ++u)
+                            mnxt[u] = *(const float*)(base + rec_off4(rec[c], rr + 1) + 256 * u);
                     }
                     const float imp = rec[c].imp[rr];
                     float cand[U];
@@ -615,17 +639,40 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
         // flight), start the copies of the chunk two ahead into the buffer that
         // was relaxed last, relax.
         int later = 0;         // copies in flight for the chunk after the current one
-        auto chunk_step = [&](float (*cur)[SLOTW], float (*free2)[SLOTW], int i0) {
+        // (A one-row task has its own, simple relax so that the whole-group path
+        //  keeps its records untouched in scalar registers.)
+        auto relax_one_row = [&](const float (*buf)[SLOTW], int i0) __attribute__((always_inline)) {
+            for (int c = 0; c < CH; ++c) {
+                const int i = i0 + c;
+                if (i >= ilimit) break;
+                int w;
+                float imp;
+                one_row_of(i, w, imp);
+                if (w < 0) continue;
+                const float* base = &buf[c][tl0];       // the window starts at tS - w
+#pragma unroll
+                for (int rr = 0; rr < R; ++rr) {
+                    if (rr != sub) continue;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const float cand = base[64 * u] + imp;
+                        if (cand > best[rr][u]) { best[rr][u] = cand; arg[rr][u] = i; }
+                    }
+                }
+            }
+        };
+        auto chunk_step = [&](auto whole, float (*cur)[SLOTW], float (*free2)[SLOTW], int i0)
+                              __attribute__((always_inline)) {
+            constexpr bool WHOLE = decltype(whole)::value;
             S2Rec rec[CH];
-            S2Info inf[CH];
-            if (!wave_idle) {
+            if (WHOLE && !wave_idle) {
 #pragma unroll
-                for (int c = 0; c < CH; ++c) rec[c] = brec[min(i0 + c, L)];
+                for (int c = 0; c < CH; ++c) {
+                    const S2Rec* r = &brec[min(i0 + c, L)];
 #pragma unroll
-                for (int c = 0; c < CH; ++c) inf[c] = binfo[min(i0 + c, L)];
-                if (!full) {
+                    for (int x = 0; x < R / 2; ++x) rec[c].offp[x] = r->offp[x];
 #pragma unroll
-                    for (int c = 0; c < CH; ++c) fix_one_row(rec[c], inf[c]);
+                    for (int x = 0; x < R; ++x) rec[c].imp[x] = r->imp[x];
                 }
             }
             TMARK(ta);
@@ -634,23 +681,30 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
             TMARK(tb);
             const int fresh = stage_chunk(free2, i0 + 2 * CH);
             TMARK(tc);
-            if (!wave_idle) relax_chunk(cur, i0, rec, inf);
+            if (!wave_idle) {
+                if constexpr (WHOLE) relax_chunk(cur, i0, rec);
+                else relax_one_row(cur, i0);
+            }
             TMARK(td);
             TACC(0, ta, tb);
             TACC(1, tb, tc);
             TACC(2, tc, td);
             return fresh;
         };
+        auto off_diagonal = [&](auto whole) __attribute__((always_inline)) {
+            // (the barrier that ended the previous task has freed all buffers)
+            stage_chunk(bufA, 0);
+            later = stage_chunk(bufB, CH);
+            for (int i0 = 0; i0 < ilimit; i0 += 3 * CH) {
+                later = chunk_step(whole, bufA, bufC, i0);
+                if (i0 + CH < ilimit) later = chunk_step(whole, bufB, bufA, i0 + CH);
+                if (i0 + 2 * CH < ilimit) later = chunk_step(whole, bufC, bufB, i0 + 2 * CH);
+            }
+        };
 
         // ---------------- off-diagonal part: rows i < ilimit ----------------
-        // (the barrier that ended the previous task has freed all buffers)
-        stage_chunk(bufA, 0);
-        later = stage_chunk(bufB, CH);
-        for (int i0 = 0; i0 < ilimit; i0 += 3 * CH) {
-            later = chunk_step(bufA, bufC, i0);
-            if (i0 + CH < ilimit) later = chunk_step(bufB, bufA, i0 + CH);
-            if (i0 + 2 * CH < ilimit) later = chunk_step(bufC, bufB, i0 + 2 * CH);
-        }
+        if (full) off_diagonal(std::true_type{});
+        else off_diagonal(std::false_type{});
         TMARK(t_c);
         __syncthreads();                               // off-diagonal readers done
         if (full && tS == 0) {
@@ -666,7 +720,7 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
         // records of the group's own rows, fetched four at a time
         S2Rec drec[4];
         int dmaxs[4];
-        auto load_diag = [&](int first) {
+        auto load_diag = [&](int first) __attribute__((always_inline)) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 drec[c] = brec[min(j0 + first + c, L)];
@@ -706,7 +760,7 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
                             // shifts inside a group are at most DMAX: a shift beyond
                             // the task's last column can only occur in the first
                             // strip, whose pad holds -inf
-                            const int w = maxs - rec.off[r2];
+                            const int w = maxs - (rec_off4(rec, r2) >> 2);
                             const float imp = rec.imp[r2];
                             const float* sp = &slot[DMAX - w + tl0];
 #pragma unroll
@@ -750,6 +804,7 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     int32_t* groups = (int32_t*)(base + lay.group_off);
     S2Rec* recs = (S2Rec*)(base + lay.rec_off);
     S2Info* infos = (S2Info*)(base + lay.info_off);
+    S2Shift* shifts = (S2Shift*)(base + lay.shift_off);
 
     hipError_t e = launch_clear_words(workspace, (int)(sizeof(S2Header) / 4) + N, st);
     if (e != hipSuccess) return e;
@@ -757,7 +812,7 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     // chain of shifts must fit the pad in front of a diagonal slot
     const int gmax = std::min(DMAX, WCAP / 4);
     hipLaunchKernelGGL(stage2_pack_kernel, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I, recs,
-                       infos, groups, gmax, DMAX, WCAP);
+                       infos, shifts, groups, gmax, DMAX, WCAP);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(stage2_layout_kernel, dim3(1), dim3(1024), 0, st, B, L, P, NQ, WCAP, groups,
@@ -772,12 +827,12 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     const long long wait_limit = 500000000LL;      // 5 s of the 100 MHz wall clock
     if (K)
         hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, true>), dim3(grid), dim3(NT),
-                           0, st, B, L, P, M, K, hdr, done, entries, tasks, recs, infos, NQ,
-                           wait_limit);
+                           0, st, B, L, P, M, K, hdr, done, entries, tasks, recs, infos, shifts,
+                           NQ, wait_limit);
     else
         hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, false>), dim3(grid),
                            dim3(NT), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs, infos,
-                           NQ, wait_limit);
+                           shifts, NQ, wait_limit);
     return hipGetLastError();
 }
 
