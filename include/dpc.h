@@ -155,8 +155,9 @@ const char *dpc_status_string(int code);
  *   0  automatic (default)
  *   1  row-at-a-time kernels reading M from global memory (one launch per row)
  *   2  persistent LDS-tiled kernel, strip shape chosen from the problem size
- *   21..25  persistent LDS-tiled kernel with a fixed strip shape: 256, 512,
- *       1024, 2048 or 4096 budgets per workgroup
+ *   21..26  persistent LDS-tiled kernel with a fixed task shape (threads x
+ *       columns per thread, window buffers): 256x1, 256x2, 256x4 (2 buffers),
+ *       512x2, 1024x2, 512x2 (2 buffers)
  * Returns the previous value, or DPC_ERR_SHAPE for an unknown one.  Results
  * are bit-identical for every choice.  Process-wide, not thread-safe.
  */

@@ -45,7 +45,7 @@ const char* dpc_status_string(int code)
 
 int dpc_set_stage2_variant(int variant)
 {
-    if (!((variant >= 0 && variant <= 2) || (variant >= 21 && variant <= 25))) return DPC_ERR_SHAPE;
+    if (!((variant >= 0 && variant <= 2) || (variant >= 21 && variant <= 26))) return DPC_ERR_SHAPE;
     int prev = g_stage2_variant;
     g_stage2_variant = variant;
     dpc::g_s2_shape = variant > 20 ? variant - 20 : 0;

@@ -428,7 +428,7 @@ __device__ __forceinline__ int stage_window(float* slot, const float* row, int l
     return issued;
 }
 
-template <int NT, int U, int CH, int DMAX, int WPE, bool STORE_K>
+template <int NT, int U, int CH, int DMAX, int WPE, int NBUF, bool STORE_K>
 __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
     int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* done,
     const S2Entry* __restrict__ entries, const S2Task* __restrict__ tasks,
@@ -442,7 +442,8 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
     static_assert(2 * CH >= R - 1, "the diagonal part needs R-1 slots");
     __shared__ __attribute__((aligned(16))) float bufA[CH][SLOTW];
     __shared__ __attribute__((aligned(16))) float bufB[CH][SLOTW];
-    __shared__ __attribute__((aligned(16))) float bufC[CH][SLOTW];
+    static_assert(NBUF == 2 || NBUF == 3, "two or three window buffers");
+    __shared__ __attribute__((aligned(16))) float bufC[NBUF == 3 ? CH : 1][NBUF == 3 ? SLOTW : 4];
     __shared__ int sh_word[4];
 
     const int tid = threadIdx.x;
@@ -679,7 +680,7 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
             wait_vm(later);
             lds_barrier();                             // `cur` filled, `free2` no longer read
             TMARK(tb);
-            const int fresh = stage_chunk(free2, i0 + 2 * CH);
+            const int fresh = stage_chunk(free2, i0 + (NBUF - 1) * CH);
             TMARK(tc);
             if (!wave_idle) {
                 if constexpr (WHOLE) relax_chunk(cur, i0, rec);
@@ -694,11 +695,22 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
         auto off_diagonal = [&](auto whole) __attribute__((always_inline)) {
             // (the barrier that ended the previous task has freed all buffers)
             stage_chunk(bufA, 0);
-            later = stage_chunk(bufB, CH);
-            for (int i0 = 0; i0 < ilimit; i0 += 3 * CH) {
-                later = chunk_step(whole, bufA, bufC, i0);
-                if (i0 + CH < ilimit) later = chunk_step(whole, bufB, bufA, i0 + CH);
-                if (i0 + 2 * CH < ilimit) later = chunk_step(whole, bufC, bufB, i0 + 2 * CH);
+            if constexpr (NBUF == 3) {
+                later = stage_chunk(bufB, CH);
+                for (int i0 = 0; i0 < ilimit; i0 += 3 * CH) {
+                    later = chunk_step(whole, bufA, (float (*)[SLOTW])bufC, i0);
+                    if (i0 + CH < ilimit) later = chunk_step(whole, bufB, bufA, i0 + CH);
+                    if (i0 + 2 * CH < ilimit)
+                        later = chunk_step(whole, (float (*)[SLOTW])bufC, bufB, i0 + 2 * CH);
+                }
+            } else {
+                // two buffers: the copy in flight is always the one waited for next
+                for (int i0 = 0; i0 < ilimit; i0 += 2 * CH) {
+                    chunk_step(whole, bufA, bufB, i0);
+                    later = 0;
+                    if (i0 + CH < ilimit) chunk_step(whole, bufB, bufA, i0 + CH);
+                    later = 0;
+                }
             }
         };
 
@@ -787,7 +799,7 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
     }
 }
 
-template <int NT, int U, int CH, int DMAX, int WPE>
+template <int NT, int U, int CH, int DMAX, int WPE, int NBUF>
 static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                              uint8_t* K, void* workspace, int num_cu, hipStream_t st)
 {
@@ -826,11 +838,11 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     const int grid = num_cu * wg_per_cu;
     const long long wait_limit = 500000000LL;      // 5 s of the 100 MHz wall clock
     if (K)
-        hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, true>), dim3(grid), dim3(NT),
+        hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, NBUF, true>), dim3(grid), dim3(NT),
                            0, st, B, L, P, M, K, hdr, done, entries, tasks, recs, infos, shifts,
                            NQ, wait_limit);
     else
-        hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, false>), dim3(grid),
+        hipLaunchKernelGGL((stage2_tiled_kernel<NT, U, CH, DMAX, WPE, NBUF, false>), dim3(grid),
                            dim3(NT), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs, infos,
                            shifts, NQ, wait_limit);
     return hipGetLastError();
@@ -842,19 +854,23 @@ hipError_t launch_stage2_tiled(int B, int L, int P, const int32_t* Topt, const f
                                uint8_t* K, void* workspace, int num_cu, hipStream_t st)
 {
     // WCAP = NT*U columns per task.  Narrow tables take the narrowest shape that
-    // covers them.
+    // covers them.  Wide tables use 1024 columns per task: with many rows (long
+    // tasks) two workgroups per compute unit and three window buffers, with few
+    // rows (short tasks, latency-bound) three workgroups and two buffers
+    // (measured on the stress, L=100 and L=53 workloads).
     int shape = g_s2_shape;
     if (shape == 0) {
         if (P <= 256) shape = 1;
         else if (P <= 512) shape = 2;
-        else shape = 4;
+        else shape = L >= 128 ? 4 : 6;
     }
     switch (shape) {
-        case 1: return launch_cfg<256, 1, 4, 240, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 2: return launch_cfg<256, 2, 4, 240, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 3: return launch_cfg<256, 4, 4, 256, 2>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 4: return launch_cfg<512, 2, 4, 256, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 5: return launch_cfg<1024, 2, 4, 256, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 1: return launch_cfg<256, 1, 4, 240, 4, 3>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 2: return launch_cfg<256, 2, 4, 240, 4, 3>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 3: return launch_cfg<256, 4, 4, 240, 4, 2>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 4: return launch_cfg<512, 2, 4, 256, 4, 3>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 5: return launch_cfg<1024, 2, 4, 256, 4, 3>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 6: return launch_cfg<512, 2, 4, 256, 6, 2>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         default: return hipErrorInvalidValue;
     }
 }

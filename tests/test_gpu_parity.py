@@ -11,6 +11,7 @@ from gpu_common import compare, run_gpu, run_oracle
 pytestmark = pytest.mark.gpu
 
 VARIANTS = [1, 2]
+SHAPES = [21, 22, 23, 24, 25, 26]      # every task shape of the tiled kernel
 
 
 def _all_budgets(B, P, step=1):
@@ -52,7 +53,7 @@ def test_tiny_tie_rich_instances(seed, variant):
     compare(g, r, L, f"tiny seed {seed} L={L} P={P}")
 
 
-@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("variant", VARIANTS + SHAPES)
 def test_ragged_shapes_span_several_tiles(variant):
     """Sizes that are not multiples of any tile: several t-tiles with a ragged
     tail, row counts that leave a partial row block."""
@@ -71,7 +72,7 @@ def test_ragged_shapes_span_several_tiles(variant):
         compare(g, r, L, f"ragged B={B} L={L} P={P}")
 
 
-@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("variant", VARIANTS + SHAPES)
 def test_wide_shift_spread_and_infeasible_blocks(variant):
     """Adversarial latencies: shifts that differ wildly between neighbouring
     columns of Topt, latencies beyond P, whole instances that are infeasible."""
@@ -144,7 +145,7 @@ def test_config3_batch(variant):
     compare(g, r, cfg.L, cfg.name)
 
 
-@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("variant", VARIANTS + [24, 26])
 def test_config4_batch(variant):
     cfg = inputs.CONFIGS[4]
     T, I, base = inputs.make_batch(cfg, seed=0)
