@@ -221,24 +221,26 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
 }
 
 // Task table: entries in ticket order (level-major, then instance), the task
-// list (entry and strip of every ticket) and the total.  One workgroup; the
-// per-group decisions are first brought into LDS when they fit.
+// list (entry and strip of every ticket) and the total.  One workgroup walks
+// the entries in tiles of 1024, one entry per thread (so that its stores are
+// coalesced), with a running prefix sum of the strip counts: wave scan, then
+// one combine of the 16 wave totals per tile.  The per-group decisions are
+// first brought into LDS when they fit.
 constexpr int S2_LAYOUT_CACHE = 12288;
 __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     int B, int L, int P, int NQ, int wcap, const int32_t* __restrict__ groups,
     S2Entry* __restrict__ entries, S2Task* __restrict__ tasks, S2Header* hdr)
 {
-    __shared__ int part[1024];
+    __shared__ int wsum[2][16];
     __shared__ int gcache[S2_LAYOUT_CACHE];
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const int N = NQ * S2_R * B;
     const bool cached = B * NQ <= S2_LAYOUT_CACHE;
     if (cached)
         for (int x = tid; x < B * NQ; x += 1024) gcache[x] = groups[x];
     __syncthreads();
     auto group_of = [&](int b, int q) { return cached ? gcache[b * NQ + q] : groups[(size_t)b * NQ + q]; };
-    const int per = (N + 1023) / 1024;
-    const int e0 = min(tid * per, N), e1 = min(e0 + per, N);
     auto count = [&](int b, int q, int sub) {
         const int hq = min(S2_R, L - q * S2_R);
         const int grp = group_of(b, q);
@@ -247,58 +249,59 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
             return sub != 0 ? 0 : P <= wcap ? 1 : 1 + (P - wcap + (wcap - grp) - 1) / (wcap - grp);
         return sub < hq ? (P + wcap - 1) / wcap : 0;
     };
-    int sum = 0;
-    {
-        int level = e0 / max(B, 1), b = e0 - level * B;
-        for (int e = e0; e < e1; ++e) {
-            sum += count(b, level / S2_R, level % S2_R);
-            if (++b == B) { b = 0; ++level; }
-        }
-    }
-    part[tid] = sum;
-    __syncthreads();
-    // inclusive scan over the 1024 partial sums
-    for (int d = 1; d < 1024; d <<= 1) {
-        int v = tid >= d ? part[tid - d] : 0;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
-    }
-    int run = part[tid] - sum;
-    {
-        int level = e0 / max(B, 1), b = e0 - level * B;
-        for (int e = e0; e < e1; ++e) {
+    int base = 0;                                   // tickets before this tile
+    for (int e0 = 0, it = 0; e0 < N; e0 += 1024, ++it) {
+        const int e = e0 + tid;
+        int c = 0, prev = -1, prev_cnt = 0, g = -1;
+        if (e < N) {
+            const int level = e / B, b = e - level * B;
             const int q = level / S2_R, sub = level % S2_R;
-            const int c = count(b, q, sub);
+            c = count(b, q, sub);
             const int grp = group_of(b, q);
-            int prev, prev_cnt = 0;
+            g = grp >= 0 && sub == 0 ? grp : -1;
             if (sub > 0) {
                 prev = e - B;
                 prev_cnt = count(b, q, sub - 1);
-            } else if (q == 0) {
-                prev = -1;
-            } else {
+            } else if (q > 0) {
                 const int psub = group_of(b, q - 1) >= 0 ? 0 : S2_R - 1;
                 prev = ((q - 1) * S2_R + psub) * B + b;
                 prev_cnt = count(b, q - 1, psub);
             }
+        }
+        // inclusive scan of c inside the wave
+        int incl = c;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int v = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += v;
+        }
+        if (lane == 63) wsum[it & 1][wave] = incl;
+        __syncthreads();
+        int before = 0, tile_total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int v = wsum[it & 1][w];
+            if (w < wave) before += v;
+            tile_total += v;
+        }
+        const int tstart = base + before + incl - c;
+        if (e < N) {
             S2Entry en;
             en.cnt = c;
             en.prev = prev;
             en.prev_cnt = prev_cnt;
-            en.g = grp >= 0 && sub == 0 ? grp : -1;
+            en.g = g;
             entries[e] = en;
             for (int x = 0; x < c; ++x) {
                 S2Task t;
                 t.entry = e;
                 t.strip = x;
-                tasks[run + x] = t;
+                tasks[tstart + x] = t;
             }
-            run += c;
-            if (++b == B) { b = 0; ++level; }
         }
+        base += tile_total;
     }
-    if (tid == 1023) hdr->total = (uint32_t)part[1023];
+    if (tid == 0) hdr->total = (uint32_t)base;
 }
 
 // Optional phase timers (build with -DDPC_S2_TIMERS): thread 0 of every
