@@ -158,6 +158,10 @@ const char *dpc_status_string(int code);
  *   21..26  persistent LDS-tiled kernel with a fixed task shape (threads x
  *       columns per thread, window buffers): 256x1, 256x2, 256x4 (2 buffers),
  *       512x2, 1024x2, 512x2 (2 buffers)
+ *   3  persistent kernel with wave-private windows, task shape chosen from
+ *       the problem size (tables narrower than 16 budgets run as 2)
+ *   31..35  the same with a fixed task shape (waves x columns per lane):
+ *       4x4, 8x4, 2x4, 1x4, 4x2
  * Returns the previous value, or DPC_ERR_SHAPE for an unknown one.  Results
  * are bit-identical for every choice.  Process-wide, not thread-safe.
  */

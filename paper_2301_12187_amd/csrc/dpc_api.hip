@@ -45,10 +45,13 @@ const char* dpc_status_string(int code)
 
 int dpc_set_stage2_variant(int variant)
 {
-    if (!((variant >= 0 && variant <= 2) || (variant >= 21 && variant <= 26))) return DPC_ERR_SHAPE;
+    if (!((variant >= 0 && variant <= 3) || (variant >= 21 && variant <= 26) ||
+          (variant >= 31 && variant <= 35)))
+        return DPC_ERR_SHAPE;
     int prev = g_stage2_variant;
     g_stage2_variant = variant;
-    dpc::g_s2_shape = variant > 20 ? variant - 20 : 0;
+    dpc::g_s2_shape = variant > 20 && variant < 30 ? variant - 20 : 0;
+    dpc::g_s2w_shape = variant > 30 ? variant - 30 : 0;
     return prev;
 }
 
@@ -85,7 +88,12 @@ int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, co
     } else {
         const int ncu = num_compute_units();
         if (ncu <= 0) return DPC_ERR_HIP;
-        e = dpc::launch_stage2_tiled(B, L, P, Topt, I, M, K, workspace, ncu, (hipStream_t)stream);
+        // the wave-window family reads whole 16-byte cells: narrow tables stay tiled
+        const bool wave = (g_stage2_variant == 3 || g_stage2_variant > 30) && P >= 16;
+        e = wave ? dpc::launch_stage2_wave(B, L, P, Topt, I, M, K, workspace, ncu,
+                                           (hipStream_t)stream)
+                 : dpc::launch_stage2_tiled(B, L, P, Topt, I, M, K, workspace, ncu,
+                                            (hipStream_t)stream);
     }
     return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
 }

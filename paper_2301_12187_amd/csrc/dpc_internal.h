@@ -16,6 +16,9 @@ hipError_t launch_clear_words(void* p, int nwords, hipStream_t st);
 size_t stage2_tiled_workspace_bytes(int B, int L, int P);
 hipError_t launch_stage2_tiled(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                                uint8_t* K, void* workspace, int num_cu, hipStream_t st);
+hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
+                              uint8_t* K, void* workspace, int num_cu, hipStream_t st);
+extern int g_s2w_shape;  // the same for the wave-window family, 1..5
 extern int g_s2_shape;   // 0 = choose the strip shape from the problem size, 1..5 = force it
 // reads the error word out of a host copy of the first 8 workspace bytes
 int stage2_tiled_error(const void* workspace_host_copy);

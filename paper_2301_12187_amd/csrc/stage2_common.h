@@ -1,0 +1,128 @@
+// Declarations shared by the persistent stage-2 kernels (Algorithm 2 /
+// recurrence Eq. 7 of the paper): the workspace layout, the repacked operand
+// records and the task table, and the small kernels that build them.
+#pragma once
+#include <algorithm>
+#include <type_traits>
+#include "dpc_internal.h"
+
+namespace dpc {
+
+typedef __attribute__((address_space(3))) void lds_void;
+
+constexpr int S2_R = 8;            // rows per group (record layout depends on it)
+
+struct S2Header {
+    uint32_t ticket;
+    uint32_t error;
+    uint32_t total;                // number of tasks, written by the layout kernel
+    uint32_t pad[29];              // (phase timers of instrumented builds)
+    float ninf[4];                 // byte 128: sixteen bytes of -inf, the source of window
+                                   // cells that lie below column 0 (layout kernel)
+    uint32_t pad2[28];
+};
+static_assert(sizeof(S2Header) == 256, "header is one 256-byte block");
+
+struct __attribute__((aligned(64))) S2Rec {
+    uint32_t offp[S2_R / 2];       // 4 * (maxs - Topt[i][j0+rr]) as 16-bit halves (rr even: low),
+                                   // the byte offset of the candidate in the LDS window of row
+                                   // i; 0 where there is no candidate
+    float imp[S2_R];               // I[i][j0+rr]; -inf where there is no candidate
+    uint32_t pad[S2_R / 2];        // [0]: largest shift of the record; [1], [2]: largest and
+                                   // smallest shift of the record `ahead` rows further on
+                                   // (0 where a record holds no candidate); [3]: i
+};
+
+// byte offset of candidate rr inside the window of its row
+__device__ __forceinline__ int rec_off4(const S2Rec& r, int rr)
+{
+    return (rr & 1) ? (int)(r.offp[rr >> 1] >> 16) : (int)(r.offp[rr >> 1] & 0xFFFFu);
+}
+
+struct S2Shift {
+    int32_t w[S2_R];               // Topt[i][j0+rr] itself, -1 where there is no candidate
+};                                 // (read by the row-by-row path only)
+
+struct S2Info {
+    int32_t mins, maxs;            // over the valid shifts of the record; maxs = -1: none
+};
+
+// one entry per (level, instance); level = group * R + row-in-group
+struct S2Entry {
+    int32_t cnt;                   // number of strips (tasks)
+    int32_t prev;                  // entry whose rows this one reads last, -1: none
+    int32_t prev_cnt;              // number of tasks of that entry
+    int32_t g;                     // >= 0: whole group, ghost width; -1: one row
+    int32_t prev_row0;             // first row that entry `prev` writes
+    int32_t prev2;                 // the entry before `prev` (all rows below prev_row0 are
+    int32_t prev2_cnt;             // final once it is complete), -1: none; its task count
+    int32_t pad;
+};
+
+struct S2Task {
+    int32_t entry, strip;          // in ticket order
+};
+
+struct S2Layout {
+    size_t done_off, entry_off, group_off, task_off, rec_off, info_off, shift_off, total;
+    long long nentries, maxtasks;
+};
+
+S2Layout s2_layout(int B, int L, int P);
+
+// Queues the kernels that prepare a stage-2 launch on `st`: clears the header
+// and the completion counters, writes row 0 of M (and K), repacks Topt and I
+// into records for row groups of S2_R rows and decides per group whether it
+// runs whole (ghost width <= gmax, every spread and every shift inside the
+// group <= dmax) or row by row, and lays out the task table for strips of
+// `wcap` columns.  `ahead`: see S2Rec::pad.
+hipError_t launch_stage2_prepare(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
+                                 uint8_t* K, void* workspace, int gmax, int dmax, int wcap,
+                                 int ahead, hipStream_t st);
+
+__device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// M and K travel between workgroups on different compute units (and L2
+// slices): they are written with agent-scope stores, which go through to the
+// level every compute unit sees, and read back with agent-scope loads, which
+// do not use a copy cached before the write.  A task counts as complete once
+// the vector-memory counter of every wave has drained (the stores have been
+// acknowledged) and the completion counter has then been incremented.
+__device__ __forceinline__ void st_agent(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(uint8_t* p, uint8_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+constexpr int DMA_AGENT_SCOPE = 16;        // cache-policy bit sc1 of the global -> LDS load
+
+// Wait until at most `later` of the vector-memory operations this wave has
+// issued are still outstanding.  They complete in order, so this waits for
+// everything issued before the last `later` ones.  A smaller number only waits
+// longer, so the count is clamped to what is spelled out here.
+__device__ __forceinline__ void wait_vm(int later)
+{
+    // s_waitcnt immediates: vmcnt in bits 3:0 (and 15:14), expcnt 6:4 and lgkmcnt 11:8 left alone
+    switch (later) {
+        case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+        case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
+        case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
+        case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
+        case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+        case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
+        case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+        case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
+        default: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+    }
+}
+
+}  // namespace dpc

@@ -42,267 +42,11 @@
 // Topt and I are first repacked per (instance, row group, predecessor i) into
 // 64-byte records {offset[R], importance[R]} plus the minimum and maximum
 // shift, so that the wave-uniform operands of a row arrive with one scalar
-// load; a second small kernel lays out the task table.
-#include <algorithm>
-#include <type_traits>
-#include "dpc_internal.h"
+// load; a second small kernel lays out the task table and the first also
+// writes row 0 of M, the base case (see stage2_pack.hip).
+#include "stage2_common.h"
 
 namespace dpc {
-
-typedef __attribute__((address_space(3))) void lds_void;
-
-constexpr int S2_R = 8;            // rows per group (record layout depends on it)
-
-struct S2Header {
-    uint32_t ticket;
-    uint32_t error;
-    uint32_t total;                // number of tasks, written by the layout kernel
-    uint32_t pad[61];
-};
-
-struct __attribute__((aligned(64))) S2Rec {
-    uint32_t offp[S2_R / 2];       // 4 * (maxs - Topt[i][j0+rr]) as 16-bit halves (rr even: low),
-                                   // the byte offset of the candidate in the LDS window of row
-                                   // i; 0 where there is no candidate
-    float imp[S2_R];               // I[i][j0+rr]; -inf where there is no candidate
-    uint32_t pad[S2_R / 2];
-};
-
-// byte offset of candidate rr inside the window of its row
-__device__ __forceinline__ int rec_off4(const S2Rec& r, int rr)
-{
-    return (rr & 1) ? (int)(r.offp[rr >> 1] >> 16) : (int)(r.offp[rr >> 1] & 0xFFFFu);
-}
-
-struct S2Shift {
-    int32_t w[S2_R];               // Topt[i][j0+rr] itself, -1 where there is no candidate
-};                                 // (read by the row-by-row path only)
-
-struct S2Info {
-    int32_t mins, maxs;            // over the valid shifts of the record; maxs = -1: none
-};
-
-// one entry per (level, instance); level = group * R + row-in-group
-struct S2Entry {
-    int32_t cnt;                   // number of strips (tasks)
-    int32_t prev;                  // entry that must be complete first, -1: none
-    int32_t prev_cnt;              // number of tasks of that entry
-    int32_t g;                     // >= 0: whole group, ghost width; -1: one row
-};
-
-struct S2Task {
-    int32_t entry, strip;          // in ticket order
-};
-
-struct S2Layout {
-    size_t done_off, entry_off, group_off, task_off, rec_off, info_off, shift_off, total;
-    long long nentries, maxtasks;
-};
-
-static S2Layout s2_layout(int B, int L, int P)
-{
-    S2Layout l;
-    const size_t nq = ((size_t)L + S2_R - 1) / S2_R;
-    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-    l.nentries = (long long)nq * S2_R * B;
-    // most tasks arise when every group runs row by row with the narrowest strips
-    l.maxtasks = l.nentries * (((long long)P + 255) / 256);
-    l.done_off = sizeof(S2Header);
-    l.entry_off = up(l.done_off + 4 * (size_t)l.nentries);
-    l.group_off = up(l.entry_off + sizeof(S2Entry) * ((size_t)l.nentries + 1));
-    l.task_off = up(l.group_off + 4 * (size_t)B * nq);
-    l.rec_off = up(l.task_off + sizeof(S2Task) * (size_t)l.maxtasks);
-    l.info_off = up(l.rec_off + sizeof(S2Rec) * (size_t)B * nq * (L + 1));
-    l.shift_off = up(l.info_off + sizeof(S2Info) * (size_t)B * nq * (L + 1));
-    l.total = up(l.shift_off + sizeof(S2Shift) * (size_t)B * nq * (L + 1));
-    return l;
-}
-
-size_t stage2_tiled_workspace_bytes(int B, int L, int P) { return s2_layout(B, L, P).total; }
-
-__global__ void stage2_clear_kernel(uint32_t* w, int n)
-{
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) w[i] = 0;
-}
-
-hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
-{
-    hipLaunchKernelGGL(stage2_clear_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st,
-                       (uint32_t*)p, nwords);
-    return hipGetLastError();
-}
-
-// One record per (instance b, row group q, predecessor i): the candidates that
-// row i offers to the rows j0..j0+R-1 of the group (j0 = 1 + q*R).  A candidate
-// exists when i < j, j <= L and 0 <= Topt[i][j] < P.  Shifts are stored as
-// offsets below the largest shift of the record, the position of the candidate
-// inside the LDS window of row i; a missing candidate has importance -inf and
-// so never wins whatever it is added to.  The workgroup also decides how the
-// group runs: groups[b][q] = ghost width g if every spread and every shift
-// inside the group fits dmax and g <= gmax, else -1 (row by row).
-__global__ __launch_bounds__(256) void stage2_pack_kernel(
-    int L, int P, int NQ, const int32_t* __restrict__ Topt, const float* __restrict__ I,
-    S2Rec* __restrict__ recs, S2Info* __restrict__ infos, S2Shift* __restrict__ shifts,
-    int32_t* __restrict__ groups, int gmax, int dmax, int wcap)
-{
-    __shared__ int wd[S2_R][S2_R];
-    __shared__ int viol;
-    const int ld = L + 1;
-    const int i = threadIdx.x;             // L <= 255: one thread per predecessor
-    const int q = blockIdx.x;
-    const int b = blockIdx.y;
-    const int j0 = 1 + q * S2_R;
-    const int32_t* To = Topt + (size_t)b * ld * ld;
-    const float* Ib = I + (size_t)b * ld * ld;
-    if (i == 0) viol = 0;
-    __syncthreads();
-    S2Rec rec;
-    int wv[S2_R];
-    int mins = 0x7FFFFFFF, maxs = -1;
-#pragma unroll
-    for (int rr = 0; rr < S2_R; ++rr) {
-        const int j = j0 + rr;
-        int w = -1;
-        float imp = -INFINITY;
-        if (i < ld && j <= L && i < j) {
-            const int v = To[i * ld + j];
-            if (v >= 0 && v < P) {
-                w = v;
-                imp = Ib[i * ld + j];
-                mins = min(mins, w);
-                maxs = max(maxs, w);
-            }
-        }
-        wv[rr] = w;
-        rec.imp[rr] = imp;
-    }
-#pragma unroll
-    for (int rr = 0; rr < S2_R / 2; ++rr) {
-        // a spread beyond dmax sends the group to the row-by-row path, which does
-        // not use these offsets: clamp so that the halves cannot overflow
-        const uint32_t lo = wv[2 * rr] < 0 ? 0u : (uint32_t)min(maxs - wv[2 * rr], 16383) * 4u;
-        const uint32_t hi = wv[2 * rr + 1] < 0 ? 0u : (uint32_t)min(maxs - wv[2 * rr + 1], 16383) * 4u;
-        rec.offp[rr] = lo | (hi << 16);
-        rec.pad[rr] = 0;
-    }
-    if (i < ld) {
-        const size_t idx = ((size_t)b * NQ + q) * ld + i;
-        recs[idx] = rec;
-        infos[idx].mins = mins;
-        infos[idx].maxs = maxs;
-#pragma unroll
-        for (int rr = 0; rr < S2_R; ++rr) shifts[idx].w[rr] = wv[rr];
-    }
-    if (i < j0 && maxs >= 0 && maxs - mins > dmax) viol = 1;
-    if (i >= j0 && i < j0 + S2_R) {
-#pragma unroll
-        for (int rr = 0; rr < S2_R; ++rr) wd[i - j0][rr] = wv[rr];
-    }
-    __syncthreads();
-    if (i == 0) {
-        // how far to the left of its stored columns each row must be correct
-        int need[S2_R];
-        int g = 0, hmax = 0;
-        for (int rr = S2_R - 1; rr >= 0; --rr) {
-            int n = 0;
-            for (int r2 = rr + 1; r2 < S2_R; ++r2)
-                if (wd[rr][r2] >= 0) {
-                    n = max(n, wd[rr][r2] + need[r2]);
-                    hmax = max(hmax, wd[rr][r2]);
-                }
-            need[rr] = n;
-            g = max(g, n);
-        }
-        // a table that fits one task has no strip to its left: no ghost columns
-        const bool bad = viol || hmax > dmax || (P > wcap && g > gmax);
-        groups[(size_t)b * NQ + q] = bad ? -1 : g;
-    }
-}
-
-// Task table: entries in ticket order (level-major, then instance), the task
-// list (entry and strip of every ticket) and the total.  One workgroup walks
-// the entries in tiles of 1024, one entry per thread (so that its stores are
-// coalesced), with a running prefix sum of the strip counts: wave scan, then
-// one combine of the 16 wave totals per tile.  The per-group decisions are
-// first brought into LDS when they fit.
-constexpr int S2_LAYOUT_CACHE = 12288;
-__global__ __launch_bounds__(1024) void stage2_layout_kernel(
-    int B, int L, int P, int NQ, int wcap, const int32_t* __restrict__ groups,
-    S2Entry* __restrict__ entries, S2Task* __restrict__ tasks, S2Header* hdr)
-{
-    __shared__ int wsum[2][16];
-    __shared__ int gcache[S2_LAYOUT_CACHE];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int N = NQ * S2_R * B;
-    const bool cached = B * NQ <= S2_LAYOUT_CACHE;
-    if (cached)
-        for (int x = tid; x < B * NQ; x += 1024) gcache[x] = groups[x];
-    __syncthreads();
-    auto group_of = [&](int b, int q) { return cached ? gcache[b * NQ + q] : groups[(size_t)b * NQ + q]; };
-    auto count = [&](int b, int q, int sub) {
-        const int hq = min(S2_R, L - q * S2_R);
-        const int grp = group_of(b, q);
-        // the first strip starts at t = 0 and has no ghost columns
-        if (grp >= 0)
-            return sub != 0 ? 0 : P <= wcap ? 1 : 1 + (P - wcap + (wcap - grp) - 1) / (wcap - grp);
-        return sub < hq ? (P + wcap - 1) / wcap : 0;
-    };
-    int base = 0;                                   // tickets before this tile
-    for (int e0 = 0, it = 0; e0 < N; e0 += 1024, ++it) {
-        const int e = e0 + tid;
-        int c = 0, prev = -1, prev_cnt = 0, g = -1;
-        if (e < N) {
-            const int level = e / B, b = e - level * B;
-            const int q = level / S2_R, sub = level % S2_R;
-            c = count(b, q, sub);
-            const int grp = group_of(b, q);
-            g = grp >= 0 && sub == 0 ? grp : -1;
-            if (sub > 0) {
-                prev = e - B;
-                prev_cnt = count(b, q, sub - 1);
-            } else if (q > 0) {
-                const int psub = group_of(b, q - 1) >= 0 ? 0 : S2_R - 1;
-                prev = ((q - 1) * S2_R + psub) * B + b;
-                prev_cnt = count(b, q - 1, psub);
-            }
-        }
-        // inclusive scan of c inside the wave
-        int incl = c;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int v = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += v;
-        }
-        if (lane == 63) wsum[it & 1][wave] = incl;
-        __syncthreads();
-        int before = 0, tile_total = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            const int v = wsum[it & 1][w];
-            if (w < wave) before += v;
-            tile_total += v;
-        }
-        const int tstart = base + before + incl - c;
-        if (e < N) {
-            S2Entry en;
-            en.cnt = c;
-            en.prev = prev;
-            en.prev_cnt = prev_cnt;
-            en.g = g;
-            entries[e] = en;
-            for (int x = 0; x < c; ++x) {
-                S2Task t;
-                t.entry = e;
-                t.strip = x;
-                tasks[tstart + x] = t;
-            }
-        }
-        base += tile_total;
-    }
-    if (tid == 0) hdr->total = (uint32_t)base;
-}
 
 // Optional phase timers (build with -DDPC_S2_TIMERS): thread 0 of every
 // workgroup accumulates wall-clock ticks (100 MHz) per phase and adds them to
@@ -315,29 +59,6 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
 #define TACC(slot, a, b) do {} while (0)
 #endif
 
-__device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// M and K travel between workgroups on different compute units (and L2
-// slices): they are written with agent-scope stores, which go through to the
-// level every compute unit sees, and read back with agent-scope loads, which
-// do not use a copy cached before the write.  A task counts as complete once
-// the vector-memory counter of every wave has drained (the stores have been
-// acknowledged) and the completion counter has then been incremented.
-__device__ __forceinline__ void st_agent(float* p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_agent(uint8_t* p, uint8_t v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_agent(const float* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 // Workgroup barrier that orders LDS accesses only.  The vector-memory counter
 // is left alone, so global -> LDS copies for later chunks stay in flight
 // across it; the copies a barrier must cover are waited for explicitly
@@ -348,28 +69,6 @@ __device__ __forceinline__ void lds_barrier()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
-constexpr int DMA_AGENT_SCOPE = 16;        // cache-policy bit sc1 of the global -> LDS load
-
-// Wait until at most `later` of the vector-memory operations this wave has
-// issued are still outstanding.  They complete in order, so this waits for
-// everything issued before the last `later` ones.  A smaller number only waits
-// longer, so the count is clamped to what the instruction can encode here.
-__device__ __forceinline__ void wait_vm(int later)
-{
-    // s_waitcnt immediates: vmcnt in bits 3:0 (and 15:14), expcnt 6:4 and lgkmcnt 11:8 left alone
-    switch (later) {
-        case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-        case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
-        case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
-        case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
-        case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
-        case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
-        case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
-        case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
-        default: __builtin_amdgcn_s_waitcnt(0x0F78); break;
-    }
-}
-
 // Copy the part x in [x0, x0 + 256*NGK) of the window tp in [lo, lo + n) of a
 // row of M into slot[0..n): -inf for tp < 0, nothing for tp >= tlimit.  Run by
 // one wave; the window is cut into 16-byte groups, one per lane and pass.  A
@@ -538,18 +237,6 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
         const S2Shift* bshift = shifts + ((size_t)b * NQ + q) * ld;
         TMARK(t_b);
         TACC(3, t_a, t_b);
-
-        // row 0, the base case, is written by the first level
-        if (q == 0 && rlo == 0) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = tS + tl0 + 64 * u;
-                if (t >= t0 && t < tstore_end) {
-                    st_agent(Mb + t, 0.0f);
-                    if (STORE_K) st_agent(Kb + t, (uint8_t)DPC_NOARG);
-                }
-            }
-        }
 
         float best[R][U];
         int arg[R][U];
@@ -810,29 +497,19 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     const int NQ = (L + S2_R - 1) / S2_R;
     const S2Layout lay = s2_layout(B, L, P);
     if (lay.nentries > 0x3FFFFFF0LL || lay.maxtasks > 0x3FFFFFF0LL) return hipErrorInvalidValue;
-    const int N = (int)lay.nentries;
     char* base = (char*)workspace;
     S2Header* hdr = (S2Header*)base;
     uint32_t* done = (uint32_t*)(base + lay.done_off);
     S2Entry* entries = (S2Entry*)(base + lay.entry_off);
     S2Task* tasks = (S2Task*)(base + lay.task_off);
-    int32_t* groups = (int32_t*)(base + lay.group_off);
     S2Rec* recs = (S2Rec*)(base + lay.rec_off);
     S2Info* infos = (S2Info*)(base + lay.info_off);
     S2Shift* shifts = (S2Shift*)(base + lay.shift_off);
 
-    hipError_t e = launch_clear_words(workspace, (int)(sizeof(S2Header) / 4) + N, st);
-    if (e != hipSuccess) return e;
     // ghost columns cost recomputation: at most a quarter of a task, and the
     // chain of shifts must fit the pad in front of a diagonal slot
     const int gmax = std::min(DMAX, WCAP / 4);
-    hipLaunchKernelGGL(stage2_pack_kernel, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I, recs,
-                       infos, shifts, groups, gmax, DMAX, WCAP);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(stage2_layout_kernel, dim3(1), dim3(1024), 0, st, B, L, P, NQ, WCAP, groups,
-                       entries, tasks, hdr);
-    e = hipGetLastError();
+    hipError_t e = launch_stage2_prepare(B, L, P, Topt, I, M, K, workspace, gmax, DMAX, WCAP, 0, st);
     if (e != hipSuccess) return e;
 
     // resident workgroups per compute unit: WPE waves per SIMD, 4 SIMDs

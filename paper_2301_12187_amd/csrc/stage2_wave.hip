@@ -1,0 +1,496 @@
+// Stage 2, persistent family with wave-private windows (Algorithm 2 /
+// recurrence Eq. 7 of the paper): M[j][t] = max_i fl32(M[i][t - Topt[i][j]] +
+// I[i][j]), lowest arg-max.
+//
+// Tasks, ghost columns, ticket order, completion counters and the row-by-row
+// fallback are those of the LDS-tiled family (stage2_tiled.hip): a task is
+// (instance, group of R = 8 rows, strip of WCAP = NW*64*U columns), it keeps
+// the R x WCAP running (maximum, arg-max) pairs in registers, reads rows below
+// its group from global memory and writes its own rows.
+//
+// What differs is the off-diagonal part.  Every wave owns 64*U consecutive
+// columns and feeds itself: for predecessor row i it copies the window of
+// that row that ITS columns need, [tW - maxshift_i, tW + 64*U - minshift_i),
+// into a slot of its own ring in LDS (global -> LDS loads, 16 bytes per lane,
+// no registers), NSLOT-1 rows ahead of the row it is relaxing.  Nothing in this
+// part is shared between waves, so there is no workgroup barrier in it: a wave
+// waits only for its own loads, with a counted wait that leaves the loads of
+// the rows ahead in flight.  To make that count exact every row issues the
+// same number of loads with every lane active and no branch around them:
+//   - the window start is rounded down to a multiple of 4 columns, so a
+//     16-byte cell lies entirely below column 0 or entirely at or above it;
+//     cells below column 0 are fetched from sixteen bytes of -inf in the
+//     workspace header (those cells mean "no (A, S) reaches this budget");
+//   - cells past the part of the window that is needed are clamped to its
+//     last cell (the lanes then ask for the same 16 bytes);
+//   - the cell that straddles the end of the row reads up to three floats of
+//     the next row, which exists because a predecessor row is never row L;
+//     nothing that is stored depends on them.
+// A row that offers no candidate to the group is fetched all the same; its
+// importances are -inf in the records, so it never wins.
+//
+// The diagonal part (predecessors inside the group) is shared by the waves of
+// the workgroup as in the tiled family: a finished row goes to an LDS slot
+// (laid over the rings, which are idle by then) from which the rows below it
+// are relaxed, one workgroup barrier per row.
+#include "stage2_common.h"
+
+namespace dpc {
+
+// Optional phase timers (build with -DDPC_S2_TIMERS): lane 0 of wave 0 of every
+// workgroup accumulates wall-clock ticks (100 MHz) per phase and adds them to
+// the spare words of the workspace header.
+#ifdef DPC_S2_TIMERS
+#define TMARK(var) const long long var = wall_clock64()
+#define TACC(slot, a, b) do { if (tid == 0) tacc[slot] += (b) - (a); } while (0)
+#else
+#define TMARK(var) do {} while (0)
+#define TACC(slot, a, b) do {} while (0)
+#endif
+
+template <int NW, int U, int NSLOT, int DMAX, int WPE, bool STORE_K>
+__global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
+    int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* done,
+    const S2Entry* __restrict__ entries, const S2Task* __restrict__ tasks,
+    const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos,
+    const S2Shift* __restrict__ shifts, int NQ, long long wait_limit)
+{
+    constexpr int R = S2_R;
+    constexpr int NT = NW * 64;
+    constexpr int WV = 64 * U;                       // columns per wave
+    constexpr int WCAP = NW * WV;                    // columns per task
+    // a window holds at most WV + DMAX columns plus 3 of alignment slack
+    constexpr int NLD = (WV + DMAX + 3 + 255) / 256; // loads per row and wave
+    constexpr int SLOTF = NLD * 256;                 // floats per ring slot
+    constexpr int RINGF = NSLOT * SLOTF;             // floats per wave
+    constexpr int D = NSLOT - 1;                     // rows in flight ahead of the current one
+    constexpr int DSLOTW = WCAP + DMAX + 4;          // floats per diagonal slot
+    constexpr int LDSF = NW * RINGF > (R - 1) * DSLOTW ? NW * RINGF : (R - 1) * DSLOTW;
+    constexpr float NINF = -INFINITY;
+    static_assert(U % 2 == 0, "columns are read in pairs");
+    static_assert(D >= 1 && D * NLD <= 8, "the counted wait covers at most 8 loads");
+    static_assert(DMAX % 4 == 0, "diagonal slots stay 16-byte aligned");
+    __shared__ __attribute__((aligned(16))) float lds[LDSF];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ld = L + 1;
+    const int tl0 = wave * WV + lane;                // column of the task, u = 0
+    float* const ring = lds + wave * RINGF;
+    const char* const lbase = (const char*)(ring + lane);
+    const int tmaxg = (P - 1) & ~3;                  // last 16-byte cell that holds a column < P
+    const float* const ninf = hdr->ninf;
+    int* const sh_word = (int*)lds;                  // ticket broadcast (the rings are idle then)
+
+    const int total = (int)hdr->total;
+#ifdef DPC_S2_TIMERS
+    long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const long long tkernel0 = wall_clock64();
+#endif
+    for (;;) {
+        TMARK(t_a);
+        // ---- next ticket, its task, and the wait for the previous level of the
+        //      instance (all by one lane; the rest of the workgroup waits at the barrier)
+        if (tid == 0) {
+            const int ticket = (int)atomicAdd(&hdr->ticket, 1u);
+            int e = -1, strip = 0, g = -1, ok = 1, prev = -1, prev_cnt = 0, prev_row0 = -1;
+            if (ticket < total) {
+                const S2Task tk = tasks[ticket];
+                const S2Entry ent = entries[tk.entry];
+                e = tk.entry;
+                strip = tk.strip;
+                g = ent.g;
+                prev = ent.prev;
+                prev_cnt = ent.prev_cnt;
+                prev_row0 = ent.prev_row0;
+                // every row below prev_row0 is final once the entry before `prev`
+                // is complete; `prev` itself is waited for when its rows come up
+                if (ent.prev2 >= 0) {
+                    const uint32_t need = (uint32_t)ent.prev2_cnt;
+                    const uint32_t* flag = &done[ent.prev2];
+                    const long long start = wall_clock64();
+                    while (ld_relaxed(flag) < need) {
+                        if (ld_relaxed(&hdr->error) != 0) { ok = 0; break; }
+                        if (wall_clock64() - start > wait_limit) {
+                            __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                            ok = 0;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(2);
+                    }
+                }
+            }
+            sh_word[0] = ok ? e : -1;
+            sh_word[1] = strip;
+            sh_word[2] = g;
+            sh_word[3] = prev;
+            sh_word[4] = prev_cnt;
+            sh_word[5] = prev_row0;
+        }
+        __syncthreads();
+        const int e = __builtin_amdgcn_readfirstlane(sh_word[0]);
+        const int s = __builtin_amdgcn_readfirstlane(sh_word[1]);
+        const int entg = __builtin_amdgcn_readfirstlane(sh_word[2]);
+        const int prev = __builtin_amdgcn_readfirstlane(sh_word[3]);
+        const uint32_t prev_cnt = (uint32_t)__builtin_amdgcn_readfirstlane(sh_word[4]);
+        const int prev_row0 = __builtin_amdgcn_readfirstlane(sh_word[5]);
+        __syncthreads();
+#ifdef DPC_S2_TIMERS
+        if (e < 0 && tid == 0) {
+            tacc[7] = wall_clock64() - tkernel0;
+            for (int q = 0; q < 8; ++q)
+                atomicAdd((unsigned long long*)&hdr->pad[1 + 2 * q], (unsigned long long)tacc[q]);
+            atomicAdd(&hdr->pad[21], 1u);
+        }
+#endif
+        if (e < 0) return;                         // no ticket left, or a wait ran out: all leave
+        const int level = e / B;
+        const int b = e - level * B;
+        const int q = level / R;
+        const int sub = level - q * R;
+        const bool full = entg >= 0;
+        const int g = full && s > 0 ? entg : 0;    // the first strip has nothing to its left
+        const int j0 = 1 + q * R;
+        const int hq = min(R, ld - j0);
+        const int rlo = full ? 0 : sub;            // rows of the group this task computes
+        const int rhi = full ? hq : sub + 1;
+        const int ilimit = j0 + rlo;               // rows below come from global memory
+        const int weff = WCAP - g;
+        const int t0 = s == 0 ? 0 : WCAP + (s - 1) * weff;   // first stored column
+        const int tS = t0 - g;                     // first computed column
+        const int tend = min(tS + WCAP, P);
+        const int tstore_end = min(t0 + weff, P);
+        const int tW = tS + wave * WV;             // first column of this wave
+        float* Mb = M + (size_t)b * ld * P;
+        uint8_t* Kb = STORE_K ? K + (size_t)b * ld * P : nullptr;
+        const S2Rec* brec = recs + ((size_t)b * NQ + q) * ld;
+        const S2Info* binfo = infos + ((size_t)b * NQ + q) * ld;
+        const S2Shift* bshift = shifts + ((size_t)b * NQ + q) * ld;
+
+        float best[R][U];
+        int arg[R][U];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+            for (int u = 0; u < U; ++u) { best[rr][u] = NINF; arg[rr][u] = DPC_NOARG; }
+
+        // a wave whose columns all lie beyond the table has nothing to do but
+        // to take part in the barriers
+        const bool wave_idle = tW >= tend;
+
+        // Window of row i for this wave: the largest and smallest shift of the
+        // candidates it offers to the task (no candidate: any window will do).
+        // A whole-group task takes them from the records, a one-row task uses
+        // the shift of its row.
+        auto window_of = [&](int i, int& maxs, int& mins) __attribute__((always_inline)) {
+            if (full) {
+                const S2Info inf = binfo[i];
+                maxs = max(inf.maxs, 0);
+                mins = inf.maxs < 0 ? 0 : inf.mins;
+            } else {
+                int w = 0;
+                const S2Shift sh = bshift[i];
+#pragma unroll
+                for (int rr = 0; rr < R; ++rr)
+                    if (rr == sub) w = sh.w[rr];
+                maxs = mins = max(w, 0);
+            }
+        };
+
+        // Start the copy of the window of row i into ring slot `slot`: exactly
+        // NLD loads, every lane active.
+        auto issue_row = [&](int i, int slot, int maxs, int mins) __attribute__((always_inline)) {
+            const int lo = tW - maxs;
+            const int lo4 = lo & ~3;                               // floor to a multiple of 4
+            const int n4 = (WV + maxs - mins + (lo - lo4) + 3) & ~3;   // cells needed, in floats
+            const int last = min(tmaxg, lo4 + n4 - 4);             // last cell worth fetching
+            const float* row = Mb + (size_t)i * P;
+            float* dst = ring + slot * SLOTF;
+            if (lo4 >= 0) {
+#pragma unroll
+                for (int k = 0; k < NLD; ++k) {
+                    const int tp = min(lo4 + 256 * k + 4 * lane, last);
+                    __builtin_amdgcn_global_load_lds(row + tp, (lds_void*)(dst + 256 * k), 16, 0,
+                                                     DMA_AGENT_SCOPE);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < NLD; ++k) {
+                    const int tp = min(lo4 + 256 * k + 4 * lane, last);
+                    const float* src = tp < 0 ? ninf : row + tp;
+                    __builtin_amdgcn_global_load_lds(src, (lds_void*)(dst + 256 * k), 16, 0,
+                                                     DMA_AGENT_SCOPE);
+                }
+            }
+        };
+
+        // Relax all rows of the group from row i, whose window sits in `slot`.
+        // A candidate whose shift exceeds every column of the task reads the
+        // part of the window below column 0 (-inf); a missing candidate adds
+        // -inf to whatever its cell holds: neither needs a test here.
+        auto relax_whole = [&](int slot, const S2Rec& rec) __attribute__((always_inline)) {
+            const int i = (int)rec.pad[3];
+            const int delta = (tS - (int)rec.pad[0]) & 3;          // alignment slack of the window
+            const char* base = lbase + (slot * SLOTF + delta) * 4;
+            float mcur[U], mnxt[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                mcur[u] = *(const float*)(base + rec_off4(rec, 0) + 256 * u);
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) {
+                if (rr + 1 < R) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        mnxt[u] = *(const float*)(base + rec_off4(rec, rr + 1) + 256 * u);
+                }
+                const float imp = rec.imp[rr];
+                float cand[U];
+                bool win[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
+#pragma unroll
+                for (int u = 0; u < U; ++u) win[u] = cand[u] > best[rr][u];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    best[rr][u] = win[u] ? cand[u] : best[rr][u];
+                    arg[rr][u] = win[u] ? i : arg[rr][u];
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
+            }
+        };
+        // The same for a one-row task: only row `sub` of the group, at one shift.
+        auto relax_one = [&](int i, int slot) __attribute__((always_inline)) {
+            const S2Shift sh = bshift[i];
+            const S2Rec& rec = brec[i];
+            int w = -1;
+            float imp = NINF;
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr)
+                if (rr == sub) { w = sh.w[rr]; imp = rec.imp[rr]; }
+            if (w < 0) return;
+            const int delta = (tS - w) & 3;
+            const float* base = (const float*)(lbase + (slot * SLOTF + delta) * 4);
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) {
+                if (rr != sub) continue;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const float cand = base[64 * u] + imp;
+                    if (cand > best[rr][u]) { best[rr][u] = cand; arg[rr][u] = i; }
+                }
+            }
+        };
+
+        // The rows prev_row0 .. ilimit-1 are written by the tasks of entry `prev`,
+        // which may still be running: a wave waits for them right before it
+        // starts the copy of row prev_row0, by which time most of its work on
+        // the rows below is done.  A wait that runs out sets the error word and
+        // goes on (every access stays in bounds whatever the rows hold).
+        auto wait_prev = [&]() __attribute__((always_inline)) {
+            const uint32_t* flag = &done[prev];
+            const long long start = wall_clock64();
+            while (ld_relaxed(flag) < prev_cnt) {
+                if (ld_relaxed(&hdr->error) != 0) break;
+                if (wall_clock64() - start > wait_limit) {
+                    __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(2);
+            }
+        };
+
+        // ---------------- off-diagonal part: rows i < ilimit ----------------
+        TMARK(t_b);
+        TACC(3, t_a, t_b);
+        if (!wave_idle) {
+#pragma unroll
+            for (int d = 0; d < D; ++d)
+                if (d < ilimit) {
+                    if (d == prev_row0) wait_prev();
+                    int maxs, mins;
+                    window_of(d, maxs, mins);
+                    issue_row(d, d, maxs, mins);
+                }
+            int slot = 0;                              // ring slot of row i
+            int ahead = D;                             // ring slot of row i + D
+            if (full) {
+                S2Rec cur = brec[0];
+                for (int i = 0; i < ilimit; ++i) {
+                    TMARK(ta);
+                    const S2Rec nxt = brec[min(i + 1, L)];
+                    // the loads of the D rows ahead stay in flight; past the last
+                    // row there is nothing left to start and nothing to leave
+                    if (i + D < ilimit) {
+                        if (i + D == prev_row0) wait_prev();
+                        issue_row(i + D, ahead, (int)cur.pad[1], (int)cur.pad[2]);
+                        wait_vm(D * NLD);
+                    } else {
+                        wait_vm(0);
+                    }
+                    asm volatile("" ::: "memory");             // row i has landed
+                    TMARK(tb);
+                    relax_whole(slot, cur);
+                    TMARK(tc);
+                    TACC(0, ta, tb);
+                    TACC(2, tb, tc);
+                    cur = nxt;
+                    ahead = slot;
+                    slot = slot + 1 == NSLOT ? 0 : slot + 1;
+                }
+            } else {
+                for (int i = 0; i < ilimit; ++i) {
+                    if (i + D < ilimit) {
+                        if (i + D == prev_row0) wait_prev();
+                        int maxs, mins;
+                        window_of(i + D, maxs, mins);
+                        issue_row(i + D, ahead, maxs, mins);
+                        wait_vm(D * NLD);
+                    } else {
+                        wait_vm(0);
+                    }
+                    asm volatile("" ::: "memory");
+                    relax_one(i, slot);
+                    ahead = slot;
+                    slot = slot + 1 == NSLOT ? 0 : slot + 1;
+                }
+            }
+        }
+        TMARK(t_c);
+        __syncthreads();                               // every ring is idle: the slots below lie over them
+        TMARK(t_c2);
+        TACC(1, t_c, t_c2);
+        if (full && tS == 0) {
+            // first strip: what lies to the left of column 0 does not exist
+            for (int x = tid; x < (R - 1) * DMAX; x += NT) {
+                const int rr = x / DMAX;
+                lds[rr * DSLOTW + (x - rr * DMAX)] = NINF;
+            }
+        }
+
+        // ---------------- diagonal part and output ----------------
+        // records of the group's own rows, fetched four at a time
+        S2Rec drec[4];
+        auto load_diag = [&](int first) __attribute__((always_inline)) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) drec[c] = brec[min(j0 + first + c, L)];
+        };
+        if (full && !wave_idle) load_diag(0);
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            const int j = j0 + rr;
+            if (rr >= rlo && rr < rhi) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int t = tS + tl0 + 64 * u;
+                    if (t >= t0 && t < tstore_end) {
+                        st_agent(Mb + (size_t)j * P + t, best[rr][u]);
+                        if (STORE_K) st_agent(Kb + (size_t)j * P + t, (uint8_t)arg[rr][u]);
+                    }
+                }
+            }
+            if (rr + 1 < R) {
+                // row j of a whole-group task feeds the rows below it through an LDS
+                // slot: own column t at slot position DMAX + (t - tS)
+                const bool feeds = full && rr + 1 < rhi;
+                float* slot = lds + rr * DSLOTW;
+                if (feeds) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) slot[DMAX + tl0 + 64 * u] = best[rr][u];
+                }
+                __syncthreads();
+                if (feeds && !wave_idle) {
+                    const S2Rec& rec = drec[rr & 3];
+                    // (a row of the group that offers no candidate has -inf importances)
+                    const int maxs = (int)rec.pad[0];
+#pragma unroll
+                    for (int r2 = rr + 1; r2 < R; ++r2) {
+                        // shifts inside a group are at most DMAX: a shift beyond
+                        // the task's last column can only occur in the first
+                        // strip, whose pad holds -inf
+                        const int w = maxs - (rec_off4(rec, r2) >> 2);
+                        const float imp = rec.imp[r2];
+                        const float* sp = &slot[DMAX - w + tl0];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const float cand = sp[64 * u] + imp;
+                            if (cand > best[r2][u]) { best[r2][u] = cand; arg[r2][u] = j; }
+                        }
+                    }
+                    if (rr == 3) load_diag(4);
+                }
+            }
+        }
+
+        TMARK(t_d);
+        TACC(4, t_c2, t_d);
+        // ---- publish: one more task of this entry is complete
+        wait_vm(0);                                    // this wave's stores are acknowledged
+        __syncthreads();                               // ... every wave's; the LDS is free again
+        if (tid == 0)
+            __hip_atomic_fetch_add(&done[e], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        TMARK(t_e);
+        TACC(5, t_d, t_e);
+    }
+}
+
+template <int NW, int U, int NSLOT, int DMAX, int WPE>
+static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
+                                  uint8_t* K, void* workspace, int num_cu, hipStream_t st)
+{
+    constexpr int WCAP = NW * 64 * U;
+    const int NQ = (L + S2_R - 1) / S2_R;
+    const S2Layout lay = s2_layout(B, L, P);
+    char* base = (char*)workspace;
+    S2Header* hdr = (S2Header*)base;
+    uint32_t* done = (uint32_t*)(base + lay.done_off);
+    S2Entry* entries = (S2Entry*)(base + lay.entry_off);
+    S2Task* tasks = (S2Task*)(base + lay.task_off);
+    S2Rec* recs = (S2Rec*)(base + lay.rec_off);
+    S2Info* infos = (S2Info*)(base + lay.info_off);
+    S2Shift* shifts = (S2Shift*)(base + lay.shift_off);
+
+    // ghost columns cost recomputation: at most a quarter of a task, and the
+    // chain of shifts must fit the pad in front of a diagonal slot
+    const int gmax = std::min(DMAX, WCAP / 4);
+    hipError_t e = launch_stage2_prepare(B, L, P, Topt, I, M, K, workspace, gmax, DMAX, WCAP, NSLOT - 1, st);
+    if (e != hipSuccess) return e;
+
+    // resident workgroups per compute unit: WPE waves per SIMD, 4 SIMDs
+    constexpr int wg_per_cu = (WPE * 4) / NW;
+    static_assert(wg_per_cu >= 1, "a workgroup must fit one compute unit");
+    const int grid = num_cu * wg_per_cu;
+    const long long wait_limit = 500000000LL;      // 5 s of the 100 MHz wall clock
+    if (K)
+        hipLaunchKernelGGL((stage2_wave_kernel<NW, U, NSLOT, DMAX, WPE, true>), dim3(grid),
+                           dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
+                           infos, shifts, NQ, wait_limit);
+    else
+        hipLaunchKernelGGL((stage2_wave_kernel<NW, U, NSLOT, DMAX, WPE, false>), dim3(grid),
+                           dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
+                           infos, shifts, NQ, wait_limit);
+    return hipGetLastError();
+}
+
+int g_s2w_shape = 0;    // tuning override, see launch_stage2_wave
+
+hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
+                              uint8_t* K, void* workspace, int num_cu, hipStream_t st)
+{
+    // a window cell may read up to three floats past the end of a row
+    if (P < 16) return hipErrorInvalidValue;
+    int shape = g_s2w_shape;
+    if (shape == 0) shape = P <= 256 ? 4 : P <= 512 ? 3 : 1;
+    switch (shape) {
+        case 1: return launch_wave_cfg<4, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 2: return launch_wave_cfg<8, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 3: return launch_wave_cfg<2, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 4: return launch_wave_cfg<1, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 5: return launch_wave_cfg<4, 2, 8, 124, 6>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace dpc

@@ -10,8 +10,9 @@ from gpu_common import compare, run_gpu, run_oracle
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [1, 2]
-SHAPES = [21, 22, 23, 24, 25, 26]      # every task shape of the tiled kernel
+VARIANTS = [1, 2, 3]
+SHAPES = [21, 22, 23, 24, 25, 26,      # every task shape of the tiled kernel
+          31, 32, 33, 34, 35]          # ... and of the wave-window kernel
 
 
 def _all_budgets(B, P, step=1):
@@ -145,7 +146,7 @@ def test_config3_batch(variant):
     compare(g, r, cfg.L, cfg.name)
 
 
-@pytest.mark.parametrize("variant", VARIANTS + [24, 26])
+@pytest.mark.parametrize("variant", VARIANTS + [24, 26, 31, 32, 35])
 def test_config4_batch(variant):
     cfg = inputs.CONFIGS[4]
     T, I, base = inputs.make_batch(cfg, seed=0)
