@@ -46,7 +46,7 @@ const char* dpc_status_string(int code)
 int dpc_set_stage2_variant(int variant)
 {
     if (!((variant >= 0 && variant <= 3) || (variant >= 21 && variant <= 26) ||
-          (variant >= 31 && variant <= 35)))
+          (variant >= 31 && variant <= 37)))
         return DPC_ERR_SHAPE;
     int prev = g_stage2_variant;
     g_stage2_variant = variant;
@@ -67,7 +67,7 @@ int dpc_stage1_minplus(int32_t B, int32_t L, const int32_t* T, int32_t* Topt, ui
 size_t dpc_stage2_workspace_bytes(int32_t B, int32_t L, int32_t P)
 {
     if (!shape_ok(B, L, P)) return 0;
-    return dpc::stage2_tiled_workspace_bytes(B, L, P);
+    return dpc::stage2_workspace_bytes(B, L, P);
 }
 
 int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const float* I,

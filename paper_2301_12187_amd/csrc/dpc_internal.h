@@ -13,7 +13,7 @@ hipError_t launch_stage2_rows(int B, int L, int P, const int32_t* Topt, const fl
                               float* M, uint8_t* K, hipStream_t st);
 // zero `nwords` 32-bit words with a small kernel (safe to record into a HIP graph)
 hipError_t launch_clear_words(void* p, int nwords, hipStream_t st);
-size_t stage2_tiled_workspace_bytes(int B, int L, int P);
+size_t stage2_workspace_bytes(int B, int L, int P);
 hipError_t launch_stage2_tiled(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                                uint8_t* K, void* workspace, int num_cu, hipStream_t st);
 hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const float* I, float* M,

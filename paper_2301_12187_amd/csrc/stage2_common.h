@@ -10,7 +10,8 @@ namespace dpc {
 
 typedef __attribute__((address_space(3))) void lds_void;
 
-constexpr int S2_R = 8;            // rows per group (record layout depends on it)
+constexpr int S2_H = 8;            // rows per operand record; a group has 8 or 16 rows
+constexpr int S2_R = 8;            // rows per group of the LDS-tiled family
 
 struct S2Header {
     uint32_t ticket;
@@ -24,13 +25,15 @@ struct S2Header {
 static_assert(sizeof(S2Header) == 256, "header is one 256-byte block");
 
 struct __attribute__((aligned(64))) S2Rec {
-    uint32_t offp[S2_R / 2];       // 4 * (maxs - Topt[i][j0+rr]) as 16-bit halves (rr even: low),
+    uint32_t offp[S2_H / 2];       // 4 * (maxs - Topt[i][j0+rr]) as 16-bit halves (rr even: low),
                                    // the byte offset of the candidate in the LDS window of row
                                    // i; 0 where there is no candidate
-    float imp[S2_R];               // I[i][j0+rr]; -inf where there is no candidate
-    uint32_t pad[S2_R / 2];        // [0]: largest shift of the record; [1], [2]: largest and
+    float imp[S2_H];               // I[i][j0+rr]; -inf where there is no candidate
+    uint32_t pad[S2_H / 2];        // [0]: largest shift of the record; [1], [2]: largest and
                                    // smallest shift of the record `ahead` rows further on
-                                   // (0 where a record holds no candidate); [3]: i
+                                   // (0 where a record holds no candidate); [3]: i.  In a
+                                   // group of 16 rows the offsets of both records count from
+                                   // the largest shift of the sixteen, and so do these
 };
 
 // byte offset of candidate rr inside the window of its row
@@ -40,7 +43,7 @@ __device__ __forceinline__ int rec_off4(const S2Rec& r, int rr)
 }
 
 struct S2Shift {
-    int32_t w[S2_R];               // Topt[i][j0+rr] itself, -1 where there is no candidate
+    int32_t w[S2_H];               // Topt[i][j0+rr] itself, -1 where there is no candidate
 };                                 // (read by the row-by-row path only)
 
 struct S2Info {
@@ -68,21 +71,28 @@ struct S2Layout {
     long long nentries, maxtasks;
 };
 
-S2Layout s2_layout(int B, int L, int P);
+S2Layout s2_layout(int B, int L, int P, int R);
 
 // Queues the kernels that prepare a stage-2 launch on `st`: clears the header
 // and the completion counters, writes row 0 of M (and K), repacks Topt and I
-// into records for row groups of S2_R rows and decides per group whether it
+// into records for row groups of R (8 or 16) rows and decides per group whether it
 // runs whole (ghost width <= gmax, every spread and every shift inside the
 // group <= dmax) or row by row, and lays out the task table for strips of
 // `wcap` columns.  `ahead`: see S2Rec::pad.
-hipError_t launch_stage2_prepare(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
-                                 uint8_t* K, void* workspace, int gmax, int dmax, int wcap,
-                                 int ahead, hipStream_t st);
+hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt, const float* I,
+                                 float* M, uint8_t* K, void* workspace, int gmax, int dmax,
+                                 int wcap, int ahead, hipStream_t st);
 
 __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The same for wave-uniform code: every lane loads the word, the value of the
+// first lane is used, so what depends on it stays wave-uniform (scalar branches).
+__device__ __forceinline__ uint32_t ld_uniform(const uint32_t* p)
+{
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)ld_relaxed(p));
 }
 
 // M and K travel between workgroups on different compute units (and L2

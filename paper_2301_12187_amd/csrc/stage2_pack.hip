@@ -4,12 +4,13 @@
 
 namespace dpc {
 
-S2Layout s2_layout(int B, int L, int P)
+S2Layout s2_layout(int B, int L, int P, int R)
 {
     S2Layout l;
-    const size_t nq = ((size_t)L + S2_R - 1) / S2_R;
+    const size_t nq = ((size_t)L + R - 1) / R;
+    const size_t halves = (size_t)R / S2_H;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-    l.nentries = (long long)nq * S2_R * B;
+    l.nentries = (long long)nq * R * B;
     // most tasks arise when every group runs row by row with the narrowest strips
     l.maxtasks = l.nentries * (((long long)P + 255) / 256);
     l.done_off = sizeof(S2Header);
@@ -17,13 +18,17 @@ S2Layout s2_layout(int B, int L, int P)
     l.group_off = up(l.entry_off + sizeof(S2Entry) * ((size_t)l.nentries + 1));
     l.task_off = up(l.group_off + 4 * (size_t)B * nq);
     l.rec_off = up(l.task_off + sizeof(S2Task) * (size_t)l.maxtasks);
-    l.info_off = up(l.rec_off + sizeof(S2Rec) * (size_t)B * nq * (L + 1));
+    l.info_off = up(l.rec_off + sizeof(S2Rec) * halves * B * nq * (L + 1));
     l.shift_off = up(l.info_off + sizeof(S2Info) * (size_t)B * nq * (L + 1));
-    l.total = up(l.shift_off + sizeof(S2Shift) * (size_t)B * nq * (L + 1));
+    l.total = up(l.shift_off + sizeof(S2Shift) * halves * B * nq * (L + 1));
     return l;
 }
 
-size_t stage2_tiled_workspace_bytes(int B, int L, int P) { return s2_layout(B, L, P).total; }
+// (the caller sizes the workspace before a kernel family is chosen)
+size_t stage2_workspace_bytes(int B, int L, int P)
+{
+    return std::max(s2_layout(B, L, P, 8).total, s2_layout(B, L, P, 16).total);
+}
 
 __global__ void stage2_clear_kernel(uint32_t* w, int n)
 {
@@ -39,28 +44,31 @@ hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
 }
 
 // One record per (instance b, row group q, predecessor i): the candidates that
-// row i offers to the rows j0..j0+R-1 of the group (j0 = 1 + q*R).  A candidate
-// exists when i < j, j <= L and 0 <= Topt[i][j] < P.  Shifts are stored as
-// offsets below the largest shift of the record, the position of the candidate
-// inside the LDS window of row i; a missing candidate has importance -inf and
-// so never wins whatever it is added to.  The workgroups of the first group
-// also write row 0 of M (and K).  The workgroup also decides how the
-// group runs: groups[b][q] = ghost width g if every spread and every shift
-// inside the group fits dmax and g <= gmax, else -1 (row by row).
+// row i offers to the rows j0..j0+R-1 of the group (j0 = 1 + q*R), stored as
+// R/8 consecutive S2Rec of eight rows each.  A candidate exists when i < j,
+// j <= L and 0 <= Topt[i][j] < P.  Shifts are stored as offsets below the
+// largest shift of the record, the position of the candidate inside the LDS
+// window of row i; a missing candidate has importance -inf and so never wins
+// whatever it is added to.  The workgroups of the first group also write row
+// 0 of M (and K).  The workgroup also decides how the group runs:
+// groups[b][q] = ghost width g if every spread and every shift inside the
+// group fits dmax and g <= gmax, else -1 (row by row).
+template <int R>
 __global__ __launch_bounds__(256) void stage2_pack_kernel(
     int L, int P, int NQ, const int32_t* __restrict__ Topt, const float* __restrict__ I,
     S2Rec* __restrict__ recs, S2Info* __restrict__ infos, S2Shift* __restrict__ shifts,
     int32_t* __restrict__ groups, int gmax, int dmax, int wcap, int ahead,
     float* __restrict__ M, uint8_t* __restrict__ K)
 {
-    __shared__ int wd[S2_R][S2_R];
+    constexpr int H = R / S2_H;            // records per (group, predecessor)
+    __shared__ int wd[R][R];
     __shared__ int smax[256], smin[256];
     __shared__ int viol;
     const int ld = L + 1;
     const int i = threadIdx.x;             // L <= 255: one thread per predecessor
     const int q = blockIdx.x;
     const int b = blockIdx.y;
-    const int j0 = 1 + q * S2_R;
+    const int j0 = 1 + q * R;
     const int32_t* To = Topt + (size_t)b * ld * ld;
     const float* Ib = I + (size_t)b * ld * ld;
     if (i == 0) viol = 0;
@@ -74,11 +82,11 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
             for (int t = i; t < P; t += 256) K0[t] = (uint8_t)DPC_NOARG;
         }
     }
-    S2Rec rec;
-    int wv[S2_R];
+    S2Rec rec[H];
+    int wv[R];
     int mins = 0x7FFFFFFF, maxs = -1;
 #pragma unroll
-    for (int rr = 0; rr < S2_R; ++rr) {
+    for (int rr = 0; rr < R; ++rr) {
         const int j = j0 + rr;
         int w = -1;
         float imp = -INFINITY;
@@ -92,16 +100,15 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
             }
         }
         wv[rr] = w;
-        rec.imp[rr] = imp;
+        rec[rr / S2_H].imp[rr % S2_H] = imp;
     }
 #pragma unroll
-    for (int rr = 0; rr < S2_R / 2; ++rr) {
+    for (int rr = 0; rr < R / 2; ++rr) {
         // a spread beyond dmax sends the group to the row-by-row path, which does
         // not use these offsets: clamp so that the halves cannot overflow
         const uint32_t lo = wv[2 * rr] < 0 ? 0u : (uint32_t)min(maxs - wv[2 * rr], 16383) * 4u;
         const uint32_t hi = wv[2 * rr + 1] < 0 ? 0u : (uint32_t)min(maxs - wv[2 * rr + 1], 16383) * 4u;
-        rec.offp[rr] = lo | (hi << 16);
-        rec.pad[rr] = 0;
+        rec[rr / (S2_H / 2)].offp[rr % (S2_H / 2)] = lo | (hi << 16);
     }
     // the window of row i that the group needs (none: any window will do),
     // and that of the row `ahead` rows further on, whose copy a kernel starts
@@ -109,31 +116,35 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     smax[i] = max(maxs, 0);
     smin[i] = maxs < 0 ? 0 : mins;
     __syncthreads();
-    rec.pad[0] = (uint32_t)smax[i];
-    rec.pad[1] = i + ahead < 256 ? (uint32_t)smax[i + ahead] : 0u;
-    rec.pad[2] = i + ahead < 256 ? (uint32_t)smin[i + ahead] : 0u;
-    rec.pad[3] = (uint32_t)i;
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        rec[h].pad[0] = (uint32_t)smax[i];
+        rec[h].pad[1] = i + ahead < 256 ? (uint32_t)smax[i + ahead] : 0u;
+        rec[h].pad[2] = i + ahead < 256 ? (uint32_t)smin[i + ahead] : 0u;
+        rec[h].pad[3] = (uint32_t)i;
+    }
     if (i < ld) {
         const size_t idx = ((size_t)b * NQ + q) * ld + i;
-        recs[idx] = rec;
+#pragma unroll
+        for (int h = 0; h < H; ++h) recs[idx * H + h] = rec[h];
         infos[idx].mins = mins;
         infos[idx].maxs = maxs;
 #pragma unroll
-        for (int rr = 0; rr < S2_R; ++rr) shifts[idx].w[rr] = wv[rr];
+        for (int rr = 0; rr < R; ++rr) shifts[idx * H + rr / S2_H].w[rr % S2_H] = wv[rr];
     }
     if (i < j0 && maxs >= 0 && maxs - mins > dmax) viol = 1;
-    if (i >= j0 && i < j0 + S2_R) {
+    if (i >= j0 && i < j0 + R) {
 #pragma unroll
-        for (int rr = 0; rr < S2_R; ++rr) wd[i - j0][rr] = wv[rr];
+        for (int rr = 0; rr < R; ++rr) wd[i - j0][rr] = wv[rr];
     }
     __syncthreads();
     if (i == 0) {
         // how far to the left of its stored columns each row must be correct
-        int need[S2_R];
+        int need[R];
         int g = 0, hmax = 0;
-        for (int rr = S2_R - 1; rr >= 0; --rr) {
+        for (int rr = R - 1; rr >= 0; --rr) {
             int n = 0;
-            for (int r2 = rr + 1; r2 < S2_R; ++r2)
+            for (int r2 = rr + 1; r2 < R; ++r2)
                 if (wd[rr][r2] >= 0) {
                     n = max(n, wd[rr][r2] + need[r2]);
                     hmax = max(hmax, wd[rr][r2]);
@@ -155,21 +166,21 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
 // first brought into LDS when they fit.
 constexpr int S2_LAYOUT_CACHE = 12288;
 __global__ __launch_bounds__(1024) void stage2_layout_kernel(
-    int B, int L, int P, int NQ, int wcap, const int32_t* __restrict__ groups,
+    int B, int L, int P, int NQ, int R, int wcap, const int32_t* __restrict__ groups,
     S2Entry* __restrict__ entries, S2Task* __restrict__ tasks, S2Header* hdr)
 {
     __shared__ int wsum[2][16];
     __shared__ int gcache[S2_LAYOUT_CACHE];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int N = NQ * S2_R * B;
+    const int N = NQ * R * B;
     const bool cached = B * NQ <= S2_LAYOUT_CACHE;
     if (cached)
         for (int x = tid; x < B * NQ; x += 1024) gcache[x] = groups[x];
     __syncthreads();
     auto group_of = [&](int b, int q) { return cached ? gcache[b * NQ + q] : groups[(size_t)b * NQ + q]; };
     auto count = [&](int b, int q, int sub) {
-        const int hq = min(S2_R, L - q * S2_R);
+        const int hq = min(R, L - q * R);
         const int grp = group_of(b, q);
         // the first strip starts at t = 0 and has no ghost columns
         if (grp >= 0)
@@ -179,20 +190,20 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     // the entry whose rows the entry (level, b) needs last, its task count and
     // the first row it writes
     auto pred = [&](int level, int b, int& prev, int& prev_cnt, int& prev_row0) {
-        const int q = level / S2_R, sub = level % S2_R;
+        const int q = level / R, sub = level % R;
         prev = -1;
         prev_cnt = 0;
         prev_row0 = -1;
         if (sub > 0) {
             prev = (level - 1) * B + b;
             prev_cnt = count(b, q, sub - 1);
-            prev_row0 = q * S2_R + sub;
+            prev_row0 = q * R + sub;
         } else if (q > 0) {
             const bool whole = group_of(b, q - 1) >= 0;
-            const int psub = whole ? 0 : S2_R - 1;
-            prev = ((q - 1) * S2_R + psub) * B + b;
+            const int psub = whole ? 0 : R - 1;
+            prev = ((q - 1) * R + psub) * B + b;
             prev_cnt = count(b, q - 1, psub);
-            prev_row0 = 1 + (q - 1) * S2_R + psub;
+            prev_row0 = 1 + (q - 1) * R + psub;
         }
     };
     int base = 0;                                   // tickets before this tile
@@ -202,7 +213,7 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
         int prev = -1, prev_cnt = 0, prev_row0 = -1, prev2 = -1, prev2_cnt = 0, unused = -1;
         if (e < N) {
             const int level = e / B, b = e - level * B;
-            const int q = level / S2_R, sub = level % S2_R;
+            const int q = level / R, sub = level % R;
             c = count(b, q, sub);
             const int grp = group_of(b, q);
             g = grp >= 0 && sub == 0 ? grp : -1;
@@ -250,25 +261,32 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     if (tid < 4) hdr->ninf[tid] = -INFINITY;
 }
 
-hipError_t launch_stage2_prepare(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
-                                 uint8_t* K, void* workspace, int gmax, int dmax, int wcap,
-                                 int ahead, hipStream_t st)
+hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt, const float* I,
+                                 float* M, uint8_t* K, void* workspace, int gmax, int dmax,
+                                 int wcap, int ahead, hipStream_t st)
 {
-    const int NQ = (L + S2_R - 1) / S2_R;
-    const S2Layout lay = s2_layout(B, L, P);
+    if (R != 8 && R != 16) return hipErrorInvalidValue;
+    const int NQ = (L + R - 1) / R;
+    const S2Layout lay = s2_layout(B, L, P, R);
     if (lay.nentries > 0x3FFFFFF0LL || lay.maxtasks > 0x3FFFFFF0LL) return hipErrorInvalidValue;
     const int N = (int)lay.nentries;
     char* base = (char*)workspace;
     hipError_t e = launch_clear_words(workspace, (int)(sizeof(S2Header) / 4) + N, st);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(stage2_pack_kernel, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I,
-                       (S2Rec*)(base + lay.rec_off), (S2Info*)(base + lay.info_off),
-                       (S2Shift*)(base + lay.shift_off), (int32_t*)(base + lay.group_off), gmax,
-                       dmax, wcap, ahead, M, K);
+    S2Rec* recs = (S2Rec*)(base + lay.rec_off);
+    S2Info* infos = (S2Info*)(base + lay.info_off);
+    S2Shift* shifts = (S2Shift*)(base + lay.shift_off);
+    int32_t* groups = (int32_t*)(base + lay.group_off);
+    if (R == 8)
+        hipLaunchKernelGGL(stage2_pack_kernel<8>, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I,
+                           recs, infos, shifts, groups, gmax, dmax, wcap, ahead, M, K);
+    else
+        hipLaunchKernelGGL(stage2_pack_kernel<16>, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I,
+                           recs, infos, shifts, groups, gmax, dmax, wcap, ahead, M, K);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(stage2_layout_kernel, dim3(1), dim3(1024), 0, st, B, L, P, NQ, wcap,
-                       (const int32_t*)(base + lay.group_off), (S2Entry*)(base + lay.entry_off),
+    hipLaunchKernelGGL(stage2_layout_kernel, dim3(1), dim3(1024), 0, st, B, L, P, NQ, R, wcap,
+                       (const int32_t*)groups, (S2Entry*)(base + lay.entry_off),
                        (S2Task*)(base + lay.task_off), (S2Header*)base);
     return hipGetLastError();
 }

@@ -495,7 +495,7 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
 {
     constexpr int WCAP = NT * U;
     const int NQ = (L + S2_R - 1) / S2_R;
-    const S2Layout lay = s2_layout(B, L, P);
+    const S2Layout lay = s2_layout(B, L, P, S2_R);
     if (lay.nentries > 0x3FFFFFF0LL || lay.maxtasks > 0x3FFFFFF0LL) return hipErrorInvalidValue;
     char* base = (char*)workspace;
     S2Header* hdr = (S2Header*)base;
@@ -509,7 +509,7 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     // ghost columns cost recomputation: at most a quarter of a task, and the
     // chain of shifts must fit the pad in front of a diagonal slot
     const int gmax = std::min(DMAX, WCAP / 4);
-    hipError_t e = launch_stage2_prepare(B, L, P, Topt, I, M, K, workspace, gmax, DMAX, WCAP, 0, st);
+    hipError_t e = launch_stage2_prepare(B, L, P, S2_R, Topt, I, M, K, workspace, gmax, DMAX, WCAP, 0, st);
     if (e != hipSuccess) return e;
 
     // resident workgroups per compute unit: WPE waves per SIMD, 4 SIMDs

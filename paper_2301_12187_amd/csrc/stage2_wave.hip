@@ -4,9 +4,13 @@
 //
 // Tasks, ghost columns, ticket order, completion counters and the row-by-row
 // fallback are those of the LDS-tiled family (stage2_tiled.hip): a task is
-// (instance, group of R = 8 rows, strip of WCAP = NW*64*U columns), it keeps
-// the R x WCAP running (maximum, arg-max) pairs in registers, reads rows below
-// its group from global memory and writes its own rows.
+// (instance, group of R = 8 or 16 rows, strip of WCAP = NW*256 columns), it
+// keeps the R x WCAP running (maximum, arg-max) pairs in registers, reads rows
+// below its group from global memory and writes its own rows.  Every row of M
+// is read back once per group above it, and that traffic, not the arithmetic,
+// bounds the kernel when tables are wide: hence the tall groups.  To fit 16
+// rows x 4 columns per lane the arg-max indices are kept as bytes, four to a
+// register, and updated in place with a sub-dword select.
 //
 // What differs is the off-diagonal part.  Every wave owns 64*U consecutive
 // columns and feeds itself: for predecessor row i it copies the window of
@@ -30,9 +34,9 @@
 // importances are -inf in the records, so it never wins.
 //
 // The diagonal part (predecessors inside the group) is shared by the waves of
-// the workgroup as in the tiled family: a finished row goes to an LDS slot
-// (laid over the rings, which are idle by then) from which the rows below it
-// are relaxed, one workgroup barrier per row.
+// the workgroup as in the tiled family: a finished row goes to one of two LDS
+// slots (laid over the rings, which are idle by then) from which the rows
+// below it are relaxed, one workgroup barrier per row.
 #include "stage2_common.h"
 
 namespace dpc {
@@ -48,14 +52,51 @@ namespace dpc {
 #define TACC(slot, a, b) do {} while (0)
 #endif
 
-template <int NW, int U, int NSLOT, int DMAX, int WPE, bool STORE_K>
+// One relaxation of one cell: if cand > best then best = cand and byte BYTE of
+// argp = vi (vi < 256), i.e. Eq. 7's max with the lowest arg-max kept when
+// candidates arrive in ascending order.  The compare writes the lane mask that
+// both selects read; the second select writes one byte of its destination and
+// preserves the other three.  (Two wait states are required between a vector
+// compare and a vector instruction that reads its mask.)
+#ifndef DPC_HOST_EMU
+#define DPC_RELAX_CELL(B)                                                                    \
+    asm("v_cmp_gt_f32 vcc, %2, %0\n\t"                                                       \
+        "s_nop 1\n\t"                                                                        \
+        "v_cndmask_b32 %0, %0, %2, vcc\n\t"                                                  \
+        "v_cndmask_b32_sdwa %1, %1, %3, vcc dst_sel:BYTE_" #B                                \
+        " dst_unused:UNUSED_PRESERVE src0_sel:BYTE_" #B " src1_sel:DWORD"                    \
+        : "+v"(best), "+v"(argp)                                                             \
+        : "v"(cand), "v"(vi)                                                                 \
+        : "vcc")
+#else  // the CPU emulation build of the tests spells the same update out
+#define DPC_RELAX_CELL(B)                                                                    \
+    do {                                                                                     \
+        if (cand > best) {                                                                   \
+            best = cand;                                                                     \
+            argp = (argp & ~(0xFFu << (8 * B))) | ((vi & 0xFFu) << (8 * B));                 \
+        }                                                                                    \
+    } while (0)
+#endif
+template <int BYTE>
+__device__ __forceinline__ void relax_cell(float& best, uint32_t& argp, float cand, uint32_t vi)
+{
+    static_assert(BYTE >= 0 && BYTE < 4, "four arg-max bytes per register");
+    if constexpr (BYTE == 0) DPC_RELAX_CELL(0);
+    else if constexpr (BYTE == 1) DPC_RELAX_CELL(1);
+    else if constexpr (BYTE == 2) DPC_RELAX_CELL(2);
+    else DPC_RELAX_CELL(3);
+}
+#undef DPC_RELAX_CELL
+
+template <int R, int NW, int NSLOT, int DMAX, int WPE, bool STORE_K>
 __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* done,
     const S2Entry* __restrict__ entries, const S2Task* __restrict__ tasks,
     const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos,
     const S2Shift* __restrict__ shifts, int NQ, long long wait_limit)
 {
-    constexpr int R = S2_R;
+    constexpr int U = 4;                             // columns per lane: one arg-max byte each
+    constexpr int H = R / S2_H;                      // records per (group, predecessor)
     constexpr int NT = NW * 64;
     constexpr int WV = 64 * U;                       // columns per wave
     constexpr int WCAP = NW * WV;                    // columns per task
@@ -65,9 +106,9 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     constexpr int RINGF = NSLOT * SLOTF;             // floats per wave
     constexpr int D = NSLOT - 1;                     // rows in flight ahead of the current one
     constexpr int DSLOTW = WCAP + DMAX + 4;          // floats per diagonal slot
-    constexpr int LDSF = NW * RINGF > (R - 1) * DSLOTW ? NW * RINGF : (R - 1) * DSLOTW;
+    constexpr int LDSF = NW * RINGF > 2 * DSLOTW ? NW * RINGF : 2 * DSLOTW;
     constexpr float NINF = -INFINITY;
-    static_assert(U % 2 == 0, "columns are read in pairs");
+    static_assert(R == 8 || R == 16, "one or two records per predecessor");
     static_assert(D >= 1 && D * NLD <= 8, "the counted wait covers at most 8 loads");
     static_assert(DMAX % 4 == 0, "diagonal slots stay 16-byte aligned");
     __shared__ __attribute__((aligned(16))) float lds[LDSF];
@@ -88,12 +129,19 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const long long tkernel0 = wall_clock64();
 #endif
+    int publish = -1;                              // entry of the task this workgroup just finished
     for (;;) {
         TMARK(t_a);
-        // ---- next ticket, its task, and the wait for the previous level of the
-        //      instance (all by one lane; the rest of the workgroup waits at the barrier)
-        if (tid == 0) {
-            const int ticket = (int)atomicAdd(&hdr->ticket, 1u);
+        // ---- wave 0: count the finished task as complete, take the next ticket
+        //      and look up its task.  All of it is wave-uniform code (one lane
+        //      only issues the atomics and writes the result), so that the
+        //      loop over tasks never diverges.
+        if (wave == 0) {
+            if (publish >= 0 && lane == 0)
+                __hip_atomic_fetch_add(&done[publish], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int ticket = 0;
+            if (lane == 0) ticket = (int)atomicAdd(&hdr->ticket, 1u);
+            ticket = __builtin_amdgcn_readfirstlane(ticket);
             int e = -1, strip = 0, g = -1, ok = 1, prev = -1, prev_cnt = 0, prev_row0 = -1;
             if (ticket < total) {
                 const S2Task tk = tasks[ticket];
@@ -110,11 +158,12 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     const uint32_t need = (uint32_t)ent.prev2_cnt;
                     const uint32_t* flag = &done[ent.prev2];
                     const long long start = wall_clock64();
-                    while (ld_relaxed(flag) < need) {
-                        if (ld_relaxed(&hdr->error) != 0) { ok = 0; break; }
+                    while (ld_uniform(flag) < need) {
+                        if (ld_uniform(&hdr->error) != 0) { ok = 0; break; }
                         if (wall_clock64() - start > wait_limit) {
-                            __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
+                            if (lane == 0)
+                                __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
                             ok = 0;
                             break;
                         }
@@ -122,12 +171,14 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     }
                 }
             }
-            sh_word[0] = ok ? e : -1;
-            sh_word[1] = strip;
-            sh_word[2] = g;
-            sh_word[3] = prev;
-            sh_word[4] = prev_cnt;
-            sh_word[5] = prev_row0;
+            if (lane == 0) {
+                sh_word[0] = ok ? e : -1;
+                sh_word[1] = strip;
+                sh_word[2] = g;
+                sh_word[3] = prev;
+                sh_word[4] = prev_cnt;
+                sh_word[5] = prev_row0;
+            }
         }
         __syncthreads();
         const int e = __builtin_amdgcn_readfirstlane(sh_word[0]);
@@ -165,36 +216,49 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         const int tW = tS + wave * WV;             // first column of this wave
         float* Mb = M + (size_t)b * ld * P;
         uint8_t* Kb = STORE_K ? K + (size_t)b * ld * P : nullptr;
-        const S2Rec* brec = recs + ((size_t)b * NQ + q) * ld;
+        const S2Rec* brec = recs + ((size_t)b * NQ + q) * ld * H;
         const S2Info* binfo = infos + ((size_t)b * NQ + q) * ld;
-        const S2Shift* bshift = shifts + ((size_t)b * NQ + q) * ld;
+        const S2Shift* bshift = shifts + ((size_t)b * NQ + q) * ld * H;
 
         float best[R][U];
-        int arg[R][U];
+        uint32_t argp[R];                          // arg-max of column u in byte u
 #pragma unroll
-        for (int rr = 0; rr < R; ++rr)
+        for (int rr = 0; rr < R; ++rr) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) { best[rr][u] = NINF; arg[rr][u] = DPC_NOARG; }
+            for (int u = 0; u < U; ++u) best[rr][u] = NINF;
+            argp[rr] = 0x01010101u * DPC_NOARG;
+        }
 
         // a wave whose columns all lie beyond the table has nothing to do but
         // to take part in the barriers
         const bool wave_idle = tW >= tend;
 
+        // shift and importance of the candidate that row i offers to the row of
+        // a one-row task (w = -1: none)
+        auto one_row_of = [&](int i, int& w, float& imp) __attribute__((always_inline)) {
+            w = -1;
+            imp = NINF;
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const S2Shift sh = bshift[i * H + h];
+                const S2Rec& rec = brec[i * H + h];
+#pragma unroll
+                for (int r8 = 0; r8 < S2_H; ++r8)
+                    if (h * S2_H + r8 == sub) { w = sh.w[r8]; imp = rec.imp[r8]; }
+            }
+        };
+
         // Window of row i for this wave: the largest and smallest shift of the
         // candidates it offers to the task (no candidate: any window will do).
-        // A whole-group task takes them from the records, a one-row task uses
-        // the shift of its row.
         auto window_of = [&](int i, int& maxs, int& mins) __attribute__((always_inline)) {
             if (full) {
                 const S2Info inf = binfo[i];
                 maxs = max(inf.maxs, 0);
                 mins = inf.maxs < 0 ? 0 : inf.mins;
             } else {
-                int w = 0;
-                const S2Shift sh = bshift[i];
-#pragma unroll
-                for (int rr = 0; rr < R; ++rr)
-                    if (rr == sub) w = sh.w[rr];
+                int w;
+                float imp;
+                one_row_of(i, w, imp);
                 maxs = mins = max(w, 0);
             }
         };
@@ -209,10 +273,15 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             const float* row = Mb + (size_t)i * P;
             float* dst = ring + slot * SLOTF;
             if (lo4 >= 0) {
+                // (wave-uniform base plus an unsigned 32-bit byte offset per lane;
+                //  lo4 <= last because the wave has a column below P)
+                const char* base = (const char*)(row + lo4);
+                const unsigned lastoff = (unsigned)(last - lo4) * 4u;
 #pragma unroll
                 for (int k = 0; k < NLD; ++k) {
-                    const int tp = min(lo4 + 256 * k + 4 * lane, last);
-                    __builtin_amdgcn_global_load_lds(row + tp, (lds_void*)(dst + 256 * k), 16, 0,
+                    const unsigned off = min((unsigned)(1024 * k + 16 * lane), lastoff);
+                    __builtin_amdgcn_global_load_lds((const float*)(base + off),
+                                                     (lds_void*)(dst + 256 * k), 16, 0,
                                                      DMA_AGENT_SCOPE);
                 }
             } else {
@@ -226,61 +295,60 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             }
         };
 
-        // Relax all rows of the group from row i, whose window sits in `slot`.
-        // A candidate whose shift exceeds every column of the task reads the
-        // part of the window below column 0 (-inf); a missing candidate adds
-        // -inf to whatever its cell holds: neither needs a test here.
-        auto relax_whole = [&](int slot, const S2Rec& rec) __attribute__((always_inline)) {
-            const int i = (int)rec.pad[3];
-            const int delta = (tS - (int)rec.pad[0]) & 3;          // alignment slack of the window
-            const char* base = lbase + (slot * SLOTF + delta) * 4;
+        // Relax the eight rows h*8 .. h*8+7 of the group from the row whose
+        // window sits at `base` (byte address of this lane's column u = 0 at
+        // offset 0) with the operands of `rec`.  A candidate whose shift
+        // exceeds every column of the task reads the part of the window below
+        // column 0 (-inf); a missing candidate adds -inf to whatever its cell
+        // holds: neither needs a test here.  LDS reads run one row ahead of
+        // the arithmetic.
+        auto relax_half = [&](auto hh, const char* base, const S2Rec& rec, uint32_t vi)
+                              __attribute__((always_inline)) {
+            constexpr int h = decltype(hh)::value;
             float mcur[U], mnxt[U];
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 mcur[u] = *(const float*)(base + rec_off4(rec, 0) + 256 * u);
 #pragma unroll
-            for (int rr = 0; rr < R; ++rr) {
-                if (rr + 1 < R) {
+            for (int r8 = 0; r8 < S2_H; ++r8) {
+                constexpr int unused = 0;
+                (void)unused;
+                if (r8 + 1 < S2_H) {
 #pragma unroll
                     for (int u = 0; u < U; ++u)
-                        mnxt[u] = *(const float*)(base + rec_off4(rec, rr + 1) + 256 * u);
+                        mnxt[u] = *(const float*)(base + rec_off4(rec, r8 + 1) + 256 * u);
                 }
-                const float imp = rec.imp[rr];
+                const float imp = rec.imp[r8];
                 float cand[U];
-                bool win[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
-#pragma unroll
-                for (int u = 0; u < U; ++u) win[u] = cand[u] > best[rr][u];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    best[rr][u] = win[u] ? cand[u] : best[rr][u];
-                    arg[rr][u] = win[u] ? i : arg[rr][u];
-                }
+                relax_cell<0>(best[h * S2_H + r8][0], argp[h * S2_H + r8], cand[0], vi);
+                relax_cell<1>(best[h * S2_H + r8][1], argp[h * S2_H + r8], cand[1], vi);
+                relax_cell<2>(best[h * S2_H + r8][2], argp[h * S2_H + r8], cand[2], vi);
+                relax_cell<3>(best[h * S2_H + r8][3], argp[h * S2_H + r8], cand[3], vi);
 #pragma unroll
                 for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
             }
         };
         // The same for a one-row task: only row `sub` of the group, at one shift.
         auto relax_one = [&](int i, int slot) __attribute__((always_inline)) {
-            const S2Shift sh = bshift[i];
-            const S2Rec& rec = brec[i];
-            int w = -1;
-            float imp = NINF;
-#pragma unroll
-            for (int rr = 0; rr < R; ++rr)
-                if (rr == sub) { w = sh.w[rr]; imp = rec.imp[rr]; }
+            int w;
+            float imp;
+            one_row_of(i, w, imp);
             if (w < 0) return;
             const int delta = (tS - w) & 3;
             const float* base = (const float*)(lbase + (slot * SLOTF + delta) * 4);
+            float cand[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) cand[u] = base[64 * u] + imp;
+            const uint32_t vi = (uint32_t)i;
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) {
                 if (rr != sub) continue;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const float cand = base[64 * u] + imp;
-                    if (cand > best[rr][u]) { best[rr][u] = cand; arg[rr][u] = i; }
-                }
+                relax_cell<0>(best[rr][0], argp[rr], cand[0], vi);
+                relax_cell<1>(best[rr][1], argp[rr], cand[1], vi);
+                relax_cell<2>(best[rr][2], argp[rr], cand[2], vi);
+                relax_cell<3>(best[rr][3], argp[rr], cand[3], vi);
             }
         };
 
@@ -292,10 +360,12 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         auto wait_prev = [&]() __attribute__((always_inline)) {
             const uint32_t* flag = &done[prev];
             const long long start = wall_clock64();
-            while (ld_relaxed(flag) < prev_cnt) {
-                if (ld_relaxed(&hdr->error) != 0) break;
+            while (ld_uniform(flag) < prev_cnt) {
+                if (ld_uniform(&hdr->error) != 0) break;
                 if (wall_clock64() - start > wait_limit) {
-                    __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (lane == 0)
+                        __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
                     break;
                 }
                 __builtin_amdgcn_s_sleep(2);
@@ -317,26 +387,44 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             int slot = 0;                              // ring slot of row i
             int ahead = D;                             // ring slot of row i + D
             if (full) {
-                S2Rec cur = brec[0];
+                S2Rec cur[H];
+#pragma unroll
+                for (int h = 0; h < H; ++h) cur[h] = brec[h];
                 for (int i = 0; i < ilimit; ++i) {
                     TMARK(ta);
-                    const S2Rec nxt = brec[min(i + 1, L)];
+                    const int inext = min(i + 1, L) * H;
                     // the loads of the D rows ahead stay in flight; past the last
                     // row there is nothing left to start and nothing to leave
                     if (i + D < ilimit) {
                         if (i + D == prev_row0) wait_prev();
-                        issue_row(i + D, ahead, (int)cur.pad[1], (int)cur.pad[2]);
+                        issue_row(i + D, ahead, (int)cur[0].pad[1], (int)cur[0].pad[2]);
                         wait_vm(D * NLD);
                     } else {
                         wait_vm(0);
                     }
                     asm volatile("" ::: "memory");             // row i has landed
                     TMARK(tb);
-                    relax_whole(slot, cur);
+                    const int delta = (tS - (int)cur[0].pad[0]) & 3;   // alignment slack of the window
+                    const char* base = lbase + (slot * SLOTF + delta) * 4;
+                    const uint32_t vi = cur[0].pad[3];
+#ifndef DPC_S2_NORELAX                                         // (timing experiments only)
+                    if constexpr (H == 1) {
+                        const S2Rec nxt = brec[inext];
+                        relax_half(std::integral_constant<int, 0>{}, base, cur[0], vi);
+                        cur[0] = nxt;
+                    } else {
+                        // the operands of each half are fetched for the next row as
+                        // soon as the half has been used
+                        relax_half(std::integral_constant<int, 0>{}, base, cur[0], vi);
+                        const S2Rec nxt0 = brec[inext];
+                        relax_half(std::integral_constant<int, 1>{}, base, cur[H - 1], vi);
+                        cur[H - 1] = brec[inext + H - 1];
+                        cur[0] = nxt0;
+                    }
+#endif
                     TMARK(tc);
                     TACC(0, ta, tb);
                     TACC(2, tb, tc);
-                    cur = nxt;
                     ahead = slot;
                     slot = slot + 1 == NSLOT ? 0 : slot + 1;
                 }
@@ -359,90 +447,108 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             }
         }
         TMARK(t_c);
-        __syncthreads();                               // every ring is idle: the slots below lie over them
-        TMARK(t_c2);
-        TACC(1, t_c, t_c2);
-        if (full && tS == 0) {
-            // first strip: what lies to the left of column 0 does not exist
-            for (int x = tid; x < (R - 1) * DMAX; x += NT) {
-                const int rr = x / DMAX;
-                lds[rr * DSLOTW + (x - rr * DMAX)] = NINF;
-            }
-        }
-
-        // ---------------- diagonal part and output ----------------
-        // records of the group's own rows, fetched four at a time
-        S2Rec drec[4];
-        auto load_diag = [&](int first) __attribute__((always_inline)) {
+        if (!full) {
+            // ---------------- a one-row task only has its row to store ----------------
 #pragma unroll
-            for (int c = 0; c < 4; ++c) drec[c] = brec[min(j0 + first + c, L)];
-        };
-        if (full && !wave_idle) load_diag(0);
-#pragma unroll
-        for (int rr = 0; rr < R; ++rr) {
-            const int j = j0 + rr;
-            if (rr >= rlo && rr < rhi) {
+            for (int rr = 0; rr < R; ++rr) {
+                if (rr != sub) continue;
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int t = tS + tl0 + 64 * u;
                     if (t >= t0 && t < tstore_end) {
-                        st_agent(Mb + (size_t)j * P + t, best[rr][u]);
-                        if (STORE_K) st_agent(Kb + (size_t)j * P + t, (uint8_t)arg[rr][u]);
+                        st_agent(Mb + (size_t)(j0 + rr) * P + t, best[rr][u]);
+                        if (STORE_K)
+                            st_agent(Kb + (size_t)(j0 + rr) * P + t, (uint8_t)(argp[rr] >> (8 * u)));
                     }
                 }
             }
-            if (rr + 1 < R) {
-                // row j of a whole-group task feeds the rows below it through an LDS
-                // slot: own column t at slot position DMAX + (t - tS)
-                const bool feeds = full && rr + 1 < rhi;
-                float* slot = lds + rr * DSLOTW;
-                if (feeds) {
+        } else {
+            __syncthreads();                           // every ring is idle: the slots below lie over them
+            TMARK(t_c2);
+            TACC(1, t_c, t_c2);
+            if (tS == 0) {
+                // first strip: what lies to the left of column 0 does not exist
+                for (int x = tid; x < 2 * DMAX; x += NT) {
+                    const int sl = x / DMAX;
+                    lds[sl * DSLOTW + (x - sl * DMAX)] = NINF;
+                }
+            }
+            // ---------------- diagonal part and output ----------------
+            // Straight-line code for every wave and every row of the group: a row
+            // past the last layer has no candidates in the records (importance
+            // -inf) and is not stored, and a wave past the last column relaxes
+            // cells that are never stored.
+            S2Rec drec[H];                             // operands of the group's own row rr
+#pragma unroll
+            for (int h = 0; h < H; ++h) drec[h] = brec[min(j0, L) * H + h];
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) {
+                const int j = j0 + rr;
+                if (rr < hq) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int t = tS + tl0 + 64 * u;
+                        if (t >= t0 && t < tstore_end) {
+                            st_agent(Mb + (size_t)j * P + t, best[rr][u]);
+                            if (STORE_K)
+                                st_agent(Kb + (size_t)j * P + t, (uint8_t)(argp[rr] >> (8 * u)));
+                        }
+                    }
+                }
+                if (rr + 1 < R) {
+                    // row j feeds the rows below it through an LDS slot: own column t
+                    // at slot position DMAX + (t - tS).  Two slots alternate: a slot
+                    // is written again only after the barrier that follows the reads
+                    // of its previous contents.
+                    float* slot = lds + (rr & 1) * DSLOTW;
 #pragma unroll
                     for (int u = 0; u < U; ++u) slot[DMAX + tl0 + 64 * u] = best[rr][u];
-                }
-                __syncthreads();
-                if (feeds && !wave_idle) {
-                    const S2Rec& rec = drec[rr & 3];
-                    // (a row of the group that offers no candidate has -inf importances)
-                    const int maxs = (int)rec.pad[0];
+                    __syncthreads();
+                    const int maxs = (int)drec[0].pad[0];
+                    const uint32_t vj = (uint32_t)j;
 #pragma unroll
                     for (int r2 = rr + 1; r2 < R; ++r2) {
                         // shifts inside a group are at most DMAX: a shift beyond
                         // the task's last column can only occur in the first
                         // strip, whose pad holds -inf
-                        const int w = maxs - (rec_off4(rec, r2) >> 2);
-                        const float imp = rec.imp[r2];
+                        const S2Rec& rec = drec[r2 / S2_H];
+                        const int w = maxs - (rec_off4(rec, r2 % S2_H) >> 2);
+                        const float imp = rec.imp[r2 % S2_H];
                         const float* sp = &slot[DMAX - w + tl0];
+                        float cand[U];
 #pragma unroll
-                        for (int u = 0; u < U; ++u) {
-                            const float cand = sp[64 * u] + imp;
-                            if (cand > best[r2][u]) { best[r2][u] = cand; arg[r2][u] = j; }
-                        }
+                        for (int u = 0; u < U; ++u) cand[u] = sp[64 * u] + imp;
+                        relax_cell<0>(best[r2][0], argp[r2], cand[0], vj);
+                        relax_cell<1>(best[r2][1], argp[r2], cand[1], vj);
+                        relax_cell<2>(best[r2][2], argp[r2], cand[2], vj);
+                        relax_cell<3>(best[r2][3], argp[r2], cand[3], vj);
                     }
-                    if (rr == 3) load_diag(4);
+                    // operands of the next row of the group
+#pragma unroll
+                    for (int h = 0; h < H; ++h) drec[h] = brec[min(j + 1, L) * H + h];
                 }
             }
         }
 
         TMARK(t_d);
-        TACC(4, t_c2, t_d);
-        // ---- publish: one more task of this entry is complete
-        wait_vm(0);                                    // this wave's stores are acknowledged
-        __syncthreads();                               // ... every wave's; the LDS is free again
-        if (tid == 0)
-            __hip_atomic_fetch_add(&done[e], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        TACC(4, t_c, t_d);
+        // ---- the task is complete once every wave's stores are acknowledged;
+        //      wave 0 publishes it at the top of the loop
+        wait_vm(0);
+        __syncthreads();                               // (also: the LDS is free again)
+        publish = e;
         TMARK(t_e);
         TACC(5, t_d, t_e);
     }
 }
 
-template <int NW, int U, int NSLOT, int DMAX, int WPE>
+template <int R, int NW, int NSLOT, int DMAX, int WPE>
 static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                                   uint8_t* K, void* workspace, int num_cu, hipStream_t st)
 {
-    constexpr int WCAP = NW * 64 * U;
-    const int NQ = (L + S2_R - 1) / S2_R;
-    const S2Layout lay = s2_layout(B, L, P);
+    constexpr int WCAP = NW * 256;
+    const int NQ = (L + R - 1) / R;
+    const S2Layout lay = s2_layout(B, L, P, R);
     char* base = (char*)workspace;
     S2Header* hdr = (S2Header*)base;
     uint32_t* done = (uint32_t*)(base + lay.done_off);
@@ -455,7 +561,8 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
     // ghost columns cost recomputation: at most a quarter of a task, and the
     // chain of shifts must fit the pad in front of a diagonal slot
     const int gmax = std::min(DMAX, WCAP / 4);
-    hipError_t e = launch_stage2_prepare(B, L, P, Topt, I, M, K, workspace, gmax, DMAX, WCAP, NSLOT - 1, st);
+    hipError_t e = launch_stage2_prepare(B, L, P, R, Topt, I, M, K, workspace, gmax, DMAX, WCAP,
+                                         NSLOT - 1, st);
     if (e != hipSuccess) return e;
 
     // resident workgroups per compute unit: WPE waves per SIMD, 4 SIMDs
@@ -464,11 +571,11 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
     const int grid = num_cu * wg_per_cu;
     const long long wait_limit = 500000000LL;      // 5 s of the 100 MHz wall clock
     if (K)
-        hipLaunchKernelGGL((stage2_wave_kernel<NW, U, NSLOT, DMAX, WPE, true>), dim3(grid),
+        hipLaunchKernelGGL((stage2_wave_kernel<R, NW, NSLOT, DMAX, WPE, true>), dim3(grid),
                            dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
                            infos, shifts, NQ, wait_limit);
     else
-        hipLaunchKernelGGL((stage2_wave_kernel<NW, U, NSLOT, DMAX, WPE, false>), dim3(grid),
+        hipLaunchKernelGGL((stage2_wave_kernel<R, NW, NSLOT, DMAX, WPE, false>), dim3(grid),
                            dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
                            infos, shifts, NQ, wait_limit);
     return hipGetLastError();
@@ -484,11 +591,15 @@ hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const fl
     int shape = g_s2w_shape;
     if (shape == 0) shape = P <= 256 ? 4 : P <= 512 ? 3 : 1;
     switch (shape) {
-        case 1: return launch_wave_cfg<4, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 2: return launch_wave_cfg<8, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 3: return launch_wave_cfg<2, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 4: return launch_wave_cfg<1, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 5: return launch_wave_cfg<4, 2, 8, 124, 6>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        // groups of 8 rows: waves per task, ring slots, largest spread, waves per SIMD
+        case 1: return launch_wave_cfg<8, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 2: return launch_wave_cfg<8, 8, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 3: return launch_wave_cfg<8, 2, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 4: return launch_wave_cfg<8, 1, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        // groups of 16 rows
+        case 5: return launch_wave_cfg<16, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 6: return launch_wave_cfg<16, 8, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 7: return launch_wave_cfg<16, 2, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         default: return hipErrorInvalidValue;
     }
 }
