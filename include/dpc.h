@@ -152,16 +152,17 @@ const char *dpc_status_string(int code);
 
 /*
  * Tuning knob for measurements: selects the stage-2 kernel family.
- *   0  automatic (default)
+ *   0  automatic (default): the wave-window family, task shape chosen from
+ *      the problem size; tables narrower than 16 budgets use the tiled family
  *   1  row-at-a-time kernels reading M from global memory (one launch per row)
- *   2  persistent LDS-tiled kernel, strip shape chosen from the problem size
- *   21..26  persistent LDS-tiled kernel with a fixed task shape (threads x
- *       columns per thread, window buffers): 256x1, 256x2, 256x4 (2 buffers),
- *       512x2, 1024x2, 512x2 (2 buffers)
- *   3  persistent kernel with wave-private windows, task shape chosen from
- *       the problem size (tables narrower than 16 budgets run as 2)
- *   31..35  the same with a fixed task shape (waves x columns per lane):
- *       4x4, 8x4, 2x4, 1x4, 4x2
+ *   2  persistent LDS-tiled kernel (windows shared by a workgroup), strip
+ *      shape chosen from the problem size
+ *   21..26  the same with a fixed task shape (threads x columns per thread,
+ *       window buffers): 256x1, 256x2, 256x4 (2 buffers), 512x2, 1024x2,
+ *       512x2 (2 buffers)
+ *   3  persistent kernel with wave-private windows, same choice as 0
+ *   31..37  the same with a fixed task shape (rows per group x waves per
+ *       task, 256 columns per wave): 8x4, 8x8, 8x2, 8x1, 16x4, 16x8, 16x2
  * Returns the previous value, or DPC_ERR_SHAPE for an unknown one.  Results
  * are bit-identical for every choice.  Process-wide, not thread-safe.
  */

@@ -89,7 +89,8 @@ int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, co
         const int ncu = num_compute_units();
         if (ncu <= 0) return DPC_ERR_HIP;
         // the wave-window family reads whole 16-byte cells: narrow tables stay tiled
-        const bool wave = (g_stage2_variant == 3 || g_stage2_variant > 30) && P >= 16;
+        const bool wave = (g_stage2_variant == 0 || g_stage2_variant == 3 || g_stage2_variant > 30) &&
+                          P >= 16;
         e = wave ? dpc::launch_stage2_wave(B, L, P, Topt, I, M, K, workspace, ncu,
                                            (hipStream_t)stream)
                  : dpc::launch_stage2_tiled(B, L, P, Topt, I, M, K, workspace, ncu,

@@ -588,8 +588,19 @@ hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const fl
 {
     // a window cell may read up to three floats past the end of a row
     if (P < 16) return hipErrorInvalidValue;
+    // Task shape.  The narrowest task that covers a narrow table; wide tables
+    // take 1024 or 2048 columns per task.  Groups of 16 rows halve the number
+    // of times every row of M is read back, which is what bounds long, wide
+    // tables; short or narrow ones are faster with 8 rows (less recomputation
+    // at strip edges, windows that fit more often).  Measured on the L=53,
+    // L=100 and L=200 workloads.
     int shape = g_s2w_shape;
-    if (shape == 0) shape = P <= 256 ? 4 : P <= 512 ? 3 : 1;
+    if (shape == 0) {
+        if (P <= 256) shape = 4;
+        else if (P <= 512) shape = 3;
+        else if (P <= 1536) shape = 1;
+        else shape = (L >= 128 && P >= 8192) ? 5 : 2;
+    }
     switch (shape) {
         // groups of 8 rows: waves per task, ring slots, largest spread, waves per SIMD
         case 1: return launch_wave_cfg<8, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);

@@ -1,0 +1,75 @@
+"""The stage-2 wave-window kernels compiled for the host (tests/host_emu) and
+run under AddressSanitizer / UBSan, one workgroup at a time, one host thread
+per lane: the kernels' own index arithmetic is exercised on the CPU, where an
+out-of-bounds access is a test failure instead of a GPU fault, and the result
+is compared bit for bit with the oracle.  (What the emulation cannot show:
+anything that depends on the GPU's timing or on the inline assembly.)"""
+import os
+import shutil
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import rand_tables
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+EMU_DIR = os.path.join(HERE, "host_emu")
+
+
+@pytest.fixture(scope="module")
+def emu(tmp_path_factory):
+    if shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    exe = str(tmp_path_factory.mktemp("emu") / "dpc_emu")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-pthread",
+           "-I", EMU_DIR, "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(ROOT, "paper_2301_12187_amd", "csrc"),
+           "-x", "c++", "-o", exe, os.path.join(EMU_DIR, "emu_main.cpp")]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
+def _run(emu, tmp_path, T, I, P, shape):
+    B, ld, _ = T.shape
+    Topt, split, M, K = oracle.solve_batch(T, I, P, want_K=True, threads=4)
+    fin, fout = str(tmp_path / "in.bin"), str(tmp_path / "out.bin")
+    with open(fin, "wb") as f:
+        np.array([B, ld - 1, P, shape], np.int32).tofile(f)
+        Topt.astype(np.int32).tofile(f)
+        I.astype(np.float32).tofile(f)
+    r = subprocess.run([emu, fin, fout], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-4000:]
+    raw = np.fromfile(fout, np.uint8)
+    n = B * ld * P
+    Me = raw[:4 * n].view(np.float32).reshape(B, ld, P)
+    Ke = raw[4 * n:].reshape(B, ld, P)
+    assert (Me.view(np.uint32) == M.view(np.uint32)).all()
+    assert (Ke == K).all()
+
+
+# shape: 1 = groups of 8 rows, 4 waves; 5 = groups of 16 rows, 4 waves; 3 = 8 rows, 2 waves
+@pytest.mark.parametrize("shape", [1, 5, 3])
+def test_whole_groups_several_strips_ragged_tail(emu, tmp_path, shape):
+    rng = np.random.default_rng(501)
+    B, L, P = 2, 21, 1291                  # P not a multiple of 4, partial last group
+    T, I = zip(*[rand_tables(rng, L, tmax=12, inf_frac=0.3, ikind="neg", span=9) for _ in range(B)])
+    _run(emu, tmp_path, np.stack(T), np.stack(I), P, shape)
+
+
+@pytest.mark.parametrize("shape", [1, 5])
+def test_row_by_row_groups_and_missing_candidates(emu, tmp_path, shape):
+    rng = np.random.default_rng(502)
+    B, L, P = 2, 11, 1100
+    Ts, Is = [], []
+    for b in range(B):
+        T, I = rand_tables(rng, L, tmax=5, ikind="mixed")
+        ii, jj = np.triu_indices(L + 1, k=1)
+        jump = rng.random(ii.size) < 0.3     # wildly different shifts: spreads beyond the window
+        T[ii[jump], jj[jump]] = rng.integers(0, 1500, size=int(jump.sum()))
+        Ts.append(T)
+        Is.append(I)
+    _run(emu, tmp_path, np.stack(Ts), np.stack(Is), P, shape)
