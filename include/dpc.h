@@ -161,8 +161,9 @@ const char *dpc_status_string(int code);
  *       window buffers): 256x1, 256x2, 256x4 (2 buffers), 512x2, 1024x2,
  *       512x2 (2 buffers)
  *   3  persistent kernel with wave-private windows, same choice as 0
- *   31..37  the same with a fixed task shape (rows per group x waves per
- *       task, 256 columns per wave): 8x4, 8x8, 8x2, 8x1, 16x4, 16x8, 16x2
+ *   31..39  the same with a fixed task shape (rows per group x waves per
+ *       task, 256 columns per wave): 8x4, 8x8, 8x2, 8x1, 16x4, 16x8, 16x2,
+ *       16x16, 8x16
  * Returns the previous value, or DPC_ERR_SHAPE for an unknown one.  Results
  * are bit-identical for every choice.  Process-wide, not thread-safe.
  */

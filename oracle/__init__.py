@@ -3,7 +3,9 @@
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may
 import this package.  It wraps oracle/dpc_oracle.c (Algorithms 1 and 2 of the
 paper plus set recovery) and oracle/dpc_brute.c (exhaustive enumeration of
-Eq. 5a, Eq. 6 and Eq. 8 for tiny L) through ctypes, on numpy arrays.
+Eq. 5a, Eq. 6 and Eq. 8 for tiny L) through ctypes, on numpy arrays, and
+likewise oracle/dpc_ext_oracle.c / dpc_ext_brute.c (the extended solver of
+Appendix B: Algorithms 3 and 4).
 """
 from .api import (  # noqa: F401
     DPC_INF,
@@ -16,4 +18,9 @@ from .api import (  # noqa: F401
     brute_topt,
     brute_objective,
     brute_min_latency_given_A,
+    ext_iopt,
+    ext_dp,
+    ext_backtrack,
+    ext_solve_batch,
+    brute_ext_objective,
 )

@@ -156,3 +156,94 @@ def brute_min_latency_given_A(T, l, A):
         amask |= 1 << (int(a) - 1)
     assert l - 1 <= 20
     return _load().brute_min_latency_given_A(ld, _p(T), l, amask)
+
+
+# ---- extended solver (Appendix B of the paper: Algorithms 3 and 4) ----
+
+def _load_ext():
+    lib = _load()
+    if not getattr(lib, "_ext_ready", False):
+        i32, vp = ctypes.c_int32, ctypes.c_void_p
+        lib.oracle_ext_iopt.argtypes = [i32, vp, vp, vp]
+        lib.oracle_ext_iopt.restype = None
+        lib.oracle_ext_dp.argtypes = [i32, i32, vp, vp, vp, vp]
+        lib.oracle_ext_dp.restype = None
+        lib.oracle_ext_backtrack.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32] + [vp] * 9
+        lib.oracle_ext_backtrack.restype = i32
+        lib.brute_ext_objective.argtypes = [i32, vp, vp, i32, i32, vp]
+        lib.brute_ext_objective.restype = None
+        lib._ext_ready = True
+    return lib
+
+
+def ext_iopt(I4):
+    """I4 float32 [L+1][L+1][2][2] -> (Iopt, bsplit uint8), same shape."""
+    L = I4.shape[0] - 1
+    _chk(I4, np.float32, (L + 1, L + 1, 2, 2))
+    Iopt = np.empty_like(I4)
+    bsplit = np.empty(I4.shape, np.uint8)
+    _load_ext().oracle_ext_iopt(L, _p(I4), _p(Iopt), _p(bsplit))
+    return Iopt, bsplit
+
+
+def ext_dp(Topt, Iopt, P):
+    """-> (D float32 [L+1][P][2], Kx uint8 [L+1][P][2])."""
+    L = Topt.shape[0] - 1
+    _chk(Topt, np.int32, (L + 1, L + 1))
+    _chk(Iopt, np.float32, (L + 1, L + 1, 2, 2))
+    D = np.empty((L + 1, P, 2), np.float32)
+    Kx = np.empty((L + 1, P, 2), np.uint8)
+    _load_ext().oracle_ext_dp(L, P, _p(Topt), _p(Iopt), _p(D), _p(Kx))
+    return D, Kx
+
+
+def ext_backtrack(Topt, split, bsplit, D, Kx, T0):
+    """-> dict(status, A, S, B, obj, lat, a_last)."""
+    L = Topt.shape[0] - 1
+    P = D.shape[1]
+    assert 0 <= T0 < P
+    _chk(split, np.uint8, (L + 1, L + 1))
+    _chk(bsplit, np.uint8, (L + 1, L + 1, 2, 2))
+    _chk(D, np.float32, (L + 1, P, 2))
+    _chk(Kx, np.uint8, (L + 1, P, 2))
+    A, S, Bs = (np.full(L, -1, np.int32) for _ in range(3))
+    na, ns, nb, lat, al = (ctypes.c_int32() for _ in range(5))
+    obj = ctypes.c_float()
+    st = _load_ext().oracle_ext_backtrack(
+        L, P, _p(Topt), _p(split), _p(bsplit), _p(D), _p(Kx), int(T0), _p(A),
+        ctypes.byref(na), _p(S), ctypes.byref(ns), _p(Bs), ctypes.byref(nb),
+        ctypes.byref(obj), ctypes.byref(lat), ctypes.byref(al))
+    return dict(status=st, A=A[:max(na.value, 0)].copy(), S=S[:max(ns.value, 0)].copy(),
+                B=Bs[:max(nb.value, 0)].copy(), A_len=na.value, S_len=ns.value,
+                B_len=nb.value, obj=np.float32(obj.value), lat=lat.value, a_last=al.value)
+
+
+def _ext_solve_one(args):
+    T, I4, P = args
+    Topt, split = stage1(T)
+    Iopt, bsplit = ext_iopt(I4)
+    D, Kx = ext_dp(Topt, Iopt, P)
+    return Topt, split, Iopt, bsplit, D, Kx
+
+
+def ext_solve_batch(T, I4, P, threads=1):
+    """Algorithms 1, 3 and 4 for a batch.  -> Topt, split, Iopt, bsplit, D, Kx
+    (leading batch dimension)."""
+    jobs = [(np.ascontiguousarray(T[b]), np.ascontiguousarray(I4[b]), P)
+            for b in range(T.shape[0])]
+    if threads <= 1:
+        res = [_ext_solve_one(j) for j in jobs]
+    else:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            res = list(ex.map(_ext_solve_one, jobs))
+    return tuple(np.stack([r[x] for r in res]) for x in range(6))
+
+
+def brute_ext_objective(T, I4, l, P):
+    """Exhaustive D[l][0..P)[0..1] for the first l layers (l - 1 <= 9)."""
+    ld = T.shape[1]
+    assert T.dtype == np.int32 and I4.dtype == np.float32
+    assert T.flags.c_contiguous and I4.flags.c_contiguous and 1 <= l <= 10
+    out = np.empty((P, 2), np.float32)
+    _load_ext().brute_ext_objective(ld, _p(T), _p(I4), l, P, _p(out))
+    return out

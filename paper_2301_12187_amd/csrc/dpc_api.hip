@@ -46,7 +46,7 @@ const char* dpc_status_string(int code)
 int dpc_set_stage2_variant(int variant)
 {
     if (!((variant >= 0 && variant <= 3) || (variant >= 21 && variant <= 26) ||
-          (variant >= 31 && variant <= 37)))
+          (variant >= 31 && variant <= 39)))
         return DPC_ERR_SHAPE;
     int prev = g_stage2_variant;
     g_stage2_variant = variant;

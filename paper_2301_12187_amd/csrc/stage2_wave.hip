@@ -611,6 +611,8 @@ hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const fl
         case 5: return launch_wave_cfg<16, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         case 6: return launch_wave_cfg<16, 8, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         case 7: return launch_wave_cfg<16, 2, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 8: return launch_wave_cfg<16, 16, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 9: return launch_wave_cfg<8, 16, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         default: return hipErrorInvalidValue;
     }
 }

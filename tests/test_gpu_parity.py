@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 VARIANTS = [1, 2, 3]
 SHAPES = [21, 22, 23, 24, 25, 26,      # every task shape of the tiled kernel
-          31, 32, 33, 34, 35, 36, 37]  # ... and of the wave-window kernel
+          31, 32, 33, 34, 35, 36, 37, 38, 39]  # ... of the wave-window kernel
 
 
 def _all_budgets(B, P, step=1):
