@@ -147,6 +147,72 @@ int dpc_backtrack(int32_t B, int32_t L, int32_t P, const int32_t *Topt,
                   int32_t *S_len, float *obj, int32_t *lat, int32_t *status,
                   void *stream);
 
+/*
+ * ---- Extended solver (Appendix B of the paper, "Extension on the Importance") ----
+ *
+ * The importance of a block now depends on whether the activations at its two
+ * end points are kept: I4[k][l][a][b], a = flag at k, b = flag at l (1 = a
+ * non-identity activation).  The objective is the sum of I4 along a chain
+ * 0 -> B -> L of block boundaries, with flag 1 exactly at the members of A
+ * (A inside B), under the same latency budget on 0 -> S -> L (A inside S).
+ * Combinations a caller wants to exclude carry -inf in I4 (first lines of
+ * Algorithm 3).  The flags at the two ends of the network are free.
+ * Tables with flags are row-major [B][L+1][L+1][2][2].  1 <= L <= DPC_EXT_MAX_L.
+ *
+ * dpc_ext_importance_maxplus - Algorithm 3:
+ *     Iopt[k][l][a][b] = max over chains k -> (interior points with flag 0) -> l
+ *                        of the binary32 left-to-right sum of I4 along the chain,
+ *     bsplit[k][l][a][b] = its last interior point m (B_opt[k,l,a,b] =
+ *                        B_opt[k,m,a,0] + {m}), or k for the single block; the
+ *                        single block, then the lowest m, wins ties.
+ *   I4      in   float [B][L+1][L+1][2][2]   finite or -inf; only k < l is read
+ *   Iopt    out  float, bsplit out uint8, same shape; entries with k >= l are 0
+ */
+#define DPC_EXT_MAX_L 126      /* the 2L+3 states (layer, flag) index one byte   */
+
+int dpc_ext_importance_maxplus(int32_t B, int32_t L, const float *I4, float *Iopt,
+                               uint8_t *bsplit, void *stream);
+
+/*
+ * dpc_ext_knapsack - Algorithm 4 for every budget at once:
+ *     D[0][t][a] = +0,
+ *     D[l][t][a] = max over k' < l, alpha' in {0,1}, Topt[k'][l] <= t of
+ *                  fl32( D[k'][t - Topt[k'][l]][alpha'] + Iopt[k'][l][alpha'][a] ),
+ *     the lowest (k', alpha') attaining it is kept as 2k' + alpha'.
+ * It runs as the stage-2 recurrence on the chain of states v = 2l + a:
+ *   D    out  float [B][2L+3][P]   row 2l+a is D[l][.][a]; the last row, 2L+2,
+ *                                  is max over a of D[L][.][a] (the solution)
+ *   Kx   out  uint8 [B][2L+3][P]   row 2l+a: 2k'+alpha' of the arg-max; last
+ *                                  row: 2L + a_last; DPC_NOARG where nothing
+ *                                  reaches; must not be NULL for dpc_ext_backtrack
+ *   Topt in   from dpc_stage1_minplus;  Iopt in  from dpc_ext_importance_maxplus
+ *   workspace   at least dpc_ext_workspace_bytes(B, L, P) bytes, 256-byte
+ *               aligned, private to the call while its work is queued
+ * dpc_ext_check is dpc_stage2_check for such a workspace.
+ */
+size_t dpc_ext_workspace_bytes(int32_t B, int32_t L, int32_t P);
+
+int dpc_ext_knapsack(int32_t B, int32_t L, int32_t P, const int32_t *Topt, const float *Iopt,
+                     float *D, uint8_t *Kx, void *workspace, size_t workspace_bytes,
+                     void *stream);
+
+int dpc_ext_check(int32_t B, int32_t L, int32_t P, const void *workspace, void *stream);
+
+/*
+ * dpc_ext_backtrack - the sets of Algorithm 4 for Q queries (instance, budget):
+ * A (activations kept), S (merge boundaries, A inside S) and B (block
+ * boundaries of the objective, A inside B), each ascending in int32 [Q][L]
+ * with its length; obj = D[L][T0][a_last], a_last = the better final flag
+ * (lowest on ties), lat = summed latency of 0 -> S -> L.  status and the
+ * values for a status other than DPC_Q_OK are as in dpc_backtrack.
+ */
+int dpc_ext_backtrack(int32_t B, int32_t L, int32_t P, const int32_t *Topt,
+                      const uint8_t *split, const uint8_t *bsplit, const float *D,
+                      const uint8_t *Kx, int32_t Q, const int32_t *q_inst,
+                      const int32_t *q_T0, int32_t *A, int32_t *A_len, int32_t *S,
+                      int32_t *S_len, int32_t *Bs, int32_t *B_len, float *obj,
+                      int32_t *lat, int32_t *a_last, int32_t *status, void *stream);
+
 /* Name of a DPC_ERR_* code (static string, never NULL). */
 const char *dpc_status_string(int code);
 

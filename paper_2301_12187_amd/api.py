@@ -22,6 +22,8 @@ EXPORTS = (
     "dpc_stage1_minplus", "dpc_stage2_workspace_bytes", "dpc_stage2_knapsack",
     "dpc_stage2_check", "dpc_backtrack", "dpc_status_string",
     "dpc_set_stage2_variant",
+    "dpc_ext_importance_maxplus", "dpc_ext_workspace_bytes", "dpc_ext_knapsack",
+    "dpc_ext_check", "dpc_ext_backtrack",
 )
 
 _lib = None
@@ -167,3 +169,105 @@ def solve(T, I, q_inst, q_T0, buf: Buffers, stream=None):
     dpc_stage2_knapsack(buf.Topt, I, buf.M, buf.K, buf.workspace, stream)
     dpc_backtrack(buf.Topt, buf.split, I, buf.M, buf.K, q_inst, q_T0, buf.A, buf.A_len,
                   buf.S, buf.S_len, buf.obj, buf.lat, buf.status, stream)
+
+
+# ---- extended solver (Appendix B of the paper) ----
+
+DPC_EXT_MAX_L = 126
+EXT_EXPORTS = ("dpc_ext_importance_maxplus", "dpc_ext_workspace_bytes", "dpc_ext_knapsack",
+               "dpc_ext_check", "dpc_ext_backtrack")
+
+
+def _load_ext():
+    lib = load()
+    if not getattr(lib, "_ext_ready", False):
+        i32, vp, sz = ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+        lib.dpc_ext_importance_maxplus.argtypes = [i32, i32, vp, vp, vp, vp]
+        lib.dpc_ext_importance_maxplus.restype = ctypes.c_int
+        lib.dpc_ext_workspace_bytes.argtypes = [i32, i32, i32]
+        lib.dpc_ext_workspace_bytes.restype = sz
+        lib.dpc_ext_knapsack.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.dpc_ext_knapsack.restype = ctypes.c_int
+        lib.dpc_ext_check.argtypes = [i32, i32, i32, vp, vp]
+        lib.dpc_ext_check.restype = ctypes.c_int
+        lib.dpc_ext_backtrack.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, i32] + [vp] * 13
+        lib.dpc_ext_backtrack.restype = ctypes.c_int
+        lib._ext_ready = True
+    return lib
+
+
+def dpc_ext_importance_maxplus(I4, Iopt, bsplit, stream=None):
+    B, ld = I4.shape[0], I4.shape[1]
+    shp = (B, ld, ld, 2, 2)
+    _check(_load_ext().dpc_ext_importance_maxplus(
+        B, ld - 1, _dev(I4, torch.float32, shp, "I4"), _dev(Iopt, torch.float32, shp, "Iopt"),
+        _dev(bsplit, torch.uint8, shp, "bsplit"), _stream(stream)))
+
+
+def dpc_ext_workspace_bytes(B, L, P):
+    return int(_load_ext().dpc_ext_workspace_bytes(B, L, P))
+
+
+def dpc_ext_knapsack(Topt, Iopt, D, Kx, workspace, stream=None):
+    B, ld, _ = Topt.shape
+    L, P = ld - 1, D.shape[2]
+    V = 2 * L + 3
+    _check(_load_ext().dpc_ext_knapsack(
+        B, L, P, _dev(Topt, torch.int32, (B, ld, ld), "Topt"),
+        _dev(Iopt, torch.float32, (B, ld, ld, 2, 2), "Iopt"),
+        _dev(D, torch.float32, (B, V, P), "D"), _dev(Kx, torch.uint8, (B, V, P), "Kx"),
+        ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+
+
+def dpc_ext_check(B, L, P, workspace, stream=None):
+    _check(_load_ext().dpc_ext_check(B, L, P, ctypes.c_void_p(workspace.data_ptr()),
+                                     _stream(stream)))
+
+
+def dpc_ext_backtrack(Topt, split, bsplit, D, Kx, q_inst, q_T0, A, A_len, S, S_len, Bs, B_len,
+                      obj, lat, a_last, status, stream=None):
+    B, ld, _ = Topt.shape
+    L, P, Q = ld - 1, D.shape[2], q_inst.shape[0]
+    V = 2 * L + 3
+    if Q == 0:
+        return
+    i32 = torch.int32
+    _check(_load_ext().dpc_ext_backtrack(
+        B, L, P, _dev(Topt, i32, (B, ld, ld), "Topt"), _dev(split, torch.uint8, (B, ld, ld), "split"),
+        _dev(bsplit, torch.uint8, (B, ld, ld, 2, 2), "bsplit"),
+        _dev(D, torch.float32, (B, V, P), "D"), _dev(Kx, torch.uint8, (B, V, P), "Kx"), Q,
+        _dev(q_inst, i32, (Q,), "q_inst"), _dev(q_T0, i32, (Q,), "q_T0"),
+        _dev(A, i32, (Q, L), "A"), _dev(A_len, i32, (Q,), "A_len"),
+        _dev(S, i32, (Q, L), "S"), _dev(S_len, i32, (Q,), "S_len"),
+        _dev(Bs, i32, (Q, L), "Bs"), _dev(B_len, i32, (Q,), "B_len"),
+        _dev(obj, torch.float32, (Q,), "obj"), _dev(lat, i32, (Q,), "lat"),
+        _dev(a_last, i32, (Q,), "a_last"), _dev(status, i32, (Q,), "status"), _stream(stream)))
+
+
+class ExtBuffers:
+    """Device buffers of the extended solver for one problem shape."""
+
+    def __init__(self, B, L, P, Q, device="cuda:0"):
+        self.B, self.L, self.P, self.Q = B, L, P, Q
+        ld, V = L + 1, 2 * L + 3
+        dev = torch.device(device)
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)  # noqa: E731
+        self.Topt, self.split = e((B, ld, ld), torch.int32), e((B, ld, ld), torch.uint8)
+        self.Iopt, self.bsplit = e((B, ld, ld, 2, 2), torch.float32), e((B, ld, ld, 2, 2), torch.uint8)
+        self.D, self.Kx = e((B, V, P), torch.float32), e((B, V, P), torch.uint8)
+        self.workspace = e((max(dpc_ext_workspace_bytes(B, L, P), 256),), torch.uint8)
+        self.A, self.S, self.Bs = (e((Q, L), torch.int32) for _ in range(3))
+        self.A_len, self.S_len, self.B_len, self.lat, self.a_last, self.status = (
+            e((Q,), torch.int32) for _ in range(6))
+        self.obj = e((Q,), torch.float32)
+
+
+def ext_solve(T, I4, q_inst, q_T0, buf: ExtBuffers, stream=None):
+    """The extended path on device tensors: Algorithm 1, Algorithm 3,
+    Algorithm 4 and set recovery, queued on `stream` without waiting."""
+    dpc_stage1_minplus(T, buf.Topt, buf.split, stream)
+    dpc_ext_importance_maxplus(I4, buf.Iopt, buf.bsplit, stream)
+    dpc_ext_knapsack(buf.Topt, buf.Iopt, buf.D, buf.Kx, buf.workspace, stream)
+    dpc_ext_backtrack(buf.Topt, buf.split, buf.bsplit, buf.D, buf.Kx, q_inst, q_T0, buf.A,
+                      buf.A_len, buf.S, buf.S_len, buf.Bs, buf.B_len, buf.obj, buf.lat,
+                      buf.a_last, buf.status, stream)

@@ -26,6 +26,45 @@ bool shape_ok(int B, int L, int P)
            (int64_t)B * (L + 1) * (int64_t)P < ((int64_t)1 << 40);
 }
 
+// the stage-2 kernel family selected by dpc_set_stage2_variant, on checked arguments
+int stage2_dispatch(int B, int L, int P, const int32_t* Topt, const float* I, float* M, uint8_t* K,
+                    void* workspace, hipStream_t stream)
+{
+    hipError_t e;
+    if (g_stage2_variant == 1) {
+        // the row family uses no workspace; clear the header so that a later
+        // dpc_stage2_check reads "no error"
+        e = dpc::launch_clear_words(workspace, 2, stream);
+        if (e == hipSuccess) e = dpc::launch_stage2_rows(B, L, P, Topt, I, M, K, stream);
+    } else {
+        const int ncu = num_compute_units();
+        if (ncu <= 0) return DPC_ERR_HIP;
+        // the wave-window family reads whole 16-byte cells: narrow tables stay tiled
+        const bool wave = (g_stage2_variant == 0 || g_stage2_variant == 3 || g_stage2_variant > 30) &&
+                          P >= 16;
+        e = wave ? dpc::launch_stage2_wave(B, L, P, Topt, I, M, K, workspace, ncu, stream)
+                 : dpc::launch_stage2_tiled(B, L, P, Topt, I, M, K, workspace, ncu, stream);
+    }
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+// layout of the extended solver's workspace: the two virtual tables, then the
+// stage-2 workspace of the chain of 2L+2 virtual layers
+struct ExtLayout { size_t tv_off, iv_off, s2_off, total; };
+ExtLayout ext_layout(int B, int L, int P)
+{
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t V = 2 * (size_t)L + 3;
+    ExtLayout l;
+    l.tv_off = 0;
+    l.iv_off = up(4 * (size_t)B * V * V);
+    l.s2_off = l.iv_off + up(4 * (size_t)B * V * V);
+    l.total = l.s2_off + dpc::stage2_workspace_bytes(B, 2 * L + 2, P);
+    return l;
+}
+
+bool ext_shape_ok(int B, int L, int P) { return L >= 1 && L <= DPC_EXT_MAX_L && shape_ok(B, 2 * L + 2, P); }
+
 }  // namespace
 
 extern "C" {
@@ -78,25 +117,7 @@ int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, co
     if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
     if (workspace_bytes < dpc_stage2_workspace_bytes(B, L, P) || ((uintptr_t)workspace & 255))
         return DPC_ERR_WORKSPACE;
-    hipError_t e;
-    if (g_stage2_variant == 1) {
-        // the row family uses no workspace; clear the header so that a later
-        // dpc_stage2_check reads "no error"
-        e = dpc::launch_clear_words(workspace, 2, (hipStream_t)stream);
-        if (e == hipSuccess)
-            e = dpc::launch_stage2_rows(B, L, P, Topt, I, M, K, (hipStream_t)stream);
-    } else {
-        const int ncu = num_compute_units();
-        if (ncu <= 0) return DPC_ERR_HIP;
-        // the wave-window family reads whole 16-byte cells: narrow tables stay tiled
-        const bool wave = (g_stage2_variant == 0 || g_stage2_variant == 3 || g_stage2_variant > 30) &&
-                          P >= 16;
-        e = wave ? dpc::launch_stage2_wave(B, L, P, Topt, I, M, K, workspace, ncu,
-                                           (hipStream_t)stream)
-                 : dpc::launch_stage2_tiled(B, L, P, Topt, I, M, K, workspace, ncu,
-                                            (hipStream_t)stream);
-    }
-    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+    return stage2_dispatch(B, L, P, Topt, I, M, K, workspace, (hipStream_t)stream);
 }
 
 int dpc_stage2_check(const void* workspace, void* stream)
@@ -124,6 +145,62 @@ int dpc_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const ui
         return DPC_ERR_NULL;
     hipError_t e = dpc::launch_backtrack(B, L, P, Topt, split, I, M, K, Q, q_inst, q_T0, A, A_len,
                                          S, S_len, obj, lat, status, (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+int dpc_ext_importance_maxplus(int32_t B, int32_t L, const float* I4, float* Iopt, uint8_t* bsplit,
+                               void* stream)
+{
+    if (!I4 || !Iopt || !bsplit) return DPC_ERR_NULL;
+    if (!shape_ok(B, L, 1)) return DPC_ERR_SHAPE;
+    hipError_t e = dpc::launch_ext_iopt(B, L, I4, Iopt, bsplit, (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+size_t dpc_ext_workspace_bytes(int32_t B, int32_t L, int32_t P)
+{
+    if (!ext_shape_ok(B, L, P)) return 0;
+    return ext_layout(B, L, P).total;
+}
+
+int dpc_ext_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const float* Iopt,
+                     float* D, uint8_t* Kx, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!Topt || !Iopt || !D || !workspace) return DPC_ERR_NULL;
+    if (!ext_shape_ok(B, L, P)) return DPC_ERR_SHAPE;
+    if (workspace_bytes < dpc_ext_workspace_bytes(B, L, P) || ((uintptr_t)workspace & 255))
+        return DPC_ERR_WORKSPACE;
+    const ExtLayout lay = ext_layout(B, L, P);
+    char* base = (char*)workspace;
+    int32_t* Tv = (int32_t*)(base + lay.tv_off);
+    float* Iv = (float*)(base + lay.iv_off);
+    hipError_t e = dpc::launch_ext_expand(B, L, Topt, Iopt, Tv, Iv, (hipStream_t)stream);
+    if (e != hipSuccess) return DPC_ERR_HIP;
+    return stage2_dispatch(B, 2 * L + 2, P, Tv, Iv, D, Kx, base + lay.s2_off, (hipStream_t)stream);
+}
+
+int dpc_ext_check(int32_t B, int32_t L, int32_t P, const void* workspace, void* stream)
+{
+    if (!workspace) return DPC_ERR_NULL;
+    if (!ext_shape_ok(B, L, P)) return DPC_ERR_SHAPE;
+    return dpc_stage2_check((const char*)workspace + ext_layout(B, L, P).s2_off, stream);
+}
+
+int dpc_ext_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const uint8_t* split,
+                      const uint8_t* bsplit, const float* D, const uint8_t* Kx, int32_t Q,
+                      const int32_t* q_inst, const int32_t* q_T0, int32_t* A, int32_t* A_len,
+                      int32_t* S, int32_t* S_len, int32_t* Bs, int32_t* B_len, float* obj,
+                      int32_t* lat, int32_t* a_last, int32_t* status, void* stream)
+{
+    if (Q < 0) return DPC_ERR_SHAPE;
+    if (!ext_shape_ok(B, L, P)) return DPC_ERR_SHAPE;
+    if (Q == 0) return DPC_OK;
+    if (!Topt || !split || !bsplit || !D || !Kx || !q_inst || !q_T0 || !A || !A_len || !S ||
+        !S_len || !Bs || !B_len || !obj || !lat || !a_last || !status)
+        return DPC_ERR_NULL;
+    hipError_t e = dpc::launch_ext_backtrack(B, L, P, Topt, split, bsplit, D, Kx, Q, q_inst, q_T0,
+                                             A, A_len, S, S_len, Bs, B_len, obj, lat, a_last,
+                                             status, (hipStream_t)stream);
     return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
 }
 

@@ -28,4 +28,16 @@ hipError_t launch_backtrack(int B, int L, int P, const int32_t* Topt, const uint
                             int32_t* A_len, int32_t* S, int32_t* S_len, float* obj,
                             int32_t* lat, int32_t* status, hipStream_t st);
 
+// extended solver (Appendix B): Algorithm 3, the virtual tables of Algorithm 4, set recovery
+hipError_t launch_ext_iopt(int B, int L, const float* I4, float* Iopt, uint8_t* bsplit,
+                           hipStream_t st);
+hipError_t launch_ext_expand(int B, int L, const int32_t* Topt, const float* Iopt, int32_t* Tv,
+                             float* Iv, hipStream_t st);
+hipError_t launch_ext_backtrack(int B, int L, int P, const int32_t* Topt, const uint8_t* split,
+                                const uint8_t* bsplit, const float* D, const uint8_t* Kx, int Q,
+                                const int32_t* q_inst, const int32_t* q_T0, int32_t* A,
+                                int32_t* A_len, int32_t* S, int32_t* S_len, int32_t* Bs,
+                                int32_t* B_len, float* obj, int32_t* lat, int32_t* a_last,
+                                int32_t* status, hipStream_t st);
+
 }  // namespace dpc

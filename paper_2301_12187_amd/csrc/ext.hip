@@ -1,0 +1,234 @@
+// Extended solver (Appendix B of the paper, "Extension on the Importance"):
+// block importances I[k][l][a][b] that depend on whether the activations at the
+// two ends of the block are kept (a at k, b at l).
+//
+//   ext_iopt_kernel      Algorithm 3: I_opt[k][l][a][b] = the best chain of
+//                        blocks from k to l whose interior end points carry an
+//                        identity activation (flag 0), as a max-plus interval
+//                        DP, with the arg-max pointers of B_opt.
+//   ext_expand_kernel    Algorithm 4 is Algorithm 2 on the states (l, a): they
+//                        are laid out as a chain of 2L+3 virtual layers,
+//                        v = 2l + a, plus one last layer that takes the better
+//                        of (L, 0) and (L, 1); this kernel writes the virtual
+//                        latency and importance tables, on which the ordinary
+//                        stage-2 kernels then run unchanged.  Predecessors in
+//                        ascending v are the (k', alpha') pairs in ascending
+//                        order, so arg-max ties break as in the paper's loop.
+//   ext_backtrack_kernel the set updates of Algorithm 4 (A, S, B) unrolled
+//                        through the stored pointers.
+#include "dpc_internal.h"
+
+namespace dpc {
+
+constexpr int X1_WAVES = 4;       // waves per workgroup
+constexpr int X1_U = 4;           // targets per lane: L <= 255
+
+__device__ __forceinline__ size_t i4_index(int ld, int k, int l, int a, int b)
+{
+    return ((((size_t)k * ld + l) * 2 + a) * 2 + b);
+}
+
+// One wave per (instance, k, a).  Lanes own the targets l = lane + 64u, both
+// end flags b.  The running maximum starts from the single block (k, l) with
+// flags (a, b); the wave then walks the split points m = k+1, k+2, ... in
+// ascending order and pushes I_opt[k][m][a][0] + I[m][l][0][b] to every l > m.
+// When the walk reaches m every smaller split point has been pushed, so the
+// owner lane's maximum for b = 0 is the final I_opt[k][m][a][0]; it is
+// broadcast with a lane read.  A candidate replaces the maximum only when
+// strictly greater: the single block, then the lowest m, wins ties.
+__global__ __launch_bounds__(64 * X1_WAVES) void ext_iopt_kernel(
+    int L, const float* __restrict__ I4, float* __restrict__ Iopt, uint8_t* __restrict__ bsplit)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * X1_WAVES + (threadIdx.x >> 6);   // = 2k + a
+    const int k = w >> 1, a = w & 1;
+    const int b = blockIdx.y;
+    if (k > L) return;                      // whole wave leaves together
+    const int ld = L + 1;
+    const size_t inst = (size_t)b * ld * ld * 4;
+    const float* Ib = I4 + inst;
+
+    float best[X1_U][2];
+    int arg[X1_U][2];
+#pragma unroll
+    for (int u = 0; u < X1_U; ++u) {
+        const int l = lane + 64 * u;
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            best[u][f] = (l > k && l <= L) ? Ib[i4_index(ld, k, l, a, f)] : -INFINITY;
+            arg[u][f] = k;
+        }
+    }
+    for (int m = k + 1; m < L; ++m) {
+        float own = best[0][0];
+        const int um = m >> 6;
+#pragma unroll
+        for (int u = 1; u < X1_U; ++u) own = (um == u) ? best[u][0] : own;
+        const float vm = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, own), m & 63));
+#pragma unroll
+        for (int u = 0; u < X1_U; ++u) {
+            const int l = lane + 64 * u;
+            if (l > m && l <= L) {
+#pragma unroll
+                for (int f = 0; f < 2; ++f) {
+                    const float c = vm + Ib[i4_index(ld, m, l, 0, f)];
+                    if (c > best[u][f]) { best[u][f] = c; arg[u][f] = m; }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < X1_U; ++u) {
+        const int l = lane + 64 * u;
+        if (l <= L) {
+            const bool upper = l > k;
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                Iopt[inst + i4_index(ld, k, l, a, f)] = upper ? best[u][f] : 0.0f;
+                bsplit[inst + i4_index(ld, k, l, a, f)] = upper ? (uint8_t)arg[u][f] : (uint8_t)0;
+            }
+        }
+    }
+}
+
+// Virtual tables of the chain of states: V = 2L+3 layers.  v = 2l + a for
+// 0 <= l <= L; v = 2L+2 is the final layer.  An entry (u, v), u < v:
+//   u = 0, v = 1          latency 0, importance +0  (D[0][t][1] = D[0][t][0] = +0)
+//   same l, u != v        none
+//   v <= 2L+1             latency Topt[k'][l], importance I_opt[k'][l][alpha'][a]
+//   v = 2L+2              from (L, 0) and (L, 1): latency 0, importance +0
+// "None" is latency DPC_INF (no budget reaches it) and importance -inf.
+__global__ __launch_bounds__(256) void ext_expand_kernel(
+    int L, const int32_t* __restrict__ Topt, const float* __restrict__ Iopt,
+    int32_t* __restrict__ Tv, float* __restrict__ Iv)
+{
+    const int V = 2 * L + 3, ld = L + 1;
+    const int b = blockIdx.y;
+    const int x = blockIdx.x * 256 + threadIdx.x;
+    if (x >= V * V) return;
+    const int u = x / V, v = x - u * V;
+    int32_t t = DPC_INF;
+    float imp = -INFINITY;
+    if (u < v) {
+        const int kp = u >> 1, al = u & 1, l = v >> 1, a = v & 1;
+        if (v == V - 1) {
+            if (kp == L) { t = 0; imp = 0.0f; }
+        } else if (kp < l) {
+            t = Topt[(size_t)b * ld * ld + (size_t)kp * ld + l];
+            imp = Iopt[(size_t)b * ld * ld * 4 + i4_index(ld, kp, l, al, a)];
+        } else if (u == 0 && v == 1) {
+            t = 0;
+            imp = 0.0f;
+        }
+    }
+    Tv[(size_t)b * V * V + x] = t;
+    Iv[(size_t)b * V * V + x] = imp;
+}
+
+// One lane per query: from the final layer at budget T0 back to layer 0.
+__global__ __launch_bounds__(64) void ext_backtrack_kernel(
+    int B, int L, int P, const int32_t* __restrict__ Topt, const uint8_t* __restrict__ split,
+    const uint8_t* __restrict__ bsplit, const float* __restrict__ D,
+    const uint8_t* __restrict__ Kx, int Q, const int32_t* __restrict__ q_inst,
+    const int32_t* __restrict__ q_T0, int32_t* A, int32_t* __restrict__ A_len, int32_t* S,
+    int32_t* __restrict__ S_len, int32_t* Bs, int32_t* __restrict__ B_len,
+    float* __restrict__ obj, int32_t* __restrict__ lat, int32_t* __restrict__ a_last,
+    int32_t* __restrict__ status)
+{
+    const int q = blockIdx.x * 64 + threadIdx.x;
+    if (q >= Q) return;
+    const int b = q_inst[q];
+    const int T0 = q_T0[q];
+    const int ld = L + 1, V = 2 * L + 3;
+    int st = DPC_Q_OK;
+    if (b < 0 || b >= B || T0 < 0 || T0 >= P) st = DPC_Q_BAD_QUERY;
+    float top = -INFINITY;
+    const float* Db = nullptr;
+    const uint8_t* Kb = nullptr;
+    if (st == DPC_Q_OK) {
+        Db = D + (size_t)b * V * P;
+        Kb = Kx + (size_t)b * V * P;
+        top = Db[(size_t)(V - 1) * P + T0];
+        if (top == -INFINITY) st = DPC_Q_INFEASIBLE;
+    }
+    if (st != DPC_Q_OK) {
+        A_len[q] = -1; S_len[q] = -1; B_len[q] = -1; obj[q] = -INFINITY; lat[q] = -1;
+        a_last[q] = -1; status[q] = st;
+        return;
+    }
+    const int32_t* To = Topt + (size_t)b * ld * ld;
+    const uint8_t* Sp = split + (size_t)b * ld * ld;
+    const uint8_t* Bp = bsplit + (size_t)b * ld * ld * 4;
+    int32_t* Aq = A + (size_t)q * L;
+    int32_t* Sq = S + (size_t)q * L;
+    int32_t* Bq = Bs + (size_t)q * L;
+    int na = 0, ns = 0, nb = 0, total = 0;
+    int v = Kb[(size_t)(V - 1) * P + T0];       // (L, a_last)
+    int l = v >> 1, a = v & 1, t = T0;
+    const int alast = a;
+    if (l != L) l = 0;                           // defensive: never true for stage-2 output
+    // members come out from high to low and strictly decrease (enforced below),
+    // so no list can hold more than L-1 entries whatever the tables contain
+    while (l > 0) {
+        const int u = Kb[(size_t)(2 * l + a) * P + t];
+        const int k = u >> 1, al = u & 1;
+        if (k >= l) break;                       // defensive
+        for (int x = l;;) {
+            const int m = Sp[k * ld + x];
+            if (m <= k || m >= x) break;         // m == k ends S_opt[k,l]; the rest is defensive
+            Sq[ns++] = m;
+            x = m;
+        }
+        for (int x = l, f = a;;) {
+            const int m = Bp[i4_index(ld, k, x, al, f)];
+            if (m <= k || m >= x) break;
+            Bq[nb++] = m;
+            x = m;
+            f = 0;
+        }
+        if (k > 0) {
+            if (al) Aq[na++] = k;
+            Sq[ns++] = k;
+            Bq[nb++] = k;
+        }
+        const int32_t w = To[k * ld + l];
+        if (w > t) break;                        // defensive
+        total += w; t -= w; l = k; a = al;
+    }
+    for (int x = 0, y = na - 1; x < y; ++x, --y) { const int32_t z = Aq[x]; Aq[x] = Aq[y]; Aq[y] = z; }
+    for (int x = 0, y = ns - 1; x < y; ++x, --y) { const int32_t z = Sq[x]; Sq[x] = Sq[y]; Sq[y] = z; }
+    for (int x = 0, y = nb - 1; x < y; ++x, --y) { const int32_t z = Bq[x]; Bq[x] = Bq[y]; Bq[y] = z; }
+    A_len[q] = na; S_len[q] = ns; B_len[q] = nb; obj[q] = top; lat[q] = total;
+    a_last[q] = alast; status[q] = DPC_Q_OK;
+}
+
+hipError_t launch_ext_iopt(int B, int L, const float* I4, float* Iopt, uint8_t* bsplit, hipStream_t st)
+{
+    dim3 grid((2 * (L + 1) + X1_WAVES - 1) / X1_WAVES, B);
+    hipLaunchKernelGGL(ext_iopt_kernel, grid, dim3(64 * X1_WAVES), 0, st, L, I4, Iopt, bsplit);
+    return hipGetLastError();
+}
+
+hipError_t launch_ext_expand(int B, int L, const int32_t* Topt, const float* Iopt, int32_t* Tv,
+                             float* Iv, hipStream_t st)
+{
+    const int V = 2 * L + 3;
+    dim3 grid((V * V + 255) / 256, B);
+    hipLaunchKernelGGL(ext_expand_kernel, grid, dim3(256), 0, st, L, Topt, Iopt, Tv, Iv);
+    return hipGetLastError();
+}
+
+hipError_t launch_ext_backtrack(int B, int L, int P, const int32_t* Topt, const uint8_t* split,
+                                const uint8_t* bsplit, const float* D, const uint8_t* Kx, int Q,
+                                const int32_t* q_inst, const int32_t* q_T0, int32_t* A,
+                                int32_t* A_len, int32_t* S, int32_t* S_len, int32_t* Bs,
+                                int32_t* B_len, float* obj, int32_t* lat, int32_t* a_last,
+                                int32_t* status, hipStream_t st)
+{
+    hipLaunchKernelGGL(ext_backtrack_kernel, dim3((Q + 63) / 64), dim3(64), 0, st, B, L, P, Topt,
+                       split, bsplit, D, Kx, Q, q_inst, q_T0, A, A_len, S, S_len, Bs, B_len, obj,
+                       lat, a_last, status);
+    return hipGetLastError();
+}
+
+}  // namespace dpc

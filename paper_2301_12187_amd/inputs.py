@@ -126,3 +126,44 @@ def relax_ops_exact(B, L, P):
 
 def relax_ops_nominal(B, L, P):
     return B * L * L * P
+
+
+# ---- extended solver (Appendix B of the paper): importances with end flags ----
+
+def make_flag_importances(I, seed_words, ident_every=3, bonus=0.02):
+    """Flag-dependent importances I4 [L+1][L+1][2][2] around a plain table I.
+
+    Stand-in for the paper's 315 measured MobileNetV2 blocks (Appendix B.2): the
+    original activation is an identity at every `ident_every`-th layer (the end
+    of an inverted-residual block) and at the two ends of the network.  Keeping
+    an activation where the original has an identity adds a small positive
+    amount, drawn per (block, end), as the paper reports non-linearities at
+    those positions to help.  Then the exclusions of the first lines of
+    Algorithm 3:
+      I4[k][l][0][b] = -inf where the original activation at k is not an identity,
+      I4[k][l][a][0] = -inf where the original activation at l is not an identity,
+      I4[k][l][a][0] = -inf where both are identities.
+    """
+    L = I.shape[0] - 1
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([*seed_words, 77])))
+    ident = np.zeros(L + 1, bool)
+    ident[::ident_every] = True
+    ident[0] = ident[L] = True
+    gain = rng.exponential(bonus, size=(L + 1, L + 1, 2)).astype(np.float32)
+    I4 = np.repeat(np.repeat(I[:, :, None, None], 2, axis=2), 2, axis=3).astype(np.float32)
+    I4[:, :, 1, :] += (gain[:, :, 0] * ident[:, None])[:, :, None]
+    I4[:, :, :, 1] += (gain[:, :, 1] * ident[None, :])[:, :, None]
+    ninf = np.float32(-np.inf)
+    I4[~ident, :, 0, :] = ninf
+    I4[:, ~ident, :, 0] = ninf
+    both = ident[:, None] & ident[None, :]
+    I4[both, :, 0] = ninf
+    I4 = I4 + np.float32(0.0)
+    return np.ascontiguousarray(I4)
+
+
+def make_ext_batch(cfg, seed=0, B=None):
+    """-> (T, I4 float32 [B][L+1][L+1][2][2], base) for the extended solver."""
+    T, I, base = make_batch(cfg, seed=seed, B=B)
+    I4 = np.stack([make_flag_importances(I[b], (seed, cfg.cid, b)) for b in range(T.shape[0])])
+    return T, I4, base
