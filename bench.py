@@ -35,9 +35,9 @@ if ROOT not in sys.path:
 METRIC = "DP relax-ops/sec (B·L²·P) + batch solve latency ms, 1×MI355X"
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9        # 39.3e12
 # HBM bytes (read + written) per stage-2 launch from the rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs summarised in profiles/stage2_tiled_kernel_cfg5.md, keyed by
+# WRITE_SIZE runs summarised in profiles/stage2_wave_kernel_cfg5.md, keyed by
 # (config, variant); None where not measured.
-MEASURED_TRAFFIC = {(5, 0): 10.58e9 + 1.197e9}
+MEASURED_TRAFFIC = {(5, 0): 5.848e9 + 1.185e9}
 
 
 def main():
@@ -50,6 +50,10 @@ def main():
     ap.add_argument("--no-K", action="store_true", help="do not store back-pointers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--ext", action="store_true",
+                    help="time the extended solver (Appendix B: Algorithms 1, 3, 4 and set "
+                         "recovery) on the flag-dependent version of --config (default 3, the "
+                         "MobileNetV2-shaped batch) instead of the headline workload")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference point for the "
                          "FETCH_SIZE / WRITE_SIZE counters), print its size and exit")
@@ -74,6 +78,8 @@ def main():
                           "launches": 3}))
         return
 
+    if args.ext:
+        return bench_ext(args, np, torch, api, inputs)
     cfg = inputs.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -174,6 +180,79 @@ def main():
             "sample": f"{nb} of {cfg.B} instances of {cfg.name}, all stages, "
                       f"{tc1 - tc0:.2f} s wall",
         }
+    print(json.dumps(out))
+
+
+def bench_ext(args, np, torch, api, inputs):
+    """Extended solver: one step = dpc_stage1_minplus + dpc_ext_importance_maxplus +
+    dpc_ext_knapsack + dpc_ext_backtrack.  A relax-op is one candidate
+    (instance, k', alpha', l, a, t) of Algorithm 4: four per pair (k', l) and budget."""
+    cid = 3 if args.config == 5 else args.config
+    cfg = inputs.CONFIGS[cid]
+    if cfg.L > api.DPC_EXT_MAX_L:
+        print(f"bench.py --ext: L = {cfg.L} exceeds the extended solver's limit", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    T, I4, base = inputs.make_ext_batch(cfg, seed=args.seed)
+    qi, qt = inputs.budgets(cfg, base)
+    Td, Id = torch.from_numpy(T).to(dev), torch.from_numpy(I4).to(dev)
+    qid, qtd = torch.from_numpy(qi).to(dev), torch.from_numpy(qt).to(dev)
+    buf = api.ExtBuffers(cfg.B, cfg.L, cfg.P, len(qi))
+    api.dpc_set_stage2_variant(args.variant)
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        api.ext_solve(Td, Id, qid, qtd, buf)
+    api.dpc_ext_check(cfg.B, cfg.L, cfg.P, buf.workspace)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for ev in evs:
+        ev[0].record(stream)
+        api.dpc_stage1_minplus(Td, buf.Topt, buf.split)
+        ev[1].record(stream)
+        api.dpc_ext_importance_maxplus(Id, buf.Iopt, buf.bsplit)
+        ev[2].record(stream)
+        api.dpc_ext_knapsack(buf.Topt, buf.Iopt, buf.D, buf.Kx, buf.workspace)
+        ev[3].record(stream)
+        api.dpc_ext_backtrack(buf.Topt, buf.split, buf.bsplit, buf.D, buf.Kx, qid, qtd, buf.A,
+                              buf.A_len, buf.S, buf.S_len, buf.Bs, buf.B_len, buf.obj, buf.lat,
+                              buf.a_last, buf.status)
+        ev[4].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    api.dpc_ext_check(cfg.B, cfg.L, cfg.P, buf.workspace)
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    seg = [[e[x].elapsed_time(e[x + 1]) for e in evs] for x in range(4)]
+    exact = 4 * inputs.relax_ops_exact(cfg.B, cfg.L, cfg.P)
+    s2 = float(np.mean(seg[2]))
+    out = {
+        "metric": "extended-solver relax-ops/sec (4 per pair and budget) + batch solve latency ms, 1xMI355X",
+        "value": exact / (ms_step * 1e-3), "unit": "relax-ops/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "extended solver on " + cfg.name, "B": cfg.B, "L": cfg.L, "P": cfg.P,
+                   "queries": int(len(qi)), "stage2_variant": args.variant, "seed": args.seed},
+        "stage_ms": {"stage1": float(np.mean(seg[0])), "importance_maxplus": float(np.mean(seg[1])),
+                     "knapsack": s2, "backtrack": float(np.mean(seg[3]))},
+        "feasible_queries": int((buf.status == 0).sum().item()),
+        "roofline": {"bound": "alu", "kernel": "Algorithm 4 (dpc_ext_knapsack)",
+                     "achieved": 4 * exact / (s2 * 1e-3) / 1e12, "peak": VALU_PEAK_LANE_OPS / 1e12,
+                     "unit": "TOP/s", "frac": 4 * exact / (s2 * 1e-3) / VALU_PEAK_LANE_OPS,
+                     "ops_per_relax": 4, "traffic": None},
+    }
+    if not args.no_cpu:
+        import oracle
+        cores = min(16, os.cpu_count() or 1)
+        nb = cfg.B
+        tc0 = time.perf_counter()
+        res = oracle.ext_solve_batch(T[:nb], I4[:nb], cfg.P, threads=cores)
+        for b, t in zip(qi[qi < nb], qt[qi < nb]):
+            oracle.ext_backtrack(res[0][b], res[1][b], res[3][b], res[4][b], res[5][b], int(t))
+        tc1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": 4 * inputs.relax_ops_exact(nb, cfg.L, cfg.P) / (tc1 - tc0),
+                               "unit": "relax-ops/s", "cores": min(cores, nb), "kind": "oracle",
+                               "sample": f"{nb} of {cfg.B} instances, all stages, {tc1 - tc0:.2f} s wall"}
     print(json.dumps(out))
 
 
