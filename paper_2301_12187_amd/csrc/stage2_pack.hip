@@ -82,6 +82,19 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
             for (int t = i; t < P; t += 256) K0[t] = (uint8_t)DPC_NOARG;
         }
     }
+    // the R columns j0 .. j0+R-1 of Topt and I, staged through LDS so that the
+    // loads run along the rows (R consecutive words per row)
+    __shared__ int32_t sT[256][R + 1];
+    __shared__ float sI[256][R + 1];
+    for (int x = i; x < ld * R; x += 256) {
+        const int row = x / R, rr = x - row * R;
+        const int j = j0 + rr;
+        if (j <= L) {
+            sT[row][rr] = To[row * ld + j];
+            sI[row][rr] = Ib[row * ld + j];
+        }
+    }
+    __syncthreads();
     S2Rec rec[H];
     int wv[R];
     int mins = 0x7FFFFFFF, maxs = -1;
@@ -91,10 +104,10 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
         int w = -1;
         float imp = -INFINITY;
         if (i < ld && j <= L && i < j) {
-            const int v = To[i * ld + j];
+            const int v = sT[i][rr];
             if (v >= 0 && v < P) {
                 w = v;
-                imp = Ib[i * ld + j];
+                imp = sI[i][rr];
                 mins = min(mins, w);
                 maxs = max(maxs, w);
             }
@@ -159,61 +172,79 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
 }
 
 // Task table: entries in ticket order (level-major, then instance), the task
-// list (entry and strip of every ticket) and the total.  One workgroup walks
-// the entries in tiles of 1024, one entry per thread (so that its stores are
+// list (entry and strip of every ticket) and the total.  One workgroup per
+// level.  It first counts the tickets of all lower levels (every thread sums
+// the groups of some instances, then one reduction), then walks its own
+// entries in tiles of 1024, one entry per thread (so that its stores are
 // coalesced), with a running prefix sum of the strip counts: wave scan, then
-// one combine of the 16 wave totals per tile.  The per-group decisions are
-// first brought into LDS when they fit.
-constexpr int S2_LAYOUT_CACHE = 12288;
+// one combine of the 16 wave totals per tile.
 __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     int B, int L, int P, int NQ, int R, int wcap, const int32_t* __restrict__ groups,
     S2Entry* __restrict__ entries, S2Task* __restrict__ tasks, S2Header* hdr)
 {
     __shared__ int wsum[2][16];
-    __shared__ int gcache[S2_LAYOUT_CACHE];
+    __shared__ int red[16];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int N = NQ * R * B;
-    const bool cached = B * NQ <= S2_LAYOUT_CACHE;
-    if (cached)
-        for (int x = tid; x < B * NQ; x += 1024) gcache[x] = groups[x];
-    __syncthreads();
-    auto group_of = [&](int b, int q) { return cached ? gcache[b * NQ + q] : groups[(size_t)b * NQ + q]; };
-    auto count = [&](int b, int q, int sub) {
-        const int hq = min(R, L - q * R);
-        const int grp = group_of(b, q);
-        // the first strip starts at t = 0 and has no ghost columns
-        if (grp >= 0)
-            return sub != 0 ? 0 : P <= wcap ? 1 : 1 + (P - wcap + (wcap - grp) - 1) / (wcap - grp);
-        return sub < hq ? (P + wcap - 1) / wcap : 0;
+    const int level = blockIdx.x;                   // = q * R + sub
+    const int q = level / R, sub = level % R;
+    const int strips1 = (P + wcap - 1) / wcap;      // tasks of a one-row level
+    auto group_of = [&](int b, int qq) { return groups[(size_t)b * NQ + qq]; };
+    // tasks of a whole group with ghost width grp: the first strip starts at
+    // t = 0 and has no ghost columns
+    auto whole_count = [&](int grp) {
+        return P <= wcap ? 1 : 1 + (P - wcap + (wcap - grp) - 1) / (wcap - grp);
     };
-    // the entry whose rows the entry (level, b) needs last, its task count and
+    auto count = [&](int b, int qq, int ss) {
+        const int hq = min(R, L - qq * R);
+        const int grp = group_of(b, qq);
+        if (grp >= 0) return ss != 0 ? 0 : whole_count(grp);
+        return ss < hq ? strips1 : 0;
+    };
+    // the entry whose rows the entry (lev, b) needs last, its task count and
     // the first row it writes
-    auto pred = [&](int level, int b, int& prev, int& prev_cnt, int& prev_row0) {
-        const int q = level / R, sub = level % R;
+    auto pred = [&](int lev, int b, int& prev, int& prev_cnt, int& prev_row0) {
+        const int qq = lev / R, ss = lev % R;
         prev = -1;
         prev_cnt = 0;
         prev_row0 = -1;
-        if (sub > 0) {
-            prev = (level - 1) * B + b;
-            prev_cnt = count(b, q, sub - 1);
-            prev_row0 = q * R + sub;
-        } else if (q > 0) {
-            const bool whole = group_of(b, q - 1) >= 0;
+        if (ss > 0) {
+            prev = (lev - 1) * B + b;
+            prev_cnt = count(b, qq, ss - 1);
+            prev_row0 = qq * R + ss;
+        } else if (qq > 0) {
+            const bool whole = group_of(b, qq - 1) >= 0;
             const int psub = whole ? 0 : R - 1;
-            prev = ((q - 1) * R + psub) * B + b;
-            prev_cnt = count(b, q - 1, psub);
-            prev_row0 = 1 + (q - 1) * R + psub;
+            prev = ((qq - 1) * R + psub) * B + b;
+            prev_cnt = count(b, qq - 1, psub);
+            prev_row0 = 1 + (qq - 1) * R + psub;
         }
     };
-    int base = 0;                                   // tickets before this tile
-    for (int e0 = 0, it = 0; e0 < N; e0 += 1024, ++it) {
-        const int e = e0 + tid;
+
+    // ---- tickets before this level
+    int part = 0;
+    for (int b = tid; b < B; b += 1024)
+        for (int qq = 0; qq <= q; ++qq) {
+            const int below = qq < q ? R : sub;     // levels of group qq that lie below this one
+            if (below == 0) continue;
+            const int grp = group_of(b, qq);
+            part += grp >= 0 ? whole_count(grp) : strips1 * min(below, min(R, L - qq * R));
+        }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
+    if (lane == 0) red[wave] = part;
+    __syncthreads();
+    int base = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) base += red[w];
+
+    // ---- this level's entries and tasks
+    for (int b0 = 0, it = 0; b0 < B; b0 += 1024, ++it) {
+        const int b = b0 + tid;
+        const int e = level * B + b;
         int c = 0, g = -1;
         int prev = -1, prev_cnt = 0, prev_row0 = -1, prev2 = -1, prev2_cnt = 0, unused = -1;
-        if (e < N) {
-            const int level = e / B, b = e - level * B;
-            const int q = level / R, sub = level % R;
+        if (b < B) {
             c = count(b, q, sub);
             const int grp = group_of(b, q);
             g = grp >= 0 && sub == 0 ? grp : -1;
@@ -237,7 +268,7 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
             tile_total += v;
         }
         const int tstart = base + before + incl - c;
-        if (e < N) {
+        if (b < B) {
             S2Entry en;
             en.cnt = c;
             en.prev = prev;
@@ -257,8 +288,10 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
         }
         base += tile_total;
     }
-    if (tid == 0) hdr->total = (uint32_t)base;
-    if (tid < 4) hdr->ninf[tid] = -INFINITY;
+    if (blockIdx.x == gridDim.x - 1) {
+        if (tid == 0) hdr->total = (uint32_t)base;
+        if (tid < 4) hdr->ninf[tid] = -INFINITY;
+    }
 }
 
 hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt, const float* I,
@@ -285,7 +318,7 @@ hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt
                            recs, infos, shifts, groups, gmax, dmax, wcap, ahead, M, K);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(stage2_layout_kernel, dim3(1), dim3(1024), 0, st, B, L, P, NQ, R, wcap,
+    hipLaunchKernelGGL(stage2_layout_kernel, dim3(NQ * R), dim3(1024), 0, st, B, L, P, NQ, R, wcap,
                        (const int32_t*)groups, (S2Entry*)(base + lay.entry_off),
                        (S2Task*)(base + lay.task_off), (S2Header*)base);
     return hipGetLastError();

@@ -53,7 +53,7 @@ struct Barrier {                       // reusable barrier for the threads of on
 };
 inline Barrier g_barrier;
 inline Barrier g_wave_barrier[16];     // the lanes of a wave run in lockstep on the GPU
-inline thread_local dim3 t_threadIdx, t_blockIdx, t_blockDim;
+inline thread_local dim3 t_threadIdx, t_blockIdx, t_blockDim, t_gridDim;
 inline int g_exchange[1024];
 
 struct Region { const char* lo; const char* hi; const char* name; };
@@ -72,26 +72,31 @@ inline void check_global(const void* p, size_t n, const char* what)
 inline const char* g_lds_lo = nullptr;
 inline const char* g_lds_hi = nullptr;
 
-// runs the blocks of a grid one after the other, the threads of a block concurrently
+// runs the blocks of a grid one after the other, the threads of a block
+// concurrently; the host threads are created once per launch and walk the
+// blocks together (a barrier between two blocks: they share the static
+// stand-ins of the kernel's LDS arrays)
 template <class F>
 void launch(dim3 grid, dim3 block, F&& body)
 {
     const int nt = (int)block.x;
-    for (unsigned by = 0; by < grid.y; ++by)
-        for (unsigned bx = 0; bx < grid.x; ++bx) {
-            g_barrier.n = nt;
-            for (int w = 0; w < 16; ++w) g_wave_barrier[w].n = std::min(64, nt);
-            std::vector<std::thread> th;
-            th.reserve(nt);
-            for (int t = 0; t < nt; ++t)
-                th.emplace_back([&, t] {
+    g_barrier.n = nt;
+    for (int w = 0; w < 16; ++w) g_wave_barrier[w].n = std::min(64, nt);
+    std::vector<std::thread> th;
+    th.reserve(nt);
+    for (int t = 0; t < nt; ++t)
+        th.emplace_back([&, t] {
+            for (unsigned by = 0; by < grid.y; ++by)
+                for (unsigned bx = 0; bx < grid.x; ++bx) {
                     t_threadIdx = dim3(t);
                     t_blockIdx = dim3(bx, by);
                     t_blockDim = block;
+                    t_gridDim = grid;
                     body();
-                });
-            for (auto& x : th) x.join();
-        }
+                    g_barrier.wait();
+                }
+        });
+    for (auto& x : th) x.join();
 }
 
 }  // namespace emu
@@ -99,13 +104,14 @@ void launch(dim3 grid, dim3 block, F&& body)
 #define threadIdx emu::t_threadIdx
 #define blockIdx emu::t_blockIdx
 #define blockDim emu::t_blockDim
+#define gridDim emu::t_gridDim
 #define hipLaunchKernelGGL(kernel, grid, block, shmem, stream, ...) \
     emu::launch(grid, block, [&] { kernel(__VA_ARGS__); })
 
 inline void __syncthreads() { emu::g_barrier.wait(); }
+inline void wave_sync() { emu::g_wave_barrier[((int)threadIdx.x >> 6) & 15].wait(); }
 template <class T> inline T __builtin_amdgcn_readfirstlane(T v) { return v; }
 inline void __builtin_amdgcn_s_sleep(int) { std::this_thread::yield(); }
-inline void wave_sync() { emu::g_wave_barrier[((int)threadIdx.x >> 6) & 15].wait(); }
 // (only used to wait for global -> LDS copies, which are synchronous here: what is
 //  left of the wait is that every lane of the wave has made its copy)
 inline void __builtin_amdgcn_s_waitcnt(int) { wave_sync(); }
@@ -122,14 +128,25 @@ template <class T> inline void __hip_atomic_store(T* p, T v, int order, int) { _
 template <class T> inline T __hip_atomic_fetch_add(T* p, T v, int order, int) { return __atomic_fetch_add(p, v, order); }
 inline unsigned atomicAdd(unsigned* p, unsigned v) { return __atomic_fetch_add(p, v, __ATOMIC_RELAXED); }
 
-// value of lane (lane - d) of the same 64-lane wave; every thread of the block calls it
+// value of lane (lane - d) of the same 64-lane wave; every lane of the wave calls it
 inline int __shfl_up(int v, int d, int)
 {
     const int t = (int)threadIdx.x;
     emu::g_exchange[t] = v;
-    __syncthreads();
+    wave_sync();
     const int r = (t & 63) >= d ? emu::g_exchange[t - d] : v;
-    __syncthreads();
+    wave_sync();
+    return r;
+}
+
+// value of lane (lane ^ d) of the same wave; every lane of the wave calls it
+inline int __shfl_xor(int v, int d, int)
+{
+    const int t = (int)threadIdx.x;
+    emu::g_exchange[t] = v;
+    wave_sync();
+    const int r = emu::g_exchange[t ^ d];
+    wave_sync();
     return r;
 }
 
