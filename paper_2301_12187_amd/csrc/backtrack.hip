@@ -1,44 +1,43 @@
 // Set recovery: A[L,T0] and S[L,T0] of Algorithm 2 (set updates Eq. 7a/7b of
 // the paper) rebuilt from the stored arg-max pointers K and, inside every
-// block (i, j) of the chain, the arg-min pointers of Algorithm 1.  One lane per
-// query; at most L pointer steps plus at most L split steps, all integer.
-// The walk visits indices from high to low; the members are written in that
-// order and each list is then reversed in place.  Members strictly decrease
-// along the walk (i < m < l <= j is enforced), so both sets hold at most L-1
-// entries whatever the tables contain.
+// block (i, j) of the chain, the arg-min pointers of Algorithm 1.
+//
+// One 64-lane wave per query; everything that steers the walk is
+// wave-uniform.  Per block of the chain the wave reads one arg-max byte, one
+// latency and the row i of `split` (L+1 bytes, one byte per lane and 64
+// targets), and then follows the arg-min pointers inside the block through
+// lane reads of that row instead of dependent loads.  Members come out from
+// high to low into two lists in LDS and are written out in ascending order at
+// the end.  Members strictly decrease along the walk (i < m < l <= j is
+// enforced), so both sets hold at most L-1 entries whatever the tables
+// contain.  Without stored pointers (K == NULL) the arg-max of a visited cell
+// is found again as the lowest i whose candidate reproduces the stored cell
+// bit for bit: the lanes test 64 predecessors at a time.
 #include "dpc_internal.h"
 
 namespace dpc {
 
-__device__ __forceinline__ int argmax_of_cell(int L, int P, const int32_t* To, const float* Ib,
-                                              const float* Mb, const uint8_t* Kb, int j, int t)
-{
-    if (Kb) return Kb[(size_t)j * P + t];
-    // no stored pointer: the lowest i whose candidate equals the stored cell
-    const int ld = L + 1;
-    const float want = Mb[(size_t)j * P + t];
-    for (int i = 0; i < j; ++i) {
-        const int32_t w = To[i * ld + j];
-        if (w <= t) {
-            const float c = Mb[(size_t)i * P + (t - w)] + Ib[i * ld + j];
-            if (c == want) return i;
-        }
-    }
-    return DPC_NOARG;   // unreachable for a table produced by stage 2
-}
+constexpr int BT_WAVES = 4;        // queries per workgroup
+constexpr int BT_U = 4;            // bytes of a split row per lane: L <= 255
 
-__global__ __launch_bounds__(64) void backtrack_kernel(
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__global__ __launch_bounds__(64 * BT_WAVES) void backtrack_kernel(
     int B, int L, int P, const int32_t* __restrict__ Topt, const uint8_t* __restrict__ split,
     const float* __restrict__ I, const float* __restrict__ M, const uint8_t* __restrict__ K,
     int Q, const int32_t* __restrict__ q_inst, const int32_t* __restrict__ q_T0,
-    int32_t* A, int32_t* __restrict__ A_len, int32_t* S,
+    int32_t* __restrict__ A, int32_t* __restrict__ A_len, int32_t* __restrict__ S,
     int32_t* __restrict__ S_len, float* __restrict__ obj, int32_t* __restrict__ lat,
     int32_t* __restrict__ status)
 {
-    const int q = blockIdx.x * 64 + threadIdx.x;
-    if (q >= Q) return;
-    const int b = q_inst[q];
-    const int T0 = q_T0[q];
+    __shared__ int32_t listA[BT_WAVES][256];
+    __shared__ int32_t listS[BT_WAVES][256];
+    const int lane = threadIdx.x & 63;
+    const int wv = uniform(threadIdx.x >> 6);
+    const int q = blockIdx.x * BT_WAVES + wv;
+    if (q >= Q) return;                     // whole wave leaves together
+    const int b = uniform(q_inst[q]);
+    const int T0 = uniform(q_T0[q]);
     int st = DPC_Q_OK;
     if (b < 0 || b >= B || T0 < 0 || T0 >= P) st = DPC_Q_BAD_QUERY;
     const int ld = L + 1;
@@ -54,46 +53,73 @@ __global__ __launch_bounds__(64) void backtrack_kernel(
         Ib = I + (size_t)b * ld * ld;
         Mb = M + (size_t)b * ld * P;
         Kb = K ? K + (size_t)b * ld * P : nullptr;
-        top = Mb[(size_t)L * P + T0];
+        top = __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, Mb[(size_t)L * P + T0])));
         if (top == -INFINITY) st = DPC_Q_INFEASIBLE;
     }
     if (st != DPC_Q_OK) {
-        A_len[q] = -1; S_len[q] = -1; obj[q] = -INFINITY; lat[q] = -1; status[q] = st;
+        if (lane == 0) {
+            A_len[q] = -1; S_len[q] = -1; obj[q] = -INFINITY; lat[q] = -1; status[q] = st;
+        }
         return;
     }
-    // one walk: members come out from high to low and are written in that order,
-    // then each list is reversed in place by the same lane
     int na = 0, ns = 0, total = 0;
+    int j = L, t = T0;
+    while (j > 0) {
+        int i;
+        if (Kb) {
+            i = uniform((int)Kb[(size_t)j * P + t]);
+        } else {
+            // no stored pointer: the lowest i whose candidate equals the stored cell
+            const float want = Mb[(size_t)j * P + t];
+            i = DPC_NOARG;                  // unreachable for a table produced by stage 2
+            for (int i0 = 0; i0 < j && i == DPC_NOARG; i0 += 64) {
+                const int ic = i0 + lane;
+                bool hit = false;
+                if (ic < j) {
+                    const int32_t w = To[ic * ld + j];
+                    if (w <= t) hit = Mb[(size_t)ic * P + (t - w)] + Ib[ic * ld + j] == want;
+                }
+                const unsigned long long mask = __ballot(hit);
+                if (mask != 0) i = i0 + __builtin_ctzll(mask);
+            }
+        }
+        if (i >= j) break;                  // defensive: never true for stage-2 output
+        const int32_t w = uniform(To[i * ld + j]);
+        // row i of split: byte l sits in lane l & 63, register l >> 6
+        int row[BT_U];
+#pragma unroll
+        for (int u = 0; u < BT_U; ++u) {
+            const int l = lane + 64 * u;
+            row[u] = l <= L ? (int)Sp[i * ld + l] : 0;
+        }
+        int l = j;
+        for (;;) {
+            int src = row[0];
+#pragma unroll
+            for (int u = 1; u < BT_U; ++u) src = (l >> 6) == u ? row[u] : src;
+            const int m = __builtin_amdgcn_readlane(src, l & 63);
+            if (m <= i || m >= l) break;    // m == i ends S_opt[i,j]; the rest is defensive
+            if (lane == 0) listS[wv][ns] = m;
+            ++ns;
+            l = m;
+        }
+        if (i > 0) {
+            if (lane == 0) { listA[wv][na] = i; listS[wv][ns] = i; }
+            ++na;
+            ++ns;
+        }
+        if (w > t) break;                   // defensive: never true for stage-2 output
+        total += w; t -= w; j = i;
+    }
+    // the lists were filled from high to low: write them out ascending
+    // (same wave wrote and reads the LDS lists: no barrier needed beyond its own order)
     int32_t* Aq = A + (size_t)q * L;
     int32_t* Sq = S + (size_t)q * L;
-    {
-        int j = L, t = T0;
-        while (j > 0) {
-            const int i = argmax_of_cell(L, P, To, Ib, Mb, Kb, j, t);
-            if (i >= j) break;              // defensive: never true for stage-2 output
-            int l = j;
-            for (;;) {
-                const int m = Sp[i * ld + l];
-                if (m <= i || m >= l) break;   // m == i ends S_opt[i,j]; the rest is defensive
-                Sq[ns++] = m;
-                l = m;
-            }
-            if (i > 0) {
-                Aq[na++] = i;
-                Sq[ns++] = i;
-            }
-            const int32_t w = To[i * ld + j];
-            if (w > t) break;               // defensive: never true for stage-2 output
-            total += w; t -= w; j = i;
-        }
+    for (int x = lane; x < na; x += 64) Aq[x] = listA[wv][na - 1 - x];
+    for (int x = lane; x < ns; x += 64) Sq[x] = listS[wv][ns - 1 - x];
+    if (lane == 0) {
+        A_len[q] = na; S_len[q] = ns; obj[q] = top; lat[q] = total; status[q] = DPC_Q_OK;
     }
-    for (int a = 0, b2 = na - 1; a < b2; ++a, --b2) {
-        const int32_t x = Aq[a]; Aq[a] = Aq[b2]; Aq[b2] = x;
-    }
-    for (int a = 0, b2 = ns - 1; a < b2; ++a, --b2) {
-        const int32_t x = Sq[a]; Sq[a] = Sq[b2]; Sq[b2] = x;
-    }
-    A_len[q] = na; S_len[q] = ns; obj[q] = top; lat[q] = total; status[q] = DPC_Q_OK;
 }
 
 hipError_t launch_backtrack(int B, int L, int P, const int32_t* Topt, const uint8_t* split,
@@ -102,9 +128,9 @@ hipError_t launch_backtrack(int B, int L, int P, const int32_t* Topt, const uint
                             int32_t* A_len, int32_t* S, int32_t* S_len, float* obj,
                             int32_t* lat, int32_t* status, hipStream_t st)
 {
-    dim3 grid((Q + 63) / 64);
-    hipLaunchKernelGGL(backtrack_kernel, grid, dim3(64), 0, st, B, L, P, Topt, split, I, M, K, Q,
-                       q_inst, q_T0, A, A_len, S, S_len, obj, lat, status);
+    dim3 grid((Q + BT_WAVES - 1) / BT_WAVES);
+    hipLaunchKernelGGL(backtrack_kernel, grid, dim3(64 * BT_WAVES), 0, st, B, L, P, Topt, split, I,
+                       M, K, Q, q_inst, q_T0, A, A_len, S, S_len, obj, lat, status);
     return hipGetLastError();
 }
 

@@ -16,9 +16,9 @@
 namespace dpc {
 
 constexpr int S1_WAVES = 4;       // waves per workgroup
-constexpr int S1_U = 4;           // targets per lane: L <= 255
-constexpr int S1_AHEAD = 8;       // source rows fetched per batch
 
+// S1_U: targets per lane (64 * S1_U > L); S1_AHEAD: source rows fetched per batch
+template <int S1_U, int S1_AHEAD>
 __global__ __launch_bounds__(64 * S1_WAVES) void stage1_kernel(
     int L, const int32_t* __restrict__ T, int32_t* __restrict__ Topt,
     uint8_t* __restrict__ split)
@@ -88,7 +88,14 @@ hipError_t launch_stage1(int B, int L, const int32_t* T, int32_t* Topt, uint8_t*
                          hipStream_t st)
 {
     dim3 grid((L + 1 + S1_WAVES - 1) / S1_WAVES, B);
-    hipLaunchKernelGGL(stage1_kernel, grid, dim3(64 * S1_WAVES), 0, st, L, T, Topt, split);
+    // short chains keep one or two targets per lane: fewer instructions per
+    // step and room to fetch more source rows at once
+    if (L < 64)
+        hipLaunchKernelGGL((stage1_kernel<1, 16>), grid, dim3(64 * S1_WAVES), 0, st, L, T, Topt, split);
+    else if (L < 128)
+        hipLaunchKernelGGL((stage1_kernel<2, 8>), grid, dim3(64 * S1_WAVES), 0, st, L, T, Topt, split);
+    else
+        hipLaunchKernelGGL((stage1_kernel<4, 8>), grid, dim3(64 * S1_WAVES), 0, st, L, T, Topt, split);
     return hipGetLastError();
 }
 
