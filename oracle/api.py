@@ -247,3 +247,51 @@ def brute_ext_objective(T, I4, l, P):
     out = np.empty((P, 2), np.float32)
     _load_ext().brute_ext_objective(ld, _p(T), _p(I4), l, P, _p(out))
     return out
+
+
+# ---- steps around the solver in a sweep (importance normalisation, trade-off
+#      curve, latency of a network merged at a given set) ----
+
+def _load_sweep():
+    lib = _load()
+    if not getattr(lib, "_sweep_ready", False):
+        i32, vp = ctypes.c_int32, ctypes.c_void_p
+        lib.oracle_importance_shift.argtypes = [i32, i32, vp, ctypes.c_float, vp]
+        lib.oracle_importance_shift.restype = ctypes.c_double
+        lib.oracle_front.argtypes = [i32, vp, i32, vp, vp]
+        lib.oracle_front.restype = i32
+        lib.oracle_chain_latency.argtypes = [i32, vp, i32, vp]
+        lib.oracle_chain_latency.restype = i32
+        lib._sweep_ready = True
+    return lib
+
+
+def importance_shift(I_raw, alpha):
+    """I_raw float32 [L+1][L+1] or [L+1][L+1][2][2] -> (shifted table, mean of D)."""
+    L = I_raw.shape[0] - 1
+    F = 1 if I_raw.ndim == 2 else 4
+    _chk(I_raw, np.float32, (L + 1, L + 1) if F == 1 else (L + 1, L + 1, 2, 2))
+    out = np.empty_like(I_raw)
+    mean = _load_sweep().oracle_importance_shift(L, F, _p(I_raw), float(np.float32(alpha)), _p(out))
+    return out, mean
+
+
+def front(Mrow, cap=None):
+    """Mrow float32 [P] -> (budgets int32 [n], objectives float32 [n], count)."""
+    P = Mrow.shape[0]
+    _chk(Mrow, np.float32, (P,))
+    cap = P if cap is None else cap
+    ft = np.full(cap, -1, np.int32)
+    fo = np.full(cap, -np.inf, np.float32)
+    n = _load_sweep().oracle_front(P, _p(Mrow), cap, _p(ft), _p(fo))
+    return ft[:min(n, cap)], fo[:min(n, cap)], n
+
+
+def chain_latency(T, X):
+    """T int32 [L+1][L+1], X ascending members of [1, L-1] (None: no set) -> int."""
+    L = T.shape[0] - 1
+    _chk(T, np.int32, (L + 1, L + 1))
+    if X is None:
+        return _load_sweep().oracle_chain_latency(L, _p(T), -1, None)
+    X = np.ascontiguousarray(X, np.int32)
+    return _load_sweep().oracle_chain_latency(L, _p(T), len(X), _p(X))

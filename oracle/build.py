@@ -7,7 +7,8 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ["dpc_oracle.c", "dpc_brute.c", "dpc_ext_oracle.c", "dpc_ext_brute.c"]
+SOURCES = ["dpc_oracle.c", "dpc_brute.c", "dpc_ext_oracle.c", "dpc_ext_brute.c",
+           "dpc_sweep_oracle.c"]
 LIB = os.path.join(HERE, "liboracle.so")
 
 
