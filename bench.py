@@ -54,6 +54,9 @@ def main():
                     help="time the extended solver (Appendix B: Algorithms 1, 3, 4 and set "
                          "recovery) on the flag-dependent version of --config (default 3, the "
                          "MobileNetV2-shaped batch) instead of the headline workload")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time a sweep over the normalisation constant alpha: shift, solve, "
+                         "trade-off curves, set recovery, latency merged at A (cfg3 shape by default)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference point for the "
                          "FETCH_SIZE / WRITE_SIZE counters), print its size and exit")
@@ -80,6 +83,8 @@ def main():
 
     if args.ext:
         return bench_ext(args, np, torch, api, inputs)
+    if args.sweep:
+        return bench_sweep(args, np, torch, api, inputs)
     cfg = inputs.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -253,6 +258,109 @@ def bench_ext(args, np, torch, api, inputs):
         out["cpu_baseline"] = {"value": 4 * inputs.relax_ops_exact(nb, cfg.L, cfg.P) / (tc1 - tc0),
                                "unit": "relax-ops/s", "cores": min(cores, nb), "kind": "oracle",
                                "sample": f"{nb} of {cfg.B} instances, all stages, {tc1 - tc0:.2f} s wall"}
+    print(json.dumps(out))
+
+
+def bench_sweep(args, np, torch, api, inputs):
+    """Sweep over the normalisation constant: one step = dpc_importance_shift (n_raw tables x
+    n_alpha constants -> B instances) + stage 1 + stage 2 + dpc_front + dpc_backtrack +
+    dpc_chain_latency at A."""
+    cid = 3 if args.config == 5 else args.config
+    cfg = inputs.CONFIGS[cid]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    n_alpha = 16 if cfg.B >= 16 else 1
+    T0, I_raw, base, alphas = inputs.make_sweep_batch(cfg, seed=args.seed, n_alpha=n_alpha)
+    n_raw = T0.shape[0]
+    B = n_raw * n_alpha
+    T = np.repeat(T0, n_alpha, axis=0)
+    qi, qt = inputs.budgets(cfg, np.repeat(base, n_alpha, axis=0))
+    Td = torch.from_numpy(T).to(dev)
+    Ird = torch.from_numpy(I_raw).to(dev)
+    ald = torch.from_numpy(alphas).to(dev)
+    qid, qtd = torch.from_numpy(qi).to(dev), torch.from_numpy(qt).to(dev)
+    buf = api.Buffers(B, cfg.L, cfg.P, len(qi), store_K=True)
+    Id = torch.empty((B, cfg.L + 1, cfg.L + 1), dtype=torch.float32, device=dev)
+    cap = 256
+    ft = torch.empty((B, cap), dtype=torch.int32, device=dev)
+    fo = torch.empty((B, cap), dtype=torch.float32, device=dev)
+    fl = torch.empty((B,), dtype=torch.int32, device=dev)
+    latA = torch.empty((len(qi),), dtype=torch.int32, device=dev)
+    api.dpc_set_stage2_variant(args.variant)
+    stream = torch.cuda.current_stream()
+    names = ["importance_shift", "stage1", "stage2", "front", "backtrack", "chain_latency"]
+
+    def step(ev=None):
+        calls = [
+            lambda: api.dpc_importance_shift(Ird, ald, Id),
+            lambda: api.dpc_stage1_minplus(Td, buf.Topt, buf.split),
+            lambda: api.dpc_stage2_knapsack(buf.Topt, Id, buf.M, buf.K, buf.workspace),
+            lambda: api.dpc_front(buf.M, ft, fo, fl),
+            lambda: api.dpc_backtrack(buf.Topt, buf.split, Id, buf.M, buf.K, qid, qtd, buf.A,
+                                      buf.A_len, buf.S, buf.S_len, buf.obj, buf.lat, buf.status),
+            lambda: api.dpc_chain_latency(Td, qid, buf.A, buf.A_len, latA),
+        ]
+        for x, call in enumerate(calls):
+            if ev:
+                ev[x].record(stream)
+            call()
+        if ev:
+            ev[len(calls)].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    api.dpc_stage2_check(buf.workspace)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for ev in evs:
+        step(ev)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    api.dpc_stage2_check(buf.workspace)
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    seg = {n: float(np.mean([e[x].elapsed_time(e[x + 1]) for e in evs])) for x, n in enumerate(names)}
+    exact = inputs.relax_ops_exact(B, cfg.L, cfg.P)
+    ok = buf.status == 0
+    out = {
+        "metric": "sweep over the normalisation constant: relax-ops/sec (B*L^2*P) + batch latency ms, 1xMI355X",
+        "value": inputs.relax_ops_nominal(B, cfg.L, cfg.P) / (ms_step * 1e-3), "unit": "relax-ops/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"alpha sweep on {cfg.name}", "raw_tables": n_raw, "alphas": n_alpha,
+                   "B": B, "L": cfg.L, "P": cfg.P, "queries": int(len(qi)), "front_cap": cap,
+                   "stage2_variant": args.variant, "seed": args.seed},
+        "stage_ms": seg,
+        "feasible_queries": int(ok.sum().item()),
+        "mean_front_points": float(fl.float().mean().item()),
+        # merging at A alone needs every block between two kept activations to be one layer
+        "mergeable_at_A": int((ok & (latA < api.DPC_INF)).sum().item()),
+        "mean_latency_merged_at_A_over_S": float(
+            (latA[ok & (latA < api.DPC_INF)].double()
+             / buf.lat[ok & (latA < api.DPC_INF)].double().clamp(min=1)).mean().item()),
+        "roofline": {"bound": "alu", "kernel": "stage 2 (dpc_stage2_knapsack)",
+                     "achieved": 4 * exact / (seg["stage2"] * 1e-3) / 1e12,
+                     "peak": VALU_PEAK_LANE_OPS / 1e12, "unit": "TOP/s",
+                     "frac": 4 * exact / (seg["stage2"] * 1e-3) / VALU_PEAK_LANE_OPS,
+                     "ops_per_relax": 4, "traffic": None},
+    }
+    if not args.no_cpu:
+        import oracle
+        cores = min(16, os.cpu_count() or 1)
+        tc0 = time.perf_counter()
+        Is = np.stack([oracle.importance_shift(I_raw[b // n_alpha], alphas[b % n_alpha])[0]
+                       for b in range(B)])
+        To, sp, Mo, Ko = oracle.solve_batch(T, Is, cfg.P, want_K=True, threads=cores)
+        for b in range(B):
+            oracle.front(Mo[b, cfg.L], cap)
+        for b, t in zip(qi, qt):
+            r = oracle.backtrack(To[b], sp[b], Is[b], Mo[b], Ko[b], int(t))
+            oracle.chain_latency(T[b], None if r["status"] else r["A"])
+        tc1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": inputs.relax_ops_nominal(B, cfg.L, cfg.P) / (tc1 - tc0),
+                               "unit": "relax-ops/s", "cores": min(cores, B), "kind": "oracle",
+                               "sample": f"all {B} instances, all steps, {tc1 - tc0:.2f} s wall"}
     print(json.dumps(out))
 
 

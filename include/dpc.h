@@ -235,6 +235,68 @@ const char *dpc_status_string(int code);
  */
 int dpc_set_stage2_variant(int variant);
 
+/*
+ * ---- Steps around the solver in a sweep over hyper-parameters ----
+ *
+ * dpc_importance_shift - the normalisation of the paper's appendix "Evaluating
+ * and Normalizing the Importance": every block's importance is lowered by
+ * alpha times the mean importance of the blocks of size one,
+ *     I_out[b][a][.] = fl32( I_raw[b][.] - alpha[a] * mean_b ),
+ *     mean_b = mean of the finite entries I_raw[b][i][i+1][f], 0 <= i < L
+ *              (0 when there is none),
+ * for every raw table b and every alpha a: B * n_alpha tables come out, table
+ * b * n_alpha + a belonging to (b, a), ready to be solved as that many
+ * instances.  The mean is accumulated in binary64 in ascending (i, f), the
+ * product and the difference are binary64 operations, the result is rounded to
+ * binary32 once.  -inf entries (excluded blocks) stay -inf.
+ *   F         1: tables [L+1][L+1];  4: tables with flags [L+1][L+1][2][2]
+ *   I_raw     in   float [B][L+1][L+1][F]
+ *   alpha     in   float [n_alpha]            device memory, 0 <= n_alpha <= 65535
+ *   I_out     out  float [B][n_alpha][L+1][L+1][F]   every entry is written
+ *   mean_out  out  double [B], or NULL
+ */
+int dpc_importance_shift(int32_t B, int32_t L, int32_t F, int32_t n_alpha, const float *I_raw,
+                         const float *alpha, float *I_out, double *mean_out, void *stream);
+
+/*
+ * dpc_front - the latency/objective trade-off curve of an instance, read off
+ * the last row of the table of Algorithm 2: the budgets t at which the optimum
+ * of Eq. 4 improves, M[L][t] > M[L][t-1] (column -1 counting as -inf).  At
+ * such a t the optimal (A, S) has latency exactly t; between two of them the
+ * solution does not change, so these are the only budgets a sweep over T0
+ * needs to recover sets for.
+ *   M          in   float [B][L+1][P]   from dpc_stage2_knapsack; only row L is
+ *                                       read.  For the table D of
+ *                                       dpc_ext_knapsack pass 2L+2 in place of L.
+ *   cap             room per instance in front_t / front_obj, >= 0
+ *   front_t    out  int32 [B][cap]      budgets, ascending
+ *   front_obj  out  float [B][cap]      M[L][t] at those budgets
+ *   front_len  out  int32 [B]           number of points of the curve; when it
+ *                                       exceeds cap only the first cap are
+ *                                       written.  Entries past the points
+ *                                       written are left untouched.
+ */
+int dpc_front(int32_t B, int32_t L, int32_t P, const float *M, int32_t cap, int32_t *front_t,
+              float *front_obj, int32_t *front_len, void *stream);
+
+/*
+ * dpc_chain_latency - latency of the network merged at a given ordered set X:
+ * the sum of T over consecutive members of 0 -> X -> L, saturating at DPC_INF
+ * (the constraint side of Eq. 4 with X in place of S).  With X = S of
+ * dpc_backtrack it reproduces lat; with X = A it is the latency of merging at
+ * the kept activations only, the comparison of the paper's ablation on the
+ * ordered set to be merged.
+ *   T       in   int32 [B][L+1][L+1]
+ *   q_inst  in   int32 [Q]      instance of each query
+ *   X       in   int32 [Q][L]   members ascending in [1, L-1], X_len[q] of them
+ *   X_len   in   int32 [Q]
+ *   lat     out  int32 [Q]      -1 for X_len < 0 (the "no solution" marker of
+ *                               dpc_backtrack), for an instance outside [0, B)
+ *                               and for a set that is not ascending in [1, L-1]
+ */
+int dpc_chain_latency(int32_t B, int32_t L, const int32_t *T, int32_t Q, const int32_t *q_inst,
+                      const int32_t *X, const int32_t *X_len, int32_t *lat, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

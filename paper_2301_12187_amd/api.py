@@ -24,6 +24,7 @@ EXPORTS = (
     "dpc_set_stage2_variant",
     "dpc_ext_importance_maxplus", "dpc_ext_workspace_bytes", "dpc_ext_knapsack",
     "dpc_ext_check", "dpc_ext_backtrack",
+    "dpc_importance_shift", "dpc_front", "dpc_chain_latency",
 )
 
 _lib = None
@@ -271,3 +272,62 @@ def ext_solve(T, I4, q_inst, q_T0, buf: ExtBuffers, stream=None):
     dpc_ext_backtrack(buf.Topt, buf.split, buf.bsplit, buf.D, buf.Kx, q_inst, q_T0, buf.A,
                       buf.A_len, buf.S, buf.S_len, buf.Bs, buf.B_len, buf.obj, buf.lat,
                       buf.a_last, buf.status, stream)
+
+
+# ---- steps around the solver in a sweep over hyper-parameters ----
+
+def _load_sweep():
+    lib = load()
+    if not getattr(lib, "_sweep_ready", False):
+        i32, vp = ctypes.c_int32, ctypes.c_void_p
+        lib.dpc_importance_shift.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        lib.dpc_importance_shift.restype = ctypes.c_int
+        lib.dpc_front.argtypes = [i32, i32, i32, vp, i32, vp, vp, vp, vp]
+        lib.dpc_front.restype = ctypes.c_int
+        lib.dpc_chain_latency.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
+        lib.dpc_chain_latency.restype = ctypes.c_int
+        lib._sweep_ready = True
+    return lib
+
+
+def dpc_importance_shift(I_raw, alpha, I_out, mean_out=None, stream=None):
+    """I_raw float32 [B][L+1][L+1] or [B][L+1][L+1][2][2], alpha float32 [n_alpha]
+    -> I_out float32 [B*n_alpha][...] (table b*n_alpha+a), mean_out float64 [B] or None."""
+    B, ld = I_raw.shape[0], I_raw.shape[1]
+    tail = tuple(I_raw.shape[1:])
+    if tail not in ((ld, ld), (ld, ld, 2, 2)):
+        raise DpcError(f"I_raw: expected [B][L+1][L+1] or [B][L+1][L+1][2][2], got {tuple(I_raw.shape)}")
+    F = 1 if len(tail) == 2 else 4
+    n_alpha = alpha.shape[0]
+    _check(_load_sweep().dpc_importance_shift(
+        B, ld - 1, F, n_alpha, _dev(I_raw, torch.float32, (B,) + tail, "I_raw"),
+        _dev(alpha, torch.float32, (n_alpha,), "alpha"),
+        _dev(I_out, torch.float32, (B * n_alpha,) + tail, "I_out"),
+        None if mean_out is None else _dev(mean_out, torch.float64, (B,), "mean_out"),
+        _stream(stream)))
+
+
+def dpc_front(M, front_t, front_obj, front_len, stream=None):
+    """M float32 [B][rows][P] (last row read) -> front_t int32 / front_obj float32 [B][cap],
+    front_len int32 [B]."""
+    B, rows, P = M.shape
+    cap = front_t.shape[1]
+    _check(_load_sweep().dpc_front(
+        B, rows - 1, P, _dev(M, torch.float32, (B, rows, P), "M"), cap,
+        _dev(front_t, torch.int32, (B, cap), "front_t"),
+        _dev(front_obj, torch.float32, (B, cap), "front_obj"),
+        _dev(front_len, torch.int32, (B,), "front_len"), _stream(stream)))
+
+
+def dpc_chain_latency(T, q_inst, X, X_len, lat, stream=None):
+    """T int32 [B][L+1][L+1]; X int32 [Q][L] ascending sets with lengths X_len -> lat int32 [Q]."""
+    B, ld, _ = T.shape
+    L = ld - 1
+    Q = q_inst.shape[0]
+    if Q == 0:
+        return
+    _check(_load_sweep().dpc_chain_latency(
+        B, L, _dev(T, torch.int32, (B, ld, ld), "T"), Q,
+        _dev(q_inst, torch.int32, (Q,), "q_inst"), _dev(X, torch.int32, (Q, L), "X"),
+        _dev(X_len, torch.int32, (Q,), "X_len"), _dev(lat, torch.int32, (Q,), "lat"),
+        _stream(stream)))

@@ -204,4 +204,37 @@ int dpc_ext_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, cons
     return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
 }
 
+int dpc_importance_shift(int32_t B, int32_t L, int32_t F, int32_t n_alpha, const float* I_raw,
+                         const float* alpha, float* I_out, double* mean_out, void* stream)
+{
+    if (!shape_ok(B, L, 1) || (F != 1 && F != 4) || n_alpha < 0 || n_alpha > 65535)
+        return DPC_ERR_SHAPE;
+    if (n_alpha == 0) return DPC_OK;
+    if (!I_raw || !alpha || !I_out) return DPC_ERR_NULL;
+    hipError_t e = dpc::launch_importance_shift(B, L, F, n_alpha, I_raw, alpha, I_out, mean_out,
+                                                (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+int dpc_front(int32_t B, int32_t L, int32_t P, const float* M, int32_t cap, int32_t* front_t,
+              float* front_obj, int32_t* front_len, void* stream)
+{
+    if (!shape_ok(B, L, P) || cap < 0) return DPC_ERR_SHAPE;
+    if (!M || !front_len || (cap > 0 && (!front_t || !front_obj))) return DPC_ERR_NULL;
+    hipError_t e = dpc::launch_front(B, L, P, M, cap, front_t, front_obj, front_len,
+                                     (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+int dpc_chain_latency(int32_t B, int32_t L, const int32_t* T, int32_t Q, const int32_t* q_inst,
+                      const int32_t* X, const int32_t* X_len, int32_t* lat, void* stream)
+{
+    if (Q < 0 || !shape_ok(B, L, 1)) return DPC_ERR_SHAPE;
+    if (Q == 0) return DPC_OK;
+    if (!T || !q_inst || !X || !X_len || !lat) return DPC_ERR_NULL;
+    hipError_t e = dpc::launch_chain_latency(B, L, T, Q, q_inst, X, X_len, lat,
+                                             (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
 }  // extern "C"

@@ -40,4 +40,14 @@ hipError_t launch_ext_backtrack(int B, int L, int P, const int32_t* Topt, const 
                                 int32_t* B_len, float* obj, int32_t* lat, int32_t* a_last,
                                 int32_t* status, hipStream_t st);
 
+// sweep steps: importance normalisation, trade-off curve, latency of a given merge set
+hipError_t launch_importance_shift(int B, int L, int F, int n_alpha, const float* I_raw,
+                                   const float* alpha, float* I_out, double* mean_out,
+                                   hipStream_t st);
+hipError_t launch_front(int B, int L, int P, const float* M, int cap, int32_t* front_t,
+                        float* front_obj, int32_t* front_len, hipStream_t st);
+hipError_t launch_chain_latency(int B, int L, const int32_t* T, int Q, const int32_t* q_inst,
+                                const int32_t* X, const int32_t* X_len, int32_t* lat,
+                                hipStream_t st);
+
 }  // namespace dpc

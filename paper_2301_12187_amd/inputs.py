@@ -167,3 +167,25 @@ def make_ext_batch(cfg, seed=0, B=None):
     T, I, base = make_batch(cfg, seed=seed, B=B)
     I4 = np.stack([make_flag_importances(I[b], (seed, cfg.cid, b)) for b in range(T.shape[0])])
     return T, I4, base
+
+
+# ---- sweep over the normalisation constant alpha (appendix "Evaluating and
+#      Normalizing the Importance") ----
+
+def make_sweep_batch(cfg, seed=0, n_raw=None, n_alpha=16, alpha_max=2.0):
+    """Raw tables for a sweep: -> (T int32 [n_raw][L+1][L+1], I_raw float32 (same shape),
+    base, alphas float32 [n_alpha]).
+
+    The tables are those of make_batch, except that the blocks of size one
+    carry a measured accuracy change instead of 0: I[i][i+1] = -Exp(mean mu/5),
+    drawn in ascending i from a stream of their own.  alphas are n_alpha evenly
+    spaced values in [0, alpha_max].  Solving table b at alpha a as instance
+    b * n_alpha + a gives n_raw * n_alpha instances (by default cfg.B)."""
+    n_raw = max(1, cfg.B // n_alpha) if n_raw is None else n_raw
+    T, I, base = make_batch(cfg, seed=seed, B=n_raw)
+    for b in range(n_raw):
+        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, cfg.cid, b, 0x51])))
+        idx = np.arange(cfg.L)
+        I[b, idx, idx + 1] = (-rng.exponential(cfg.mu / 5.0, cfg.L)).astype(np.float32)
+    alphas = np.linspace(0.0, alpha_max, n_alpha).astype(np.float32)
+    return T, I, base, alphas

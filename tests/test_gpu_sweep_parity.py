@@ -1,0 +1,201 @@
+"""GPU parity of the sweep steps (importance normalisation, trade-off curve,
+latency of a network merged at a given set) against their CPU oracle, element
+by element, tolerance 0, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2301_12187_amd import api, inputs
+from helpers import bits, rand_tables
+from gpu_common import first_diff, run_gpu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _shift_gpu(I_raw, alphas):
+    B = I_raw.shape[0]
+    n = len(alphas)
+    out = torch.full((B * n,) + I_raw.shape[1:], float("nan"), dtype=torch.float32, device=DEV)
+    mean = torch.full((B,), float("nan"), dtype=torch.float64, device=DEV)
+    api.dpc_importance_shift(torch.from_numpy(I_raw).to(DEV),
+                             torch.from_numpy(np.asarray(alphas, np.float32)).to(DEV), out, mean)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), mean.cpu().numpy()
+
+
+@pytest.mark.parametrize("flags", [False, True])
+@pytest.mark.parametrize("L", [1, 2, 53, 126, 255])
+def test_importance_shift_bit_exact(L, flags):
+    if flags and L > 126:
+        pytest.skip("tables with flags stop at the extended solver's largest L")
+    rng = np.random.default_rng(40 + L)
+    B = 3
+    shape = (B, L + 1, L + 1, 2, 2) if flags else (B, L + 1, L + 1)
+    I = rng.normal(-0.2, 0.3, shape).astype(np.float32)
+    I[rng.random(shape) < 0.1] = -np.inf
+    if L >= 2:
+        I[1, np.arange(L), np.arange(1, L + 1)] = -np.inf       # instance 1: D is empty
+    alphas = np.array([0.0, 1.0, -0.75, 1.6180339], np.float32)
+    out, mean = _shift_gpu(I, alphas)
+    for b in range(B):
+        for a, al in enumerate(alphas):
+            ref, m = oracle.importance_shift(I[b], al)
+            d = first_diff(bits(out[b * len(alphas) + a]), bits(ref))
+            assert d is None, (b, a, d)
+            assert mean[b] == m
+
+
+def test_importance_shift_on_the_batched_workload_then_solve():
+    """Shifted tables feed the solver as B * n_alpha instances; the whole chain
+    (shift, stage 1, stage 2, set recovery, curve, both latencies) against the oracle."""
+    cfg = inputs.CONFIGS[3]
+    B0 = 6
+    T0_, I0, bases, alphas = inputs.make_sweep_batch(cfg, seed=11, n_raw=B0, n_alpha=4)
+    shifted, _ = _shift_gpu(I0, alphas)
+    B = B0 * len(alphas)
+    T = np.repeat(T0_, len(alphas), axis=0)
+    qi = np.repeat(np.arange(B, dtype=np.int32), 3)
+    qt = np.tile(np.array([300, 550, 999], np.int32), B)
+    g = run_gpu(T, shifted, cfg.P, qi, qt)
+    for b in range(B):
+        ref, _ = oracle.importance_shift(I0[b // len(alphas)], alphas[b % len(alphas)])
+        assert first_diff(bits(shifted[b]), bits(ref)) is None
+    Topt, split, M, K = oracle.solve_batch(T, shifted, cfg.P, threads=8)
+    assert first_diff(bits(g["M"]), bits(M)) is None and first_diff(g["K"], K) is None
+    # curve
+    cap = 64
+    ft = torch.full((B, cap), -9, dtype=torch.int32, device=DEV)
+    fo = torch.full((B, cap), float("nan"), dtype=torch.float32, device=DEV)
+    fl = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    api.dpc_front(torch.from_numpy(g["M"]).to(DEV), ft, fo, fl)
+    # both latencies
+    Q = len(qi)
+    Td = torch.from_numpy(T).to(DEV)
+    qid = torch.from_numpy(qi).to(DEV)
+    latS = torch.full((Q,), -9, dtype=torch.int32, device=DEV)
+    latA = torch.full((Q,), -9, dtype=torch.int32, device=DEV)
+    api.dpc_chain_latency(Td, qid, torch.from_numpy(g["S"]).to(DEV),
+                          torch.from_numpy(g["S_len"]).to(DEV), latS)
+    api.dpc_chain_latency(Td, qid, torch.from_numpy(g["A"]).to(DEV),
+                          torch.from_numpy(g["A_len"]).to(DEV), latA)
+    torch.cuda.synchronize()
+    ft, fo, fl, latS, latA = (x.cpu().numpy() for x in (ft, fo, fl, latS, latA))
+    for b in range(B):
+        t, o, n = oracle.front(M[b, cfg.L], cap)
+        assert fl[b] == n
+        k = min(n, cap)
+        assert list(ft[b, :k]) == list(t) and (bits(fo[b, :k]) == bits(o)).all()
+        assert (ft[b, k:] == -9).all()
+    assert (latS == g["lat"]).all()
+    for q in range(Q):
+        r = oracle.backtrack(Topt[qi[q]], split[qi[q]], shifted[qi[q]], M[qi[q]], K[qi[q]], int(qt[q]))
+        assert latS[q] == oracle.chain_latency(T[qi[q]], None if r["status"] else r["S"])
+        assert latA[q] == oracle.chain_latency(T[qi[q]], None if r["status"] else r["A"])
+        assert latA[q] >= latS[q]
+
+
+@pytest.mark.parametrize("P,cap", [(1, 4), (63, 64), (64, 3), (257, 300), (1000, 1000),
+                                   (16000, 0), (16000, 17)])
+def test_front_bit_exact_on_synthetic_rows(P, cap):
+    """Rows with many, few and no points, lengths around the chunk size, caps
+    smaller than the number of points."""
+    rng = np.random.default_rng(P * 7 + cap)
+    B, L = 5, 3
+    M = np.full((B, L + 1, P), np.nan, np.float32)
+    for b in range(B):
+        steps = rng.random(P) < (0.0, 0.02, 0.3, 0.7, 1.0)[b]
+        row = np.cumsum(np.where(steps, rng.random(P), 0.0)).astype(np.float32) - np.float32(50.0)
+        start = int(rng.integers(0, P)) if b != 3 else 0
+        row[:start] = -np.inf
+        if b == 0:
+            row[:] = -np.inf
+        M[b, L] = row
+    ft = torch.full((B, max(cap, 1)), -9, dtype=torch.int32, device=DEV)[:, :cap].contiguous()
+    fo = torch.full((B, max(cap, 1)), float("nan"), dtype=torch.float32, device=DEV)[:, :cap].contiguous()
+    fl = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    api.dpc_front(torch.from_numpy(M).to(DEV), ft, fo, fl)
+    torch.cuda.synchronize()
+    ft, fo, fl = ft.cpu().numpy(), fo.cpu().numpy(), fl.cpu().numpy()
+    for b in range(B):
+        t, o, n = oracle.front(M[b, L], cap)
+        assert fl[b] == n, (b, fl[b], n)
+        k = min(n, cap)
+        assert list(ft[b, :k]) == list(t)
+        assert (bits(fo[b, :k]) == bits(o)).all()
+        assert (ft[b, k:] == -9).all()
+
+
+def test_chain_latency_sets_saturation_and_markers():
+    rng = np.random.default_rng(77)
+    B, L = 4, 40
+    T = np.zeros((B, L + 1, L + 1), np.int32)
+    for b in range(B):
+        T[b], _ = rand_tables(rng, L, tmax=1000, inf_frac=0.3)
+    T[3] = np.where(T[3] == oracle.DPC_INF, T[3], 0x30000000)   # sums pass 2^31 without saturation
+    sets, qi = [], []
+    for q in range(300):
+        b = int(rng.integers(0, B))
+        n = int(rng.integers(0, L))
+        sets.append(sorted(rng.choice(np.arange(1, L), size=n, replace=False).tolist()))
+        qi.append(b)
+    sets += [None, [], list(range(1, L))]
+    qi += [0, 1, 2]
+    Q = len(sets)
+    X = np.full((Q, L), -9, np.int32)
+    Xl = np.zeros(Q, np.int32)
+    for q, s in enumerate(sets):
+        Xl[q] = -1 if s is None else len(s)
+        if s:
+            X[q, :len(s)] = s
+    lat = torch.full((Q,), -9, dtype=torch.int32, device=DEV)
+    api.dpc_chain_latency(torch.from_numpy(T).to(DEV), torch.from_numpy(np.array(qi, np.int32)).to(DEV),
+                          torch.from_numpy(X).to(DEV), torch.from_numpy(Xl).to(DEV), lat)
+    torch.cuda.synchronize()
+    lat = lat.cpu().numpy()
+    for q, s in enumerate(sets):
+        assert lat[q] == oracle.chain_latency(T[qi[q]], s), (q, s)
+    two_blocks = np.array([q3 == 3 and s is not None and len(s) >= 1 for q3, s in zip(qi, sets)])
+    assert two_blocks.any() and (lat[two_blocks] == oracle.DPC_INF).all()
+
+
+def test_chain_latency_rejects_malformed_sets():
+    L = 6
+    T = np.ones((1, L + 1, L + 1), np.int32)
+    bad = [[3, 2], [0, 2], [2, 2], [2, 6], [1, 7]]
+    X = np.zeros((len(bad) + 2, L), np.int32)
+    Xl = np.zeros(len(bad) + 2, np.int32)
+    for q, s in enumerate(bad):
+        X[q, :len(s)] = s
+        Xl[q] = len(s)
+    Xl[len(bad)] = L                        # longer than any subset of [1, L-1]
+    qi = np.zeros(len(bad) + 2, np.int32)
+    qi[len(bad) + 1] = 1                    # instance outside the batch
+    lat = torch.full((len(qi),), -9, dtype=torch.int32, device=DEV)
+    api.dpc_chain_latency(torch.from_numpy(T).to(DEV), torch.from_numpy(qi).to(DEV),
+                          torch.from_numpy(X).to(DEV), torch.from_numpy(Xl).to(DEV), lat)
+    torch.cuda.synchronize()
+    assert (lat.cpu().numpy() == -1).all()
+
+
+def test_front_of_the_extended_table_reads_its_last_row():
+    from test_gpu_ext_parity import run_ext_gpu
+    cfg = inputs.CONFIGS[2]
+    T, I4, _ = inputs.make_ext_batch(cfg, seed=3, B=2)
+    qi = np.array([0, 1], np.int32)
+    qt = np.array([cfg.P - 1, cfg.P - 1], np.int32)
+    g = run_ext_gpu(T, I4, cfg.P, qi, qt)
+    cap = 128
+    ft = torch.full((2, cap), -9, dtype=torch.int32, device=DEV)
+    fo = torch.full((2, cap), float("nan"), dtype=torch.float32, device=DEV)
+    fl = torch.full((2,), -9, dtype=torch.int32, device=DEV)
+    api.dpc_front(torch.from_numpy(g["D"]).to(DEV), ft, fo, fl)
+    torch.cuda.synchronize()
+    _, _, _, _, D, _ = oracle.ext_solve_batch(T, I4, cfg.P, threads=2)
+    for b in range(2):
+        t, o, n = oracle.front(np.ascontiguousarray(D[b, cfg.L].max(axis=1)), cap)
+        k = min(n, cap)
+        assert fl[b].item() == n
+        assert list(ft[b, :k].cpu().numpy()) == list(t)
+        assert (bits(fo[b, :k].cpu().numpy()) == bits(o)).all()
