@@ -54,6 +54,9 @@ def main():
                     help="time the extended solver (Appendix B: Algorithms 1, 3, 4 and set "
                          "recovery) on the flag-dependent version of --config (default 3, the "
                          "MobileNetV2-shaped batch) instead of the headline workload")
+    ap.add_argument("--fused", action="store_true",
+                    help="stage 1 + stage 2 in one launch (dpc_stage12_fused; small instances: "
+                         "L <= 63, P <= 2048)")
     ap.add_argument("--sweep", action="store_true",
                     help="time a sweep over the normalisation constant alpha: shift, solve, "
                          "trade-off curves, set recovery, latency merged at A (cfg3 shape by default)")
@@ -96,13 +99,23 @@ def main():
     api.dpc_set_stage2_variant(args.variant)
     stream = torch.cuda.current_stream()
 
+    if args.fused and not api.dpc_stage12_fused_supported(cfg.L, cfg.P):
+        print(f"bench.py --fused: L = {cfg.L}, P = {cfg.P} is outside the single-launch path",
+              file=sys.stderr)
+        sys.exit(2)
+
     def step(ev=None):
         if ev:
             ev[0].record(stream)
-        api.dpc_stage1_minplus(Td, buf.Topt, buf.split)
-        if ev:
-            ev[1].record(stream)
-        api.dpc_stage2_knapsack(buf.Topt, Id, buf.M, buf.K, buf.workspace)
+        if args.fused:
+            if ev:
+                ev[1].record(stream)         # (stage 1 runs inside the one kernel)
+            api.dpc_stage12_fused(Td, Id, buf.Topt, buf.split, buf.M, buf.K)
+        else:
+            api.dpc_stage1_minplus(Td, buf.Topt, buf.split)
+            if ev:
+                ev[1].record(stream)
+            api.dpc_stage2_knapsack(buf.Topt, Id, buf.M, buf.K, buf.workspace)
         if ev:
             ev[2].record(stream)
         api.dpc_backtrack(buf.Topt, buf.split, Id, buf.M, buf.K, qid, qtd, buf.A, buf.A_len,
@@ -148,7 +161,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "L": cfg.L, "P": cfg.P,
                    "queries": int(len(qi)), "store_K": not args.no_K,
-                   "stage2_variant": args.variant, "seed": args.seed},
+                   "stage2_variant": args.variant, "fused_stage12": bool(args.fused),
+                   "seed": args.seed},
         "exact_relax_ops_per_s": exact / (ms_step * 1e-3),
         "stage2_exact_relax_ops_per_s": exact / (s2_avg * 1e-3),
         "stage_ms": {"stage1": float(np.mean(s1)), "stage2": s2_avg,

@@ -236,6 +236,28 @@ const char *dpc_status_string(int code);
 int dpc_set_stage2_variant(int variant);
 
 /*
+ * ---- Small instances: stage 1 and stage 2 in one launch ----
+ *
+ * dpc_stage12_fused computes exactly what dpc_stage1_minplus followed by
+ * dpc_stage2_knapsack computes (Algorithms 1 and 2; same outputs, bit for
+ * bit), in a single kernel with one workgroup per instance that keeps the
+ * tables of an instance in LDS.  It is the low-latency path for one network or
+ * a few of them; it needs no workspace and cannot time out (no workgroup waits
+ * for another).  Follow it with dpc_backtrack.
+ * Supported shapes: 1 <= L <= 63, 1 <= P <= 2048 and a device whose LDS holds
+ * the candidate table and at least one row of M (true for every such shape on
+ * MI355X); dpc_stage12_fused_supported returns 1 for them on the current
+ * device, else 0, and dpc_stage12_fused returns DPC_ERR_SHAPE for the others.
+ *   T, I            in   as for dpc_stage1_minplus / dpc_stage2_knapsack
+ *   Topt, split     out  as written by dpc_stage1_minplus
+ *   M, K            out  as written by dpc_stage2_knapsack; K may be NULL
+ */
+int dpc_stage12_fused_supported(int32_t L, int32_t P);
+
+int dpc_stage12_fused(int32_t B, int32_t L, int32_t P, const int32_t *T, const float *I,
+                      int32_t *Topt, uint8_t *split, float *M, uint8_t *K, void *stream);
+
+/*
  * ---- Steps around the solver in a sweep over hyper-parameters ----
  *
  * dpc_importance_shift - the normalisation of the paper's appendix "Evaluating

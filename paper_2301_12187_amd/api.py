@@ -25,6 +25,7 @@ EXPORTS = (
     "dpc_ext_importance_maxplus", "dpc_ext_workspace_bytes", "dpc_ext_knapsack",
     "dpc_ext_check", "dpc_ext_backtrack",
     "dpc_importance_shift", "dpc_front", "dpc_chain_latency",
+    "dpc_stage12_fused_supported", "dpc_stage12_fused",
 )
 
 _lib = None
@@ -331,3 +332,40 @@ def dpc_chain_latency(T, q_inst, X, X_len, lat, stream=None):
         _dev(q_inst, torch.int32, (Q,), "q_inst"), _dev(X, torch.int32, (Q, L), "X"),
         _dev(X_len, torch.int32, (Q,), "X_len"), _dev(lat, torch.int32, (Q,), "lat"),
         _stream(stream)))
+
+
+# ---- small instances: stage 1 and stage 2 in one launch ----
+
+def _load_fused():
+    lib = load()
+    if not getattr(lib, "_fused_ready", False):
+        i32, vp = ctypes.c_int32, ctypes.c_void_p
+        lib.dpc_stage12_fused_supported.argtypes = [i32, i32]
+        lib.dpc_stage12_fused_supported.restype = ctypes.c_int
+        lib.dpc_stage12_fused.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        lib.dpc_stage12_fused.restype = ctypes.c_int
+        lib._fused_ready = True
+    return lib
+
+
+def dpc_stage12_fused_supported(L, P):
+    return bool(_load_fused().dpc_stage12_fused_supported(L, P))
+
+
+def dpc_stage12_fused(T, I, Topt, split, M, K, stream=None):
+    """T int32, I float32 [B][L+1][L+1] -> Topt, split, M, K (or None), one launch."""
+    B, ld, _ = T.shape
+    P = M.shape[2]
+    shp = (B, ld, ld)
+    _check(_load_fused().dpc_stage12_fused(
+        B, ld - 1, P, _dev(T, torch.int32, shp, "T"), _dev(I, torch.float32, shp, "I"),
+        _dev(Topt, torch.int32, shp, "Topt"), _dev(split, torch.uint8, shp, "split"),
+        _dev(M, torch.float32, (B, ld, P), "M"),
+        None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"), _stream(stream)))
+
+
+def solve_fused(T, I, q_inst, q_T0, buf: "Buffers", stream=None):
+    """dpc_stage12_fused + dpc_backtrack into the buffers of `buf`."""
+    dpc_stage12_fused(T, I, buf.Topt, buf.split, buf.M, buf.K, stream)
+    dpc_backtrack(buf.Topt, buf.split, I, buf.M, buf.K, q_inst, q_T0, buf.A, buf.A_len, buf.S,
+                  buf.S_len, buf.obj, buf.lat, buf.status, stream)

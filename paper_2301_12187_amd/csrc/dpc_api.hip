@@ -20,6 +20,22 @@ int num_compute_units()
     return cached[dev];
 }
 
+// LDS bytes one workgroup may use on the current device
+int lds_per_workgroup()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+            n <= 0)
+            return -1;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 bool shape_ok(int B, int L, int P)
 {
     return B >= 1 && L >= 1 && L <= DPC_MAX_L && P >= 1 &&
@@ -201,6 +217,25 @@ int dpc_ext_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, cons
     hipError_t e = dpc::launch_ext_backtrack(B, L, P, Topt, split, bsplit, D, Kx, Q, q_inst, q_T0,
                                              A, A_len, S, S_len, Bs, B_len, obj, lat, a_last,
                                              status, (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+int dpc_stage12_fused_supported(int32_t L, int32_t P)
+{
+    const int lds = lds_per_workgroup();
+    return lds > 0 && dpc::fused_small_supported(L, P, lds) ? 1 : 0;
+}
+
+int dpc_stage12_fused(int32_t B, int32_t L, int32_t P, const int32_t* T, const float* I,
+                      int32_t* Topt, uint8_t* split, float* M, uint8_t* K, void* stream)
+{
+    if (!T || !I || !Topt || !split || !M) return DPC_ERR_NULL;
+    if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
+    const int lds = lds_per_workgroup();
+    if (lds <= 0) return DPC_ERR_HIP;
+    if (!dpc::fused_small_supported(L, P, lds)) return DPC_ERR_SHAPE;
+    hipError_t e = dpc::launch_fused_small(B, L, P, T, I, Topt, split, M, K, lds,
+                                           (hipStream_t)stream);
     return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
 }
 

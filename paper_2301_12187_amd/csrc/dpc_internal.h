@@ -40,6 +40,11 @@ hipError_t launch_ext_backtrack(int B, int L, int P, const int32_t* Topt, const 
                                 int32_t* B_len, float* obj, int32_t* lat, int32_t* a_last,
                                 int32_t* status, hipStream_t st);
 
+// stage 1 + stage 2 in one launch for small instances; lds_limit = LDS bytes a workgroup may use
+bool fused_small_supported(int L, int P, int lds_limit);
+hipError_t launch_fused_small(int B, int L, int P, const int32_t* T, const float* I, int32_t* Topt,
+                              uint8_t* split, float* M, uint8_t* K, int lds_limit, hipStream_t st);
+
 // sweep steps: importance normalisation, trade-off curve, latency of a given merge set
 hipError_t launch_importance_shift(int B, int L, int F, int n_alpha, const float* I_raw,
                                    const float* alpha, float* I_out, double* mean_out,

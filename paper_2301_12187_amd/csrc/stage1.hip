@@ -3,15 +3,9 @@
 //
 // Row k of Topt depends only on row k and on T, so every (instance, k) pair is
 // an independent single-source shortest-path problem on the DAG m -> l with
-// weight T[m][l].  One 64-lane wave owns one (instance, k).  Lanes own the
-// targets l = lane + 64u; the wave walks the sources m = k, k+1, ... in order
-// and, for each, relaxes every l > m at once ("push" form of the algorithm's
-// arg-min over the last block).  When the walk reaches m, every m' < m has been
-// pushed, so lane(m)'s running minimum is the final Topt[k][m]; it is broadcast
-// with a cross-lane read.  Sources are visited in ascending order and a
-// candidate replaces the minimum only when strictly smaller, so the lowest
-// arg-min m' is kept.  T[m][l] is read along l: coalesced.
-#include "dpc_internal.h"
+// weight T[m][l].  One 64-lane wave owns one (instance, k); its walk is in
+// stage1_row.h.
+#include "stage1_row.h"
 
 namespace dpc {
 
@@ -33,46 +27,7 @@ __global__ __launch_bounds__(64 * S1_WAVES) void stage1_kernel(
 
     int32_t cur[S1_U];
     int32_t arg[S1_U];
-#pragma unroll
-    for (int u = 0; u < S1_U; ++u) { cur[u] = DPC_INF; arg[u] = k; }
-
-    // The loads of T do not depend on the recurrence: fetch S1_AHEAD source rows
-    // at once, then run their dependent steps from registers.
-    for (int m0 = k; m0 < L; m0 += S1_AHEAD) {
-        int32_t tv[S1_AHEAD][S1_U];
-#pragma unroll
-        for (int a = 0; a < S1_AHEAD; ++a) {
-            const int m = min(m0 + a, L - 1);
-            const int32_t* Trow = Tb + (size_t)m * ld;
-#pragma unroll
-            for (int u = 0; u < S1_U; ++u) {
-                const int l = lane + 64 * u;
-                tv[a][u] = (l > m && l <= L) ? Trow[l] : DPC_INF;
-            }
-        }
-#pragma unroll
-        for (int a = 0; a < S1_AHEAD; ++a) {
-            const int m = m0 + a;
-            if (m >= L) break;
-            // final Topt[k][m]: 0 for m == k, else the owner lane's minimum
-            int32_t own = cur[0];
-            const int um = m >> 6;
-#pragma unroll
-            for (int u = 1; u < S1_U; ++u) own = (um == u) ? cur[u] : own;
-            int32_t tm = __shfl(own, m & 63, 64);
-            if (m == k) tm = 0;
-#pragma unroll
-            for (int u = 0; u < S1_U; ++u) {
-                const int l = lane + 64 * u;
-                if (l > m && l <= L) {
-                    // both terms are <= DPC_INF = 2^30 - 1: the sum fits int32
-                    int32_t c = tm + tv[a][u];
-                    c = c > DPC_INF ? DPC_INF : c;
-                    if (c < cur[u]) { cur[u] = c; arg[u] = m; }
-                }
-            }
-        }
-    }
+    stage1_row<S1_U, S1_AHEAD>(L, Tb, k, lane, cur, arg);
 #pragma unroll
     for (int u = 0; u < S1_U; ++u) {
         const int l = lane + 64 * u;

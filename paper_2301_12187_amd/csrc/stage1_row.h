@@ -1,0 +1,67 @@
+// Stage 1, the walk of one wave over one source row k (Algorithm 1, Eq. 5a/5b
+// of the paper), shared by the batched kernel and the single-launch path for
+// small instances.
+//
+// Lanes own the targets l = lane + 64u.  The wave visits the sources
+// m = k, k+1, ... in order and, for each, relaxes every l > m at once ("push"
+// form of the algorithm's arg-min over the last block).  When the walk reaches
+// m, every m' < m has been pushed, so lane(m)'s running minimum is the final
+// Topt[k][m]; it is broadcast with a cross-lane read.  Sources are visited in
+// ascending order and a candidate replaces the minimum only when strictly
+// smaller, so the lowest arg-min m' is kept.  T[m][l] is read along l: coalesced.
+#pragma once
+#include "dpc_internal.h"
+
+namespace dpc {
+
+// S1_U: targets per lane (64 * S1_U > L); S1_AHEAD: source rows fetched per batch.
+// On return cur[u] = Topt[k][lane + 64u] and arg[u] = its arg-min for l > k.
+template <int S1_U, int S1_AHEAD>
+__device__ __forceinline__ void stage1_row(int L, const int32_t* __restrict__ Tb, int k, int lane,
+                                           int32_t (&cur)[S1_U], int32_t (&arg)[S1_U])
+{
+    const int ld = L + 1;
+#pragma unroll
+    for (int u = 0; u < S1_U; ++u) { cur[u] = DPC_INF; arg[u] = k; }
+
+    // The loads of T do not depend on the recurrence: fetch S1_AHEAD source rows
+    // at once, then run their dependent steps from registers.
+    for (int m0 = k; m0 < L; m0 += S1_AHEAD) {
+        int32_t tv[S1_AHEAD][S1_U];
+#pragma unroll
+        for (int a = 0; a < S1_AHEAD; ++a) {
+            const int m = min(m0 + a, L - 1);
+            const int32_t* Trow = Tb + (size_t)m * ld;
+#pragma unroll
+            for (int u = 0; u < S1_U; ++u) {
+                const int l = lane + 64 * u;
+                tv[a][u] = (l > m && l <= L) ? Trow[l] : DPC_INF;
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < S1_AHEAD; ++a) {
+            const int m = m0 + a;
+            if (m >= L) break;
+            // final Topt[k][m]: 0 for m == k, else the owner lane's minimum
+            int32_t own = cur[0];
+            const int um = m >> 6;
+#pragma unroll
+            for (int u = 1; u < S1_U; ++u) own = (um == u) ? cur[u] : own;
+            // (m is the same in every lane: a scalar lane read, not a permute)
+            int32_t tm = __builtin_amdgcn_readlane(own, m & 63);
+            if (m == k) tm = 0;
+#pragma unroll
+            for (int u = 0; u < S1_U; ++u) {
+                const int l = lane + 64 * u;
+                if (l > m && l <= L) {
+                    // both terms are <= DPC_INF = 2^30 - 1: the sum fits int32
+                    int32_t c = tm + tv[a][u];
+                    c = c > DPC_INF ? DPC_INF : c;
+                    if (c < cur[u]) { cur[u] = c; arg[u] = m; }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace dpc

@@ -8,7 +8,7 @@ from paper_2301_12187_amd import api
 from helpers import bits
 
 
-def run_gpu(T, I, P, q_inst, q_T0, store_K=True, variant=0):
+def run_gpu(T, I, P, q_inst, q_T0, store_K=True, variant=0, fused=False):
     """numpy in -> dict of numpy outputs from the HIP path."""
     B, ld, _ = T.shape
     L = ld - 1
@@ -28,8 +28,11 @@ def run_gpu(T, I, P, q_inst, q_T0, store_K=True, variant=0):
     buf.S.fill_(-9)
     prev = api.dpc_set_stage2_variant(variant)
     try:
-        api.solve(Td, Id, qi, qt, buf)
-        api.dpc_stage2_check(buf.workspace)
+        if fused:                      # stage 1 + stage 2 in one launch, then set recovery
+            api.solve_fused(Td, Id, qi, qt, buf)
+        else:
+            api.solve(Td, Id, qi, qt, buf)
+            api.dpc_stage2_check(buf.workspace)
     finally:
         api.dpc_set_stage2_variant(prev)
     torch.cuda.synchronize()

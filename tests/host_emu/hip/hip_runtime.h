@@ -35,6 +35,8 @@ typedef int hipError_t;
 enum { hipSuccess = 0, hipErrorInvalidValue = 1 };
 typedef void* hipStream_t;
 inline hipError_t hipGetLastError() { return hipSuccess; }
+enum { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
+inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
 
 namespace emu {
 
@@ -69,6 +71,7 @@ inline void check_global(const void* p, size_t n, const char* what)
     std::fprintf(stderr, "EMU: %s of %zu bytes at %p is outside every registered buffer\n", what, n, p);
     std::abort();
 }
+inline char* g_dyn_lds = nullptr;         // stand-in for the dynamic LDS of the running launch
 inline const char* g_lds_lo = nullptr;
 inline const char* g_lds_hi = nullptr;
 
@@ -105,8 +108,14 @@ void launch(dim3 grid, dim3 block, F&& body)
 #define blockIdx emu::t_blockIdx
 #define blockDim emu::t_blockDim
 #define gridDim emu::t_gridDim
-#define hipLaunchKernelGGL(kernel, grid, block, shmem, stream, ...) \
-    emu::launch(grid, block, [&] { kernel(__VA_ARGS__); })
+// (the dynamic LDS is an exact-size heap block: the sanitizer sees an access past its end)
+#define hipLaunchKernelGGL(kernel, grid, block, shmem, stream, ...)                \
+    do {                                                                           \
+        emu::g_dyn_lds = (size_t)(shmem) ? (char*)std::malloc((size_t)(shmem)) : nullptr; \
+        emu::launch(grid, block, [&] { kernel(__VA_ARGS__); });                    \
+        std::free(emu::g_dyn_lds);                                                 \
+        emu::g_dyn_lds = nullptr;                                                  \
+    } while (0)
 
 inline void __syncthreads() { emu::g_barrier.wait(); }
 inline void wave_sync() { emu::g_wave_barrier[((int)threadIdx.x >> 6) & 15].wait(); }
@@ -138,6 +147,19 @@ inline int __shfl_up(int v, int d, int)
     wave_sync();
     return r;
 }
+
+// value of lane `src` of the same wave; every lane of the wave calls it
+inline int __shfl(int v, int src, int)
+{
+    const int t = (int)threadIdx.x;
+    emu::g_exchange[t] = v;
+    wave_sync();
+    const int r = emu::g_exchange[(t & ~63) + (src & 63)];
+    wave_sync();
+    return r;
+}
+
+inline int __builtin_amdgcn_readlane(int v, int src) { return __shfl(v, src, 64); }
 
 // value of lane (lane ^ d) of the same wave; every lane of the wave calls it
 inline int __shfl_xor(int v, int d, int)

@@ -19,18 +19,27 @@ ROOT = os.path.dirname(HERE)
 EMU_DIR = os.path.join(HERE, "host_emu")
 
 
-@pytest.fixture(scope="module")
-def emu(tmp_path_factory):
+def _build(tmp_path_factory, main_cpp, name):
     if shutil.which("g++") is None:
         pytest.skip("no host compiler")
-    exe = str(tmp_path_factory.mktemp("emu") / "dpc_emu")
+    exe = str(tmp_path_factory.mktemp(name) / name)
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
            "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-pthread",
            "-I", EMU_DIR, "-I", os.path.join(ROOT, "include"),
            "-I", os.path.join(ROOT, "paper_2301_12187_amd", "csrc"),
-           "-x", "c++", "-o", exe, os.path.join(EMU_DIR, "emu_main.cpp")]
+           "-x", "c++", "-o", exe, os.path.join(EMU_DIR, main_cpp)]
     subprocess.run(cmd, check=True)
     return exe
+
+
+@pytest.fixture(scope="module")
+def emu(tmp_path_factory):
+    return _build(tmp_path_factory, "emu_main.cpp", "dpc_emu")
+
+
+@pytest.fixture(scope="module")
+def emu_fused(tmp_path_factory):
+    return _build(tmp_path_factory, "emu_fused_main.cpp", "dpc_emu_fused")
 
 
 def _run(emu, tmp_path, T, I, P, shape):
@@ -73,3 +82,48 @@ def test_row_by_row_groups_and_missing_candidates(emu, tmp_path, shape):
         Ts.append(T)
         Is.append(I)
     _run(emu, tmp_path, np.stack(Ts), np.stack(Is), P, shape)
+
+
+# ---- the single-launch kernel for small instances (stage 1 + stage 2) ----
+
+def _run_fused(emu_fused, tmp_path, T, I, P, lds_limit):
+    B, ld, _ = T.shape
+    Topt, split, M, K = oracle.solve_batch(T, I, P, want_K=True, threads=4)
+    fin, fout = str(tmp_path / "fin.bin"), str(tmp_path / "fout.bin")
+    with open(fin, "wb") as f:
+        np.array([B, ld - 1, P, lds_limit], np.int32).tofile(f)
+        T.astype(np.int32).tofile(f)
+        I.astype(np.float32).tofile(f)
+    r = subprocess.run([emu_fused, fin, fout], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-4000:]
+    raw = np.fromfile(fout, np.uint8)
+    n2, n = B * ld * ld, B * ld * P
+    o = 0
+    Te = raw[o:o + 4 * n2].view(np.int32).reshape(B, ld, ld); o += 4 * n2
+    Se = raw[o:o + n2].reshape(B, ld, ld); o += n2
+    Me = raw[o:o + 4 * n].view(np.float32).reshape(B, ld, P); o += 4 * n
+    Ke = raw[o:o + n].reshape(B, ld, P)
+    assert (Te == Topt).all() and (Se == split).all()
+    assert (Me.view(np.uint32) == M.view(np.uint32)).all()
+    assert (Ke == K).all()
+
+
+# lds_limit: 160 KB keeps every row of these shapes in LDS; the small limits
+# leave room for a few rows only (4 and 1 resident rows plus the ring of three,
+# then 20 resident rows, then 2 resident rows, two columns per thread and several batches per row), the rest
+# is read back from the output array
+@pytest.mark.parametrize("L,P,lds_limit", [(1, 1, 163840), (7, 100, 163840), (21, 333, 163840),
+                                           (21, 333, 8 * 22 * 22 + 7 * 334 * 4),
+                                           (13, 1291, 8 * 14 * 14 + 4 * 1292 * 4),
+                                           (40, 70, 8 * 41 * 41 + 41 * 41 * 4),
+                                           (63, 1291, 8 * 64 * 64 + 5 * 1292 * 4),
+                                           (63, 130, 163840)])
+def test_fused_small_kernel(emu_fused, tmp_path, L, P, lds_limit):
+    rng = np.random.default_rng(600 + L + P)
+    B = 2
+    T, I = zip(*[rand_tables(rng, L, tmax=12, inf_frac=0.3, ikind="neg", span=9) for _ in range(B)])
+    T, I = np.stack(T), np.stack(I)
+    if L >= 7:
+        T[1, 0, 3] = 5000                    # a shift beyond every budget
+        I[1, 2, 5] = -np.inf                 # an excluded block
+    _run_fused(emu_fused, tmp_path, T, I, P, lds_limit)
