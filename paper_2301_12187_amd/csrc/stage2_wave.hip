@@ -77,11 +77,23 @@ namespace dpc {
         }                                                                                    \
     } while (0)
 #endif
-template <int BYTE>
+// Without back-pointers (TRACK false) the update is the plain maximum: the
+// table never holds -0 (row 0 is +0 and a sum is -0 only when both terms are),
+// so the maximum has the bits of the first candidate that attains it, as the
+// strict comparison would leave them.
+template <int BYTE, bool TRACK>
 __device__ __forceinline__ void relax_cell(float& best, uint32_t& argp, float cand, uint32_t vi)
 {
     static_assert(BYTE >= 0 && BYTE < 4, "four arg-max bytes per register");
-    if constexpr (BYTE == 0) DPC_RELAX_CELL(0);
+    if constexpr (!TRACK) {
+#ifndef DPC_HOST_EMU
+        // (the instruction itself: the library maximum would first re-quiet its operands)
+        asm("v_max_f32 %0, %0, %1" : "+v"(best) : "v"(cand));
+#else
+        best = cand > best ? cand : best;
+#endif
+    }
+    else if constexpr (BYTE == 0) DPC_RELAX_CELL(0);
     else if constexpr (BYTE == 1) DPC_RELAX_CELL(1);
     else if constexpr (BYTE == 2) DPC_RELAX_CELL(2);
     else DPC_RELAX_CELL(3);
@@ -322,10 +334,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 float cand[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) cand[u] = mcur[u] + imp;
-                relax_cell<0>(best[h * S2_H + r8][0], argp[h * S2_H + r8], cand[0], vi);
-                relax_cell<1>(best[h * S2_H + r8][1], argp[h * S2_H + r8], cand[1], vi);
-                relax_cell<2>(best[h * S2_H + r8][2], argp[h * S2_H + r8], cand[2], vi);
-                relax_cell<3>(best[h * S2_H + r8][3], argp[h * S2_H + r8], cand[3], vi);
+                relax_cell<0, STORE_K>(best[h * S2_H + r8][0], argp[h * S2_H + r8], cand[0], vi);
+                relax_cell<1, STORE_K>(best[h * S2_H + r8][1], argp[h * S2_H + r8], cand[1], vi);
+                relax_cell<2, STORE_K>(best[h * S2_H + r8][2], argp[h * S2_H + r8], cand[2], vi);
+                relax_cell<3, STORE_K>(best[h * S2_H + r8][3], argp[h * S2_H + r8], cand[3], vi);
 #pragma unroll
                 for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
             }
@@ -345,10 +357,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) {
                 if (rr != sub) continue;
-                relax_cell<0>(best[rr][0], argp[rr], cand[0], vi);
-                relax_cell<1>(best[rr][1], argp[rr], cand[1], vi);
-                relax_cell<2>(best[rr][2], argp[rr], cand[2], vi);
-                relax_cell<3>(best[rr][3], argp[rr], cand[3], vi);
+                relax_cell<0, STORE_K>(best[rr][0], argp[rr], cand[0], vi);
+                relax_cell<1, STORE_K>(best[rr][1], argp[rr], cand[1], vi);
+                relax_cell<2, STORE_K>(best[rr][2], argp[rr], cand[2], vi);
+                relax_cell<3, STORE_K>(best[rr][3], argp[rr], cand[3], vi);
             }
         };
 
@@ -518,10 +530,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                         float cand[U];
 #pragma unroll
                         for (int u = 0; u < U; ++u) cand[u] = sp[64 * u] + imp;
-                        relax_cell<0>(best[r2][0], argp[r2], cand[0], vj);
-                        relax_cell<1>(best[r2][1], argp[r2], cand[1], vj);
-                        relax_cell<2>(best[r2][2], argp[r2], cand[2], vj);
-                        relax_cell<3>(best[r2][3], argp[r2], cand[3], vj);
+                        relax_cell<0, STORE_K>(best[r2][0], argp[r2], cand[0], vj);
+                        relax_cell<1, STORE_K>(best[r2][1], argp[r2], cand[1], vj);
+                        relax_cell<2, STORE_K>(best[r2][2], argp[r2], cand[2], vj);
+                        relax_cell<3, STORE_K>(best[r2][3], argp[r2], cand[3], vj);
                     }
                     // operands of the next row of the group
 #pragma unroll

@@ -123,6 +123,39 @@ def test_without_stored_backpointers(variant):
     compare(g, r, cfg.L, "K == NULL")
 
 
+@pytest.mark.parametrize("variant", [0, 31, 35, 36])
+def test_without_stored_backpointers_shapes_and_special_values(variant):
+    """The kernels without arg-max tracking (plain maximum per candidate):
+    ragged shapes over several strips, wide shifts (row-by-row fallback),
+    denormals and signed zeros; sets come from the recomputed arg-max."""
+    rng = np.random.default_rng(91)
+    for (B, L, P, tmax, kind) in ((3, 37, 2333, 60, "neg"), (2, 70, 1025, 9, "mixed"),
+                                  (2, 21, 3000, 5, "wide"), (2, 9, 700, 20, "tiny")):
+        T, I = zip(*[rand_tables(rng, L, tmax=tmax, inf_frac=0.2,
+                                 ikind="neg" if kind == "neg" else "mixed") for _ in range(B)])
+        T, I = np.stack(T), np.stack(I)
+        if kind == "wide":
+            ii, jj = np.triu_indices(L + 1, k=1)
+            jump = rng.random(ii.size) < 0.3
+            T[0, ii[jump], jj[jump]] = rng.integers(0, 4000, size=int(jump.sum()))
+        if kind == "tiny":
+            I[0] = (I[0] * np.float32(1e-39)).astype(np.float32)
+            I[1][np.triu_indices(L + 1, k=1)] = np.float32(-0.0)
+        qi, qt = _all_budgets(B, P, step=max(1, P // 40))
+        g = run_gpu(T, I, P, qi, qt, store_K=False, variant=variant)
+        compare(g, run_oracle(T, I, P, qi, qt), L, f"K == NULL, {kind}")
+
+
+def test_config5_shape_without_stored_backpointers():
+    """The stress workload's launch configuration (16-row groups) on a few of
+    its instances, values only."""
+    cfg = inputs.CONFIGS[5]
+    T, I, base = inputs.make_batch(cfg, seed=0, B=4)
+    qi, qt = inputs.budgets(cfg, base)
+    g = run_gpu(T, I, cfg.P, qi, qt, store_K=False, variant=35)
+    compare(g, run_oracle(T, I, cfg.P, qi, qt, threads=4), cfg.L, "cfg5 shape, K == NULL")
+
+
 def test_bad_queries_and_empty_query_list():
     cfg = inputs.CONFIGS[1]
     T, I, _ = inputs.make_batch(cfg, seed=0)
