@@ -1,6 +1,7 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element
 by element, tolerance 0 (integers, indices and binary32 bit patterns)."""
 import numpy as np
+import oracle
 import pytest
 import torch
 
@@ -154,6 +155,25 @@ def test_config5_shape_without_stored_backpointers():
     qi, qt = inputs.budgets(cfg, base)
     g = run_gpu(T, I, cfg.P, qi, qt, store_K=False, variant=35)
     compare(g, run_oracle(T, I, cfg.P, qi, qt, threads=4), cfg.L, "cfg5 shape, K == NULL")
+
+
+@pytest.mark.parametrize("L", [1, 2, 15, 16, 63, 64, 65, 126, 127, 128, 191, 192])
+def test_stage1_at_the_chain_lengths_where_the_kernel_changes(L):
+    """Stage 1 alone (the table staged in LDS for batches of short chains, else
+    one wave per source row with 1, 2 or 4 targets per lane), saturating sums
+    included."""
+    rng = np.random.default_rng(1300 + L)
+    B = 130 if L < 64 else 3                           # (short chains in large batches have a kernel of their own)
+    T = np.stack([rand_tables(rng, L, tmax=50, inf_frac=0.3, span=max(2, L // 3))[0] for _ in range(B)])
+    T[2][T[2] < oracle.DPC_INF] += 0x10000000          # sums that reach the saturation value
+    dev = "cuda:0"
+    Topt = torch.full((B, L + 1, L + 1), -7, dtype=torch.int32, device=dev)
+    split = torch.full((B, L + 1, L + 1), 0xEE, dtype=torch.uint8, device=dev)
+    api.dpc_stage1_minplus(torch.from_numpy(T).to(dev), Topt, split)
+    torch.cuda.synchronize()
+    for b in range(B):
+        To, sp = oracle.stage1(T[b])
+        assert (Topt[b].cpu().numpy() == To).all() and (split[b].cpu().numpy() == sp).all(), (L, b)
 
 
 def test_bad_queries_and_empty_query_list():
