@@ -21,7 +21,6 @@
 namespace dpc {
 
 constexpr int X1_WAVES = 4;       // waves per workgroup
-constexpr int X1_U = 4;           // targets per lane: L <= 255
 
 __device__ __forceinline__ size_t i4_index(int ld, int k, int l, int a, int b)
 {
@@ -36,6 +35,10 @@ __device__ __forceinline__ size_t i4_index(int ld, int k, int l, int a, int b)
 // owner lane's maximum for b = 0 is the final I_opt[k][m][a][0]; it is
 // broadcast with a lane read.  A candidate replaces the maximum only when
 // strictly greater: the single block, then the lowest m, wins ties.
+// The importances I[m][l][0][.] do not depend on the walk: X1_AHEAD rows of
+// them are fetched at once (both flags b of a target are one 8-byte load).
+// X1_U: targets per lane, 64 * X1_U > L.
+template <int X1_U, int X1_AHEAD>
 __global__ __launch_bounds__(64 * X1_WAVES) void ext_iopt_kernel(
     int L, const float* __restrict__ I4, float* __restrict__ Iopt, uint8_t* __restrict__ bsplit)
 {
@@ -59,20 +62,36 @@ __global__ __launch_bounds__(64 * X1_WAVES) void ext_iopt_kernel(
             arg[u][f] = k;
         }
     }
-    for (int m = k + 1; m < L; ++m) {
-        float own = best[0][0];
-        const int um = m >> 6;
+    for (int m0 = k + 1; m0 < L; m0 += X1_AHEAD) {
+        float2 iv[X1_AHEAD][X1_U];          // I[m][l][0][0], I[m][l][0][1]
 #pragma unroll
-        for (int u = 1; u < X1_U; ++u) own = (um == u) ? best[u][0] : own;
-        const float vm = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, own), m & 63));
+        for (int x = 0; x < X1_AHEAD; ++x) {
+            const int m = min(m0 + x, L - 1);
 #pragma unroll
-        for (int u = 0; u < X1_U; ++u) {
-            const int l = lane + 64 * u;
-            if (l > m && l <= L) {
+            for (int u = 0; u < X1_U; ++u) {
+                const int l = lane + 64 * u;
+                iv[x][u] = (l > m && l <= L) ? *(const float2*)(Ib + i4_index(ld, m, l, 0, 0))
+                                             : make_float2(-INFINITY, -INFINITY);
+            }
+        }
 #pragma unroll
-                for (int f = 0; f < 2; ++f) {
-                    const float c = vm + Ib[i4_index(ld, m, l, 0, f)];
-                    if (c > best[u][f]) { best[u][f] = c; arg[u][f] = m; }
+        for (int x = 0; x < X1_AHEAD; ++x) {
+            const int m = m0 + x;
+            if (m >= L) break;
+            float own = best[0][0];
+            const int um = m >> 6;
+#pragma unroll
+            for (int u = 1; u < X1_U; ++u) own = (um == u) ? best[u][0] : own;
+            const float vm = __builtin_bit_cast(
+                float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, own), m & 63));
+#pragma unroll
+            for (int u = 0; u < X1_U; ++u) {
+                const int l = lane + 64 * u;
+                if (l > m && l <= L) {
+                    const float c0 = vm + iv[x][u].x;
+                    if (c0 > best[u][0]) { best[u][0] = c0; arg[u][0] = m; }
+                    const float c1 = vm + iv[x][u].y;
+                    if (c1 > best[u][1]) { best[u][1] = c1; arg[u][1] = m; }
                 }
             }
         }
@@ -125,8 +144,18 @@ __global__ __launch_bounds__(256) void ext_expand_kernel(
     Iv[(size_t)b * V * V + x] = imp;
 }
 
-// One lane per query: from the final layer at budget T0 back to layer 0.
-__global__ __launch_bounds__(64) void ext_backtrack_kernel(
+// One wave per query: from the final layer at budget T0 back to layer 0.
+// Everything that steers the walk is wave-uniform.  Per DP step (k, alpha') ->
+// (l, a) the wave reads one pointer byte, one latency, row k of `split` and the
+// rows (k, ., alpha', 0/1) of `bsplit` (a byte, resp. a byte pair, per lane and
+// 64 targets), then follows both pointer chains inside the block through lane
+// reads.  Members come out from high to low into three lists in LDS and are
+// written out ascending at the end; they strictly decrease along the walk
+// (enforced), so no list holds more than L-1 entries whatever the tables hold.
+constexpr int XB_WAVES = 4;       // queries per workgroup
+constexpr int XB_U = 2;           // targets per lane: L <= DPC_EXT_MAX_L = 126
+
+__global__ __launch_bounds__(64 * XB_WAVES) void ext_backtrack_kernel(
     int B, int L, int P, const int32_t* __restrict__ Topt, const uint8_t* __restrict__ split,
     const uint8_t* __restrict__ bsplit, const float* __restrict__ D,
     const uint8_t* __restrict__ Kx, int Q, const int32_t* __restrict__ q_inst,
@@ -135,10 +164,15 @@ __global__ __launch_bounds__(64) void ext_backtrack_kernel(
     float* __restrict__ obj, int32_t* __restrict__ lat, int32_t* __restrict__ a_last,
     int32_t* __restrict__ status)
 {
-    const int q = blockIdx.x * 64 + threadIdx.x;
-    if (q >= Q) return;
-    const int b = q_inst[q];
-    const int T0 = q_T0[q];
+    __shared__ int32_t listA[XB_WAVES][128];
+    __shared__ int32_t listS[XB_WAVES][128];
+    __shared__ int32_t listB[XB_WAVES][128];
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q = blockIdx.x * XB_WAVES + wv;
+    if (q >= Q) return;                          // whole wave leaves together
+    const int b = __builtin_amdgcn_readfirstlane(q_inst[q]);
+    const int T0 = __builtin_amdgcn_readfirstlane(q_T0[q]);
     const int ld = L + 1, V = 2 * L + 3;
     int st = DPC_Q_OK;
     if (b < 0 || b >= B || T0 < 0 || T0 >= P) st = DPC_Q_BAD_QUERY;
@@ -148,64 +182,93 @@ __global__ __launch_bounds__(64) void ext_backtrack_kernel(
     if (st == DPC_Q_OK) {
         Db = D + (size_t)b * V * P;
         Kb = Kx + (size_t)b * V * P;
-        top = Db[(size_t)(V - 1) * P + T0];
+        top = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
+                                            __builtin_bit_cast(int, Db[(size_t)(V - 1) * P + T0])));
         if (top == -INFINITY) st = DPC_Q_INFEASIBLE;
     }
     if (st != DPC_Q_OK) {
-        A_len[q] = -1; S_len[q] = -1; B_len[q] = -1; obj[q] = -INFINITY; lat[q] = -1;
-        a_last[q] = -1; status[q] = st;
+        if (lane == 0) {
+            A_len[q] = -1; S_len[q] = -1; B_len[q] = -1; obj[q] = -INFINITY; lat[q] = -1;
+            a_last[q] = -1; status[q] = st;
+        }
         return;
     }
     const int32_t* To = Topt + (size_t)b * ld * ld;
     const uint8_t* Sp = split + (size_t)b * ld * ld;
     const uint8_t* Bp = bsplit + (size_t)b * ld * ld * 4;
-    int32_t* Aq = A + (size_t)q * L;
-    int32_t* Sq = S + (size_t)q * L;
-    int32_t* Bq = Bs + (size_t)q * L;
     int na = 0, ns = 0, nb = 0, total = 0;
-    int v = Kb[(size_t)(V - 1) * P + T0];       // (L, a_last)
+    int v = __builtin_amdgcn_readfirstlane((int)Kb[(size_t)(V - 1) * P + T0]);   // (L, a_last)
     int l = v >> 1, a = v & 1, t = T0;
     const int alast = a;
     if (l != L) l = 0;                           // defensive: never true for stage-2 output
-    // members come out from high to low and strictly decrease (enforced below),
-    // so no list can hold more than L-1 entries whatever the tables contain
     while (l > 0) {
-        const int u = Kb[(size_t)(2 * l + a) * P + t];
+        const int u = __builtin_amdgcn_readfirstlane((int)Kb[(size_t)(2 * l + a) * P + t]);
         const int k = u >> 1, al = u & 1;
         if (k >= l) break;                       // defensive
+        const int32_t w = __builtin_amdgcn_readfirstlane(To[k * ld + l]);
+        // row k of split and rows (k, ., al, 0/1) of bsplit: target x in lane x & 63, register x >> 6
+        int srow[XB_U], brow[XB_U];
+#pragma unroll
+        for (int uu = 0; uu < XB_U; ++uu) {
+            const int x = lane + 64 * uu;
+            srow[uu] = x <= L ? (int)Sp[k * ld + x] : 0;
+            brow[uu] = x <= L ? (int)*(const uint16_t*)(Bp + i4_index(ld, k, x, al, 0)) : 0;
+        }
         for (int x = l;;) {
-            const int m = Sp[k * ld + x];
+            int src = srow[0];
+#pragma unroll
+            for (int uu = 1; uu < XB_U; ++uu) src = (x >> 6) == uu ? srow[uu] : src;
+            const int m = __builtin_amdgcn_readlane(src, x & 63);
             if (m <= k || m >= x) break;         // m == k ends S_opt[k,l]; the rest is defensive
-            Sq[ns++] = m;
+            if (lane == 0) listS[wv][ns] = m;
+            ++ns;
             x = m;
         }
         for (int x = l, f = a;;) {
-            const int m = Bp[i4_index(ld, k, x, al, f)];
+            int src = brow[0];
+#pragma unroll
+            for (int uu = 1; uu < XB_U; ++uu) src = (x >> 6) == uu ? brow[uu] : src;
+            const int m = (__builtin_amdgcn_readlane(src, x & 63) >> (8 * f)) & 0xFF;
             if (m <= k || m >= x) break;
-            Bq[nb++] = m;
+            if (lane == 0) listB[wv][nb] = m;
+            ++nb;
             x = m;
             f = 0;
         }
         if (k > 0) {
-            if (al) Aq[na++] = k;
-            Sq[ns++] = k;
-            Bq[nb++] = k;
+            if (lane == 0) {
+                if (al) listA[wv][na] = k;
+                listS[wv][ns] = k;
+                listB[wv][nb] = k;
+            }
+            na += al;
+            ++ns;
+            ++nb;
         }
-        const int32_t w = To[k * ld + l];
         if (w > t) break;                        // defensive
         total += w; t -= w; l = k; a = al;
     }
-    for (int x = 0, y = na - 1; x < y; ++x, --y) { const int32_t z = Aq[x]; Aq[x] = Aq[y]; Aq[y] = z; }
-    for (int x = 0, y = ns - 1; x < y; ++x, --y) { const int32_t z = Sq[x]; Sq[x] = Sq[y]; Sq[y] = z; }
-    for (int x = 0, y = nb - 1; x < y; ++x, --y) { const int32_t z = Bq[x]; Bq[x] = Bq[y]; Bq[y] = z; }
-    A_len[q] = na; S_len[q] = ns; B_len[q] = nb; obj[q] = top; lat[q] = total;
-    a_last[q] = alast; status[q] = DPC_Q_OK;
+    int32_t* Aq = A + (size_t)q * L;
+    int32_t* Sq = S + (size_t)q * L;
+    int32_t* Bq = Bs + (size_t)q * L;
+    for (int x = lane; x < na; x += 64) Aq[x] = listA[wv][na - 1 - x];
+    for (int x = lane; x < ns; x += 64) Sq[x] = listS[wv][ns - 1 - x];
+    for (int x = lane; x < nb; x += 64) Bq[x] = listB[wv][nb - 1 - x];
+    if (lane == 0) {
+        A_len[q] = na; S_len[q] = ns; B_len[q] = nb; obj[q] = top; lat[q] = total;
+        a_last[q] = alast; status[q] = DPC_Q_OK;
+    }
 }
 
 hipError_t launch_ext_iopt(int B, int L, const float* I4, float* Iopt, uint8_t* bsplit, hipStream_t st)
 {
     dim3 grid((2 * (L + 1) + X1_WAVES - 1) / X1_WAVES, B);
-    hipLaunchKernelGGL(ext_iopt_kernel, grid, dim3(64 * X1_WAVES), 0, st, L, I4, Iopt, bsplit);
+    if (L < 64)
+        hipLaunchKernelGGL((ext_iopt_kernel<1, 8>), grid, dim3(64 * X1_WAVES), 0, st, L, I4, Iopt, bsplit);
+    else if (L < 128)
+        hipLaunchKernelGGL((ext_iopt_kernel<2, 8>), grid, dim3(64 * X1_WAVES), 0, st, L, I4, Iopt, bsplit);
+    else
+        hipLaunchKernelGGL((ext_iopt_kernel<4, 4>), grid, dim3(64 * X1_WAVES), 0, st, L, I4, Iopt, bsplit);
     return hipGetLastError();
 }
 
@@ -225,9 +288,9 @@ hipError_t launch_ext_backtrack(int B, int L, int P, const int32_t* Topt, const 
                                 int32_t* B_len, float* obj, int32_t* lat, int32_t* a_last,
                                 int32_t* status, hipStream_t st)
 {
-    hipLaunchKernelGGL(ext_backtrack_kernel, dim3((Q + 63) / 64), dim3(64), 0, st, B, L, P, Topt,
-                       split, bsplit, D, Kx, Q, q_inst, q_T0, A, A_len, S, S_len, Bs, B_len, obj,
-                       lat, a_last, status);
+    hipLaunchKernelGGL(ext_backtrack_kernel, dim3((Q + XB_WAVES - 1) / XB_WAVES),
+                       dim3(64 * XB_WAVES), 0, st, B, L, P, Topt, split, bsplit, D, Kx, Q, q_inst,
+                       q_T0, A, A_len, S, S_len, Bs, B_len, obj, lat, a_last, status);
     return hipGetLastError();
 }
 
