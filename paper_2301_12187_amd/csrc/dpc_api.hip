@@ -57,7 +57,7 @@ int stage2_dispatch(int B, int L, int P, const int32_t* Topt, const float* I, fl
         if (ncu <= 0) return DPC_ERR_HIP;
         // the wave-window family reads whole 16-byte cells: narrow tables stay tiled
         const bool wave = (g_stage2_variant == 0 || g_stage2_variant == 3 || g_stage2_variant > 30) &&
-                          P >= 16;
+                          P >= 16 && P < (1 << 29);   // (byte offsets inside a row are 32-bit there)
         e = wave ? dpc::launch_stage2_wave(B, L, P, Topt, I, M, K, workspace, ncu, stream)
                  : dpc::launch_stage2_tiled(B, L, P, Topt, I, M, K, workspace, ncu, stream);
     }

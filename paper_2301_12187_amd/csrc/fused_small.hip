@@ -27,8 +27,8 @@ struct FsCand { int32_t off; float imp; };      // 8 bytes, read as one LDS acce
 #ifndef DPC_HOST_EMU
 typedef __attribute__((address_space(3))) float lds_float;
 typedef __attribute__((address_space(3))) char lds_char;
-__device__ __forceinline__ float lds_ld(int addr) { return *(const lds_float*)(uint32_t)addr; }
-__device__ __forceinline__ void lds_st(int addr, float v) { *(lds_float*)(uint32_t)addr = v; }
+__device__ __forceinline__ float lds_ld(int addr) { return *(const lds_float*)(uintptr_t)(uint32_t)addr; }
+__device__ __forceinline__ void lds_st(int addr, float v) { *(lds_float*)(uintptr_t)(uint32_t)addr = v; }
 __device__ __forceinline__ int lds_address(char* p) { return (int)(uint32_t)(uintptr_t)(lds_char*)p; }
 #else
 inline float lds_ld(int addr) { return *(const float*)(emu::g_dyn_lds + addr); }

@@ -218,7 +218,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         const int j0 = 1 + q * R;
         const int hq = min(R, ld - j0);
         const int rlo = full ? 0 : sub;            // rows of the group this task computes
-        const int rhi = full ? hq : sub + 1;
         const int ilimit = j0 + rlo;               // rows below come from global memory
         const int weff = WCAP - g;
         const int t0 = s == 0 ? 0 : WCAP + (s - 1) * weff;   // first stored column
@@ -244,6 +243,29 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         // a wave whose columns all lie beyond the table has nothing to do but
         // to take part in the barriers
         const bool wave_idle = tW >= tend;
+
+        // Stores of a finished row: which of this lane's columns are stored and
+        // at which offset from the start of the row does not depend on the row,
+        // so a store is a wave-uniform row address plus a 32-bit lane offset.
+        bool st_ok[U];
+        unsigned st_off[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = tS + tl0 + 64 * u;               // >= 0: the first computed column is
+            st_ok[u] = t >= t0 && t < tstore_end;
+            st_off[u] = (unsigned)t;
+        }
+        auto store_row = [&](int j, int rr) __attribute__((always_inline)) {
+            char* const mrow = (char*)(Mb + (size_t)j * P);
+            uint8_t* const krow = STORE_K ? Kb + (size_t)j * P : nullptr;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (st_ok[u]) {
+                    st_agent((float*)(mrow + 4u * st_off[u]), best[rr][u]);
+                    if (STORE_K) st_agent(krow + st_off[u], (uint8_t)(argp[rr] >> (8 * u)));
+                }
+            }
+        };
 
         // shift and importance of the candidate that row i offers to the row of
         // a one-row task (w = -1: none)
@@ -464,15 +486,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) {
                 if (rr != sub) continue;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int t = tS + tl0 + 64 * u;
-                    if (t >= t0 && t < tstore_end) {
-                        st_agent(Mb + (size_t)(j0 + rr) * P + t, best[rr][u]);
-                        if (STORE_K)
-                            st_agent(Kb + (size_t)(j0 + rr) * P + t, (uint8_t)(argp[rr] >> (8 * u)));
-                    }
-                }
+                store_row(j0 + rr, rr);
             }
         } else {
             __syncthreads();                           // every ring is idle: the slots below lie over them
@@ -496,17 +510,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) {
                 const int j = j0 + rr;
-                if (rr < hq) {
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const int t = tS + tl0 + 64 * u;
-                        if (t >= t0 && t < tstore_end) {
-                            st_agent(Mb + (size_t)j * P + t, best[rr][u]);
-                            if (STORE_K)
-                                st_agent(Kb + (size_t)j * P + t, (uint8_t)(argp[rr] >> (8 * u)));
-                        }
-                    }
-                }
+                if (rr < hq) store_row(j, rr);
                 if (rr + 1 < R) {
                     // row j feeds the rows below it through an LDS slot: own column t
                     // at slot position DMAX + (t - tS).  Two slots alternate: a slot
