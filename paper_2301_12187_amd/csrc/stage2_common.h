@@ -83,6 +83,20 @@ hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt
                                  float* M, uint8_t* K, void* workspace, int gmax, int dmax,
                                  int wcap, int ahead, hipStream_t st);
 
+// Row groups.  Rows 1..L are cut into NQ = ceil(L / R) groups of R rows; when R
+// does not divide L the FIRST group is the short one (it has next to no
+// predecessors), so that the groups with many predecessors carry no rows that
+// do not exist.  A task still spans R row slots: the slots past the rows of a
+// short group have no candidates and are never stored.
+__host__ __device__ __forceinline__ int s2_group_rows(int L, int R, int q)
+{
+    return q == 0 ? L - ((L + R - 1) / R - 1) * R : R;
+}
+__host__ __device__ __forceinline__ int s2_group_first_row(int L, int R, int q)
+{
+    return q == 0 ? 1 : 1 + (L - ((L + R - 1) / R - 1) * R) + (q - 1) * R;
+}
+
 __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -44,9 +44,9 @@ hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
 }
 
 // One record per (instance b, row group q, predecessor i): the candidates that
-// row i offers to the rows j0..j0+R-1 of the group (j0 = 1 + q*R), stored as
+// row i offers to the rows j0..j0+hq-1 of the group (R row slots), stored as
 // R/8 consecutive S2Rec of eight rows each.  A candidate exists when i < j,
-// j <= L and 0 <= Topt[i][j] < P.  Shifts are stored as offsets below the
+// j is a row of the group and 0 <= Topt[i][j] < P.  Shifts are stored as offsets below the
 // largest shift of the record, the position of the candidate inside the LDS
 // window of row i; a missing candidate has importance -inf and so never wins
 // whatever it is added to.  The workgroups of the first group also write row
@@ -68,7 +68,8 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     const int i = threadIdx.x;             // L <= 255: one thread per predecessor
     const int q = blockIdx.x;
     const int b = blockIdx.y;
-    const int j0 = 1 + q * R;
+    const int j0 = s2_group_first_row(L, R, q);
+    const int hq = s2_group_rows(L, R, q);
     const int32_t* To = Topt + (size_t)b * ld * ld;
     const float* Ib = I + (size_t)b * ld * ld;
     if (i == 0) viol = 0;
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     for (int x = i; x < ld * R; x += 256) {
         const int row = x / R, rr = x - row * R;
         const int j = j0 + rr;
-        if (j <= L) {
+        if (rr < hq) {
             sT[row][rr] = To[row * ld + j];
             sI[row][rr] = Ib[row * ld + j];
         }
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
         const int j = j0 + rr;
         int w = -1;
         float imp = -INFINITY;
-        if (i < ld && j <= L && i < j) {
+        if (i < ld && rr < hq && i < j) {
             const int v = sT[i][rr];
             if (v >= 0 && v < P) {
                 w = v;
@@ -146,9 +147,9 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
         for (int rr = 0; rr < R; ++rr) shifts[idx * H + rr / S2_H].w[rr % S2_H] = wv[rr];
     }
     if (i < j0 && maxs >= 0 && maxs - mins > dmax) viol = 1;
-    if (i >= j0 && i < j0 + R) {
+    if (i >= j0 && i < j0 + R) {             // (slots past the group's rows offer nothing)
 #pragma unroll
-        for (int rr = 0; rr < R; ++rr) wd[i - j0][rr] = wv[rr];
+        for (int rr = 0; rr < R; ++rr) wd[i - j0][rr] = i < j0 + hq ? wv[rr] : -1;
     }
     __syncthreads();
     if (i == 0) {
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
         return P <= wcap ? 1 : 1 + (P - wcap + (wcap - grp) - 1) / (wcap - grp);
     };
     auto count = [&](int b, int qq, int ss) {
-        const int hq = min(R, L - qq * R);
+        const int hq = s2_group_rows(L, R, qq);
         const int grp = group_of(b, qq);
         if (grp >= 0) return ss != 0 ? 0 : whole_count(grp);
         return ss < hq ? strips1 : 0;
@@ -211,13 +212,13 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
         if (ss > 0) {
             prev = (lev - 1) * B + b;
             prev_cnt = count(b, qq, ss - 1);
-            prev_row0 = qq * R + ss;
+            prev_row0 = s2_group_first_row(L, R, qq) + ss - 1;
         } else if (qq > 0) {
             const bool whole = group_of(b, qq - 1) >= 0;
-            const int psub = whole ? 0 : R - 1;
+            const int psub = whole ? 0 : s2_group_rows(L, R, qq - 1) - 1;   // its last level with tasks
             prev = ((qq - 1) * R + psub) * B + b;
             prev_cnt = count(b, qq - 1, psub);
-            prev_row0 = 1 + (qq - 1) * R + psub;
+            prev_row0 = s2_group_first_row(L, R, qq - 1) + psub;
         }
     };
 
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
             const int below = qq < q ? R : sub;     // levels of group qq that lie below this one
             if (below == 0) continue;
             const int grp = group_of(b, qq);
-            part += grp >= 0 ? whole_count(grp) : strips1 * min(below, min(R, L - qq * R));
+            part += grp >= 0 ? whole_count(grp) : strips1 * min(below, s2_group_rows(L, R, qq));
         }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);

@@ -220,8 +220,8 @@ __global__ __launch_bounds__(NT, WPE) void stage2_tiled_kernel(
         const int sub = level - q * R;
         const bool full = entg >= 0;
         const int g = full && s > 0 ? entg : 0;    // the first strip has nothing to its left
-        const int j0 = 1 + q * R;
-        const int hq = min(R, ld - j0);
+        const int j0 = s2_group_first_row(L, R, q);
+        const int hq = s2_group_rows(L, R, q);     // rows of the group; the other row slots are empty
         const int rlo = full ? 0 : sub;            // rows of the group this task computes
         const int rhi = full ? hq : sub + 1;
         const int ilimit = j0 + rlo;               // rows below come from global memory
