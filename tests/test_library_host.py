@@ -54,6 +54,38 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.dpc_status_string(12345)
 
 
+def test_argument_errors_of_the_widened_entry_points():
+    api._load_ext(), api._load_sweep(), api._load_fused()
+    lib = api.load()
+    p = ctypes.c_void_p(256)          # never dereferenced: checks fail first
+    NULL, SHAPE = -1, -2
+    # extended solver
+    assert lib.dpc_ext_importance_maxplus(1, 4, None, p, p, None) == NULL
+    assert lib.dpc_ext_importance_maxplus(1, 256, p, p, p, None) == SHAPE
+    assert lib.dpc_ext_workspace_bytes(1, 127, 100) == 0          # beyond DPC_EXT_MAX_L
+    assert lib.dpc_ext_workspace_bytes(1, 126, 100) > 0
+    assert lib.dpc_ext_knapsack(1, 127, 100, p, p, p, p, p, 1 << 30, None) == SHAPE
+    assert lib.dpc_ext_knapsack(1, 10, 100, p, None, p, p, p, 1 << 30, None) == NULL
+    assert lib.dpc_ext_backtrack(1, 10, 100, p, p, p, p, p, -1, *([p] * 12), None) == SHAPE
+    assert lib.dpc_ext_backtrack(1, 10, 100, p, p, p, p, None, 2, *([p] * 12), None) == NULL
+    # sweep steps
+    assert lib.dpc_importance_shift(1, 4, 2, 1, p, p, p, None, None) == SHAPE      # F is 1 or 4
+    assert lib.dpc_importance_shift(1, 4, 1, -1, p, p, p, None, None) == SHAPE
+    assert lib.dpc_importance_shift(1, 4, 1, 0, None, None, None, None, None) == 0  # nothing to do
+    assert lib.dpc_importance_shift(1, 4, 4, 3, p, None, p, None, None) == NULL
+    assert lib.dpc_front(1, 4, 8, p, -1, p, p, p, None) == SHAPE
+    assert lib.dpc_front(1, 4, 8, None, 4, p, p, p, None) == NULL
+    assert lib.dpc_front(1, 4, 8, p, 4, None, p, p, None) == NULL
+    assert lib.dpc_chain_latency(1, 4, p, -1, p, p, p, p, None) == SHAPE
+    assert lib.dpc_chain_latency(1, 4, p, 0, None, None, None, None, None) == 0
+    assert lib.dpc_chain_latency(1, 4, p, 3, p, None, p, p, None) == NULL
+    # single-launch path
+    assert lib.dpc_stage12_fused(1, 4, 8, None, p, p, p, p, p, None) == NULL
+    assert lib.dpc_stage12_fused(1, 300, 8, p, p, p, p, p, p, None) == SHAPE
+    assert lib.dpc_stage12_fused_supported(64, 100) == 0
+    assert lib.dpc_stage12_fused_supported(10, 4096) == 0
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     T = torch.zeros((1, 5, 5), dtype=torch.int32)
