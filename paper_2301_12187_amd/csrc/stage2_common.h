@@ -20,9 +20,21 @@ struct S2Header {
     uint32_t pad[29];              // (phase timers of instrumented builds)
     float ninf[4];                 // byte 128: sixteen bytes of -inf, the source of window
                                    // cells that lie below column 0 (layout kernel)
-    uint32_t pad2[28];
+    uint32_t choice;               // which of two prepared shapes runs (launch_stage2_decide)
+    uint32_t pad2[27];
 };
 static_assert(sizeof(S2Header) == 256, "header is one 256-byte block");
+
+// A launch can be made conditional on the header's `choice` word: its kernels
+// return at once unless the word equals `want` (word == nullptr: unconditional).
+struct S2Gate {
+    const uint32_t* word;
+    uint32_t want;
+};
+__device__ __forceinline__ bool s2_gate_closed(S2Gate g)
+{
+    return g.word != nullptr && __hip_atomic_load(g.word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != g.want;
+}
 
 struct __attribute__((aligned(64))) S2Rec {
     uint32_t offp[S2_H / 2];       // 4 * (maxs - Topt[i][j0+rr]) as 16-bit halves (rr even: low),
@@ -59,7 +71,7 @@ struct S2Entry {
     int32_t prev_row0;             // first row that entry `prev` writes
     int32_t prev2;                 // the entry before `prev` (all rows below prev_row0 are
     int32_t prev2_cnt;             // final once it is complete), -1: none; its task count
-    int32_t pad;
+    int32_t spread;                // whole group: largest spread of a predecessor's shifts into it
 };
 
 struct S2Task {
@@ -76,12 +88,35 @@ S2Layout s2_layout(int B, int L, int P, int R);
 // Queues the kernels that prepare a stage-2 launch on `st`: clears the header
 // and the completion counters, writes row 0 of M (and K), repacks Topt and I
 // into records for row groups of R (8 or 16) rows and decides per group whether it
-// runs whole (ghost width <= gmax, every spread and every shift inside the
-// group <= dmax) or row by row, and lays out the task table for strips of
-// `wcap` columns.  `ahead`: see S2Rec::pad.
+// runs whole (ghost width <= gmax, every spread <= dspread, every shift inside
+// the group <= dpad) or row by row, and lays out the task table for strips of
+// `wcap` columns.  `ahead`: see S2Rec::pad; a negative value asks for
+// min(-ahead, s2_rows_ahead(spread of the group)).
+// gated: every kernel returns at once unless the header's choice word equals
+// `want` (the word survives this call's clearing).  decide: after packing, the
+// choice word is set to 1 if more than 2 % of the groups have to run row by
+// row (so that a second, gated preparation with smaller groups takes over),
+// else to 0; the layout kernel that follows is then gated on 0.
 hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt, const float* I,
-                                 float* M, uint8_t* K, void* workspace, int gmax, int dmax,
-                                 int wcap, int ahead, hipStream_t st);
+                                 float* M, uint8_t* K, void* workspace, int gmax, int dspread,
+                                 int dpad, int wcap, int ahead, hipStream_t st,
+                                 bool gated = false, uint32_t want = 0, bool decide = false);
+
+// What the pack kernel records about a group that runs whole: ghost width
+// (< 4096) and largest spread, in one non-negative word.
+__host__ __device__ __forceinline__ int s2_group_code(int ghost, int spread) { return ghost | (spread << 12); }
+__host__ __device__ __forceinline__ int s2_group_ghost(int code) { return code & 0xFFF; }
+__host__ __device__ __forceinline__ int s2_group_spread(int code) { return code >> 12; }
+
+// The wave-window kernel keeps, per wave, a ring of S2W_RING floats in LDS.  A
+// window of 256 columns plus `spread` (plus 3 of alignment slack) takes
+// s2_window_loads() copies of 256 floats; the ring then holds 5, 3 or 2 such
+// slots, and the kernel copies 4, 2 or 1 rows ahead of the one it relaxes.
+constexpr int S2W_RING = 2560;
+constexpr int S2W_MAX_SPREAD = 764;        // four copies per row at most
+__host__ __device__ __forceinline__ int s2_window_loads(int spread) { return (256 + spread + 3 + 255) >> 8; }
+__host__ __device__ __forceinline__ int s2_ring_slots(int spread) { return S2W_RING / (256 * s2_window_loads(spread)); }
+__host__ __device__ __forceinline__ int s2_rows_ahead(int spread) { return s2_ring_slots(spread) - 1; }
 
 // Row groups.  Rows 1..L are cut into NQ = ceil(L / R) groups of R rows; when R
 // does not divide L the FIRST group is the short one (it has next to no

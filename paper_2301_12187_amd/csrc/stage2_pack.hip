@@ -36,6 +36,31 @@ __global__ void stage2_clear_kernel(uint32_t* w, int n)
     if (i < n) w[i] = 0;
 }
 
+// the same for a gated preparation: nothing unless the gate is open, and the
+// word the gate reads is left alone
+__global__ void stage2_clear_gated_kernel(uint32_t* w, int n, S2Gate gate, int keep)
+{
+    if (s2_gate_closed(gate)) return;
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n && i != keep) w[i] = 0;
+}
+
+// Sets the choice word: 1 if more than 2 % of the groups run row by row (a
+// group of 16 rows that does costs about eight times a whole one, groups of 8
+// rows about a tenth more overall), else 0.
+__global__ __launch_bounds__(256) void stage2_decide_kernel(int n, const int32_t* __restrict__ groups,
+                                                            S2Header* hdr)
+{
+    __shared__ int bad;
+    if (threadIdx.x == 0) bad = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int x = threadIdx.x; x < n; x += 256) mine += groups[x] < 0 ? 1 : 0;
+    if (mine) atomicAdd(&bad, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) hdr->choice = (long long)bad * 50 > n ? 1u : 0u;
+}
+
 hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
 {
     hipLaunchKernelGGL(stage2_clear_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st,
@@ -51,19 +76,20 @@ hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
 // window of row i; a missing candidate has importance -inf and so never wins
 // whatever it is added to.  The workgroups of the first group also write row
 // 0 of M (and K).  The workgroup also decides how the group runs:
-// groups[b][q] = ghost width g if every spread and every shift inside the
-// group fits dmax and g <= gmax, else -1 (row by row).
+// groups[b][q] = (ghost width g, largest spread) if every spread fits dspread,
+// every shift inside the group fits dpad and g <= gmax, else -1 (row by row).
 template <int R>
 __global__ __launch_bounds__(256) void stage2_pack_kernel(
     int L, int P, int NQ, const int32_t* __restrict__ Topt, const float* __restrict__ I,
     S2Rec* __restrict__ recs, S2Info* __restrict__ infos, S2Shift* __restrict__ shifts,
-    int32_t* __restrict__ groups, int gmax, int dmax, int wcap, int ahead,
-    float* __restrict__ M, uint8_t* __restrict__ K)
+    int32_t* __restrict__ groups, int gmax, int dspread, int dpad, int wcap, int ahead,
+    float* __restrict__ M, uint8_t* __restrict__ K, S2Gate gate)
 {
+    if (s2_gate_closed(gate)) return;
     constexpr int H = R / S2_H;            // records per (group, predecessor)
     __shared__ int wd[R][R];
     __shared__ int smax[256], smin[256];
-    __shared__ int viol;
+    __shared__ int spread;                 // largest spread of a predecessor's shifts into the group
     const int ld = L + 1;
     const int i = threadIdx.x;             // L <= 255: one thread per predecessor
     const int q = blockIdx.x;
@@ -72,7 +98,7 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     const int hq = s2_group_rows(L, R, q);
     const int32_t* To = Topt + (size_t)b * ld * ld;
     const float* Ib = I + (size_t)b * ld * ld;
-    if (i == 0) viol = 0;
+    if (i == 0) spread = 0;
     __syncthreads();
     if (q == 0) {
         // the base case of the recurrence: M[0][t] = +0 for every budget, no arg-max
@@ -129,12 +155,16 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     // while it works on row i
     smax[i] = max(maxs, 0);
     smin[i] = maxs < 0 ? 0 : mins;
+    if (i < j0 && maxs >= 0) atomicMax(&spread, maxs - mins);
     __syncthreads();
+    // ahead < 0: the kernel sizes its ring slots by the group's spread and
+    // works -ahead rows ahead at most, fewer when the slots are large
+    const int ahead_q = ahead >= 0 ? ahead : min(-ahead, s2_rows_ahead(spread));
 #pragma unroll
     for (int h = 0; h < H; ++h) {
         rec[h].pad[0] = (uint32_t)smax[i];
-        rec[h].pad[1] = i + ahead < 256 ? (uint32_t)smax[i + ahead] : 0u;
-        rec[h].pad[2] = i + ahead < 256 ? (uint32_t)smin[i + ahead] : 0u;
+        rec[h].pad[1] = i + ahead_q < 256 ? (uint32_t)smax[i + ahead_q] : 0u;
+        rec[h].pad[2] = i + ahead_q < 256 ? (uint32_t)smin[i + ahead_q] : 0u;
         rec[h].pad[3] = (uint32_t)i;
     }
     if (i < ld) {
@@ -146,7 +176,6 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
 #pragma unroll
         for (int rr = 0; rr < R; ++rr) shifts[idx * H + rr / S2_H].w[rr % S2_H] = wv[rr];
     }
-    if (i < j0 && maxs >= 0 && maxs - mins > dmax) viol = 1;
     if (i >= j0 && i < j0 + R) {             // (slots past the group's rows offer nothing)
 #pragma unroll
         for (int rr = 0; rr < R; ++rr) wd[i - j0][rr] = i < j0 + hq ? wv[rr] : -1;
@@ -167,8 +196,8 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
             g = max(g, n);
         }
         // a table that fits one task has no strip to its left: no ghost columns
-        const bool bad = viol || hmax > dmax || (P > wcap && g > gmax);
-        groups[(size_t)b * NQ + q] = bad ? -1 : g;
+        const bool bad = spread > dspread || hmax > dpad || (P > wcap && g > gmax);
+        groups[(size_t)b * NQ + q] = bad ? -1 : s2_group_code(g, spread);
     }
 }
 
@@ -181,8 +210,9 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
 // one combine of the 16 wave totals per tile.
 __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     int B, int L, int P, int NQ, int R, int wcap, const int32_t* __restrict__ groups,
-    S2Entry* __restrict__ entries, S2Task* __restrict__ tasks, S2Header* hdr)
+    S2Entry* __restrict__ entries, S2Task* __restrict__ tasks, S2Header* hdr, S2Gate gate)
 {
+    if (s2_gate_closed(gate)) return;
     __shared__ int wsum[2][16];
     __shared__ int red[16];
     const int tid = threadIdx.x;
@@ -193,7 +223,8 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     auto group_of = [&](int b, int qq) { return groups[(size_t)b * NQ + qq]; };
     // tasks of a whole group with ghost width grp: the first strip starts at
     // t = 0 and has no ghost columns
-    auto whole_count = [&](int grp) {
+    auto whole_count = [&](int code) {
+        const int grp = s2_group_ghost(code);
         return P <= wcap ? 1 : 1 + (P - wcap + (wcap - grp) - 1) / (wcap - grp);
     };
     auto count = [&](int b, int qq, int ss) {
@@ -243,12 +274,13 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     for (int b0 = 0, it = 0; b0 < B; b0 += 1024, ++it) {
         const int b = b0 + tid;
         const int e = level * B + b;
-        int c = 0, g = -1;
+        int c = 0, g = -1, spread_q = 0;
         int prev = -1, prev_cnt = 0, prev_row0 = -1, prev2 = -1, prev2_cnt = 0, unused = -1;
         if (b < B) {
             c = count(b, q, sub);
             const int grp = group_of(b, q);
-            g = grp >= 0 && sub == 0 ? grp : -1;
+            g = grp >= 0 && sub == 0 ? s2_group_ghost(grp) : -1;
+            spread_q = grp >= 0 && sub == 0 ? s2_group_spread(grp) : 0;
             pred(level, b, prev, prev_cnt, prev_row0);
             if (prev >= 0) pred(prev / B, b, prev2, prev2_cnt, unused);
         }
@@ -278,7 +310,7 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
             en.prev_row0 = prev_row0;
             en.prev2 = prev2;
             en.prev2_cnt = prev2_cnt;
-            en.pad = 0;
+            en.spread = spread_q;
             entries[e] = en;
             for (int x = 0; x < c; ++x) {
                 S2Task t;
@@ -296,8 +328,9 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
 }
 
 hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt, const float* I,
-                                 float* M, uint8_t* K, void* workspace, int gmax, int dmax,
-                                 int wcap, int ahead, hipStream_t st)
+                                 float* M, uint8_t* K, void* workspace, int gmax, int dspread,
+                                 int dpad, int wcap, int ahead, hipStream_t st, bool gated,
+                                 uint32_t want, bool decide)
 {
     if (R != 8 && R != 16) return hipErrorInvalidValue;
     const int NQ = (L + R - 1) / R;
@@ -305,7 +338,17 @@ hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt
     if (lay.nentries > 0x3FFFFFF0LL || lay.maxtasks > 0x3FFFFFF0LL) return hipErrorInvalidValue;
     const int N = (int)lay.nentries;
     char* base = (char*)workspace;
-    hipError_t e = launch_clear_words(workspace, (int)(sizeof(S2Header) / 4) + N, st);
+    S2Header* hdr = (S2Header*)base;
+    const S2Gate gate{gated ? &hdr->choice : nullptr, want};
+    const int nwords = (int)(sizeof(S2Header) / 4) + N;
+    if (gated)
+        hipLaunchKernelGGL(stage2_clear_gated_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st,
+                           (uint32_t*)workspace, nwords, gate,
+                           (int)(offsetof(S2Header, choice) / 4));
+    else
+        hipLaunchKernelGGL(stage2_clear_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st,
+                           (uint32_t*)workspace, nwords);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     S2Rec* recs = (S2Rec*)(base + lay.rec_off);
     S2Info* infos = (S2Info*)(base + lay.info_off);
@@ -313,15 +356,24 @@ hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt
     int32_t* groups = (int32_t*)(base + lay.group_off);
     if (R == 8)
         hipLaunchKernelGGL(stage2_pack_kernel<8>, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I,
-                           recs, infos, shifts, groups, gmax, dmax, wcap, ahead, M, K);
+                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate);
     else
         hipLaunchKernelGGL(stage2_pack_kernel<16>, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I,
-                           recs, infos, shifts, groups, gmax, dmax, wcap, ahead, M, K);
+                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    S2Gate layout_gate = gate;
+    if (decide) {
+        if ((long long)NQ * B > 0x3FFFFFF0LL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(stage2_decide_kernel, dim3(1), dim3(256), 0, st, NQ * B,
+                           (const int32_t*)groups, hdr);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        layout_gate = S2Gate{&hdr->choice, 0u};
+    }
     hipLaunchKernelGGL(stage2_layout_kernel, dim3(NQ * R), dim3(1024), 0, st, B, L, P, NQ, R, wcap,
                        (const int32_t*)groups, (S2Entry*)(base + lay.entry_off),
-                       (S2Task*)(base + lay.task_off), (S2Header*)base);
+                       (S2Task*)(base + lay.task_off), hdr, layout_gate);
     return hipGetLastError();
 }
 

@@ -509,7 +509,7 @@ static hipError_t launch_cfg(int B, int L, int P, const int32_t* Topt, const flo
     // ghost columns cost recomputation: at most a quarter of a task, and the
     // chain of shifts must fit the pad in front of a diagonal slot
     const int gmax = std::min(DMAX, WCAP / 4);
-    hipError_t e = launch_stage2_prepare(B, L, P, S2_R, Topt, I, M, K, workspace, gmax, DMAX, WCAP, 0, st);
+    hipError_t e = launch_stage2_prepare(B, L, P, S2_R, Topt, I, M, K, workspace, gmax, DMAX, DMAX, WCAP, 0, st);
     if (e != hipSuccess) return e;
 
     // resident workgroups per compute unit: WPE waves per SIMD, 4 SIMDs

@@ -105,23 +105,26 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* done,
     const S2Entry* __restrict__ entries, const S2Task* __restrict__ tasks,
     const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos,
-    const S2Shift* __restrict__ shifts, int NQ, long long wait_limit)
+    const S2Shift* __restrict__ shifts, int NQ, long long wait_limit, S2Gate gate)
 {
+    if (s2_gate_closed(gate)) return;                // (another shape was chosen for this call)
     constexpr int U = 4;                             // columns per lane: one arg-max byte each
     constexpr int H = R / S2_H;                      // records per (group, predecessor)
     constexpr int NT = NW * 64;
     constexpr int WV = 64 * U;                       // columns per wave
     constexpr int WCAP = NW * WV;                    // columns per task
-    // a window holds at most WV + DMAX columns plus 3 of alignment slack
-    constexpr int NLD = (WV + DMAX + 3 + 255) / 256; // loads per row and wave
-    constexpr int SLOTF = NLD * 256;                 // floats per ring slot
-    constexpr int RINGF = NSLOT * SLOTF;             // floats per wave
-    constexpr int D = NSLOT - 1;                     // rows in flight ahead of the current one
+    // Per wave a ring of S2W_RING floats: a window holds WV + spread columns
+    // plus 3 of alignment slack and takes 2, 3 or 4 copies of 256 floats, so
+    // the ring has 5, 3 or 2 slots and the wave works 4, 2 or 1 rows ahead
+    // (chosen per task from the spread the pack kernel found for the group).
+    // DMAX: pad in front of a diagonal slot = largest shift inside a group.
+    constexpr int RINGF = S2W_RING;                  // floats per wave
     constexpr int DSLOTW = WCAP + DMAX + 4;          // floats per diagonal slot
     constexpr int LDSF = NW * RINGF > 2 * DSLOTW ? NW * RINGF : 2 * DSLOTW;
     constexpr float NINF = -INFINITY;
     static_assert(R == 8 || R == 16, "one or two records per predecessor");
-    static_assert(D >= 1 && D * NLD <= 8, "the counted wait covers at most 8 loads");
+    static_assert(NSLOT * 512 == S2W_RING, "five slots of the smallest window fill the ring");
+    static_assert(WV == 256, "the window sizes in stage2_common.h are for 256 columns per wave");
     static_assert(DMAX % 4 == 0, "diagonal slots stay 16-byte aligned");
     __shared__ __attribute__((aligned(16))) float lds[LDSF];
 
@@ -154,7 +157,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             int ticket = 0;
             if (lane == 0) ticket = (int)atomicAdd(&hdr->ticket, 1u);
             ticket = __builtin_amdgcn_readfirstlane(ticket);
-            int e = -1, strip = 0, g = -1, ok = 1, prev = -1, prev_cnt = 0, prev_row0 = -1;
+            int e = -1, strip = 0, g = -1, ok = 1, prev = -1, prev_cnt = 0, prev_row0 = -1, spread = 0;
             if (ticket < total) {
                 const S2Task tk = tasks[ticket];
                 const S2Entry ent = entries[tk.entry];
@@ -164,6 +167,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 prev = ent.prev;
                 prev_cnt = ent.prev_cnt;
                 prev_row0 = ent.prev_row0;
+                spread = ent.spread;
                 // every row below prev_row0 is final once the entry before `prev`
                 // is complete; `prev` itself is waited for when its rows come up
                 if (ent.prev2 >= 0) {
@@ -190,6 +194,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 sh_word[3] = prev;
                 sh_word[4] = prev_cnt;
                 sh_word[5] = prev_row0;
+                sh_word[6] = spread;
             }
         }
         __syncthreads();
@@ -199,6 +204,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         const int prev = __builtin_amdgcn_readfirstlane(sh_word[3]);
         const uint32_t prev_cnt = (uint32_t)__builtin_amdgcn_readfirstlane(sh_word[4]);
         const int prev_row0 = __builtin_amdgcn_readfirstlane(sh_word[5]);
+        const int spread = __builtin_amdgcn_readfirstlane(sh_word[6]);
         __syncthreads();
 #ifdef DPC_S2_TIMERS
         if (e < 0 && tid == 0) {
@@ -299,7 +305,9 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
 
         // Start the copy of the window of row i into ring slot `slot`: exactly
         // NLD loads, every lane active.
-        auto issue_row = [&](int i, int slot, int maxs, int mins) __attribute__((always_inline)) {
+        auto issue_row = [&](auto nld_c, int i, int slot, int maxs, int mins) __attribute__((always_inline)) {
+            constexpr int NLD = decltype(nld_c)::value;
+            constexpr int SLOTF = NLD * 256;
             const int lo = tW - maxs;
             const int lo4 = lo & ~3;                               // floor to a multiple of 4
             const int n4 = (WV + maxs - mins + (lo - lo4) + 3) & ~3;   // cells needed, in floats
@@ -365,13 +373,13 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             }
         };
         // The same for a one-row task: only row `sub` of the group, at one shift.
-        auto relax_one = [&](int i, int slot) __attribute__((always_inline)) {
+        auto relax_one = [&](int i, int slot) __attribute__((always_inline)) {   // (smallest window: 512 floats per slot)
             int w;
             float imp;
             one_row_of(i, w, imp);
             if (w < 0) return;
             const int delta = (tS - w) & 3;
-            const float* base = (const float*)(lbase + (slot * SLOTF + delta) * 4);
+            const float* base = (const float*)(lbase + (slot * 512 + delta) * 4);
             float cand[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) cand[u] = base[64 * u] + imp;
@@ -409,14 +417,21 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         // ---------------- off-diagonal part: rows i < ilimit ----------------
         TMARK(t_b);
         TACC(3, t_a, t_b);
-        if (!wave_idle) {
+        // The part itself, compiled once per window size: NLD copies of 256 floats
+        // per row, S2W_RING / (256 NLD) ring slots, D = slots - 1 rows ahead.
+        auto offdiag = [&](auto nld_c) __attribute__((always_inline)) {
+            constexpr int NLD = decltype(nld_c)::value;
+            constexpr int SLOTF = NLD * 256;
+            constexpr int NSL = S2W_RING / SLOTF;
+            constexpr int D = NSL - 1;
+            static_assert(D >= 1 && D * NLD <= 8, "the counted wait covers at most 8 loads");
 #pragma unroll
             for (int d = 0; d < D; ++d)
                 if (d < ilimit) {
                     if (d == prev_row0) wait_prev();
                     int maxs, mins;
                     window_of(d, maxs, mins);
-                    issue_row(d, d, maxs, mins);
+                    issue_row(nld_c, d, d, maxs, mins);
                 }
             int slot = 0;                              // ring slot of row i
             int ahead = D;                             // ring slot of row i + D
@@ -431,7 +446,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     // row there is nothing left to start and nothing to leave
                     if (i + D < ilimit) {
                         if (i + D == prev_row0) wait_prev();
-                        issue_row(i + D, ahead, (int)cur[0].pad[1], (int)cur[0].pad[2]);
+                        issue_row(nld_c, i + D, ahead, (int)cur[0].pad[1], (int)cur[0].pad[2]);
                         wait_vm(D * NLD);
                     } else {
                         wait_vm(0);
@@ -460,15 +475,16 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     TACC(0, ta, tb);
                     TACC(2, tb, tc);
                     ahead = slot;
-                    slot = slot + 1 == NSLOT ? 0 : slot + 1;
+                    slot = slot + 1 == NSL ? 0 : slot + 1;
                 }
-            } else {
+            } else if constexpr (NLD == 2) {
+                // (a one-row task has one shift per predecessor: the smallest window)
                 for (int i = 0; i < ilimit; ++i) {
                     if (i + D < ilimit) {
                         if (i + D == prev_row0) wait_prev();
                         int maxs, mins;
                         window_of(i + D, maxs, mins);
-                        issue_row(i + D, ahead, maxs, mins);
+                        issue_row(nld_c, i + D, ahead, maxs, mins);
                         wait_vm(D * NLD);
                     } else {
                         wait_vm(0);
@@ -476,9 +492,15 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     asm volatile("" ::: "memory");
                     relax_one(i, slot);
                     ahead = slot;
-                    slot = slot + 1 == NSLOT ? 0 : slot + 1;
+                    slot = slot + 1 == NSL ? 0 : slot + 1;
                 }
             }
+        };
+        if (!wave_idle) {
+            const int nld = s2_window_loads(full ? spread : 0);   // copies of 256 floats per row: 2..4
+            if (nld <= 2) offdiag(std::integral_constant<int, 2>{});
+            else if (nld == 3) offdiag(std::integral_constant<int, 3>{});
+            else offdiag(std::integral_constant<int, 4>{});
         }
         TMARK(t_c);
         if (!full) {
@@ -558,9 +580,12 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     }
 }
 
+// gated / want / decide: see launch_stage2_prepare; the main kernel is gated on
+// `want` when either is set
 template <int R, int NW, int NSLOT, int DMAX, int WPE>
 static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
-                                  uint8_t* K, void* workspace, int num_cu, hipStream_t st)
+                                  uint8_t* K, void* workspace, int num_cu, hipStream_t st,
+                                  bool gated = false, uint32_t want = 0, bool decide = false)
 {
     constexpr int WCAP = NW * 256;
     const int NQ = (L + R - 1) / R;
@@ -574,12 +599,14 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
     S2Info* infos = (S2Info*)(base + lay.info_off);
     S2Shift* shifts = (S2Shift*)(base + lay.shift_off);
 
-    // ghost columns cost recomputation: at most a quarter of a task, and the
-    // chain of shifts must fit the pad in front of a diagonal slot
-    const int gmax = std::min(DMAX, WCAP / 4);
-    hipError_t e = launch_stage2_prepare(B, L, P, R, Topt, I, M, K, workspace, gmax, DMAX, WCAP,
-                                         NSLOT - 1, st);
+    // ghost columns cost recomputation: at most half of a task (beyond that the
+    // group runs row by row), and the chain of shifts must fit the pad in front
+    // of a diagonal slot
+    const int gmax = std::min(DMAX, WCAP / 2);
+    hipError_t e = launch_stage2_prepare(B, L, P, R, Topt, I, M, K, workspace, gmax, S2W_MAX_SPREAD,
+                                         DMAX, WCAP, -(NSLOT - 1), st, gated, want, decide);
     if (e != hipSuccess) return e;
+    const S2Gate gate{gated || decide ? &hdr->choice : nullptr, want};
 
     // resident workgroups per compute unit: WPE waves per SIMD, 4 SIMDs
     constexpr int wg_per_cu = (WPE * 4) / NW;
@@ -589,11 +616,11 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
     if (K)
         hipLaunchKernelGGL((stage2_wave_kernel<R, NW, NSLOT, DMAX, WPE, true>), dim3(grid),
                            dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
-                           infos, shifts, NQ, wait_limit);
+                           infos, shifts, NQ, wait_limit, gate);
     else
         hipLaunchKernelGGL((stage2_wave_kernel<R, NW, NSLOT, DMAX, WPE, false>), dim3(grid),
                            dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
-                           infos, shifts, NQ, wait_limit);
+                           infos, shifts, NQ, wait_limit, gate);
     return hipGetLastError();
 }
 
@@ -617,18 +644,29 @@ hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const fl
         else if (P <= 1536) shape = 1;
         else shape = (L >= 128 && P >= 8192) ? 5 : 2;
     }
+    if (g_s2w_shape == 0 && shape == 5) {
+        // Groups of 16 rows need the shifts of 16 consecutive layers to fit a
+        // window and a ghost region; whether they do is only known on the
+        // device.  Prepare them, let the device decide, and queue the 8-row
+        // shape behind it: of the two main kernels one returns at once.
+        hipError_t e = launch_wave_cfg<16, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st,
+                                                         false, 0u, true);
+        if (e != hipSuccess) return e;
+        return launch_wave_cfg<8, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, true,
+                                                1u, false);
+    }
     switch (shape) {
-        // groups of 8 rows: waves per task, ring slots, largest spread, waves per SIMD
-        case 1: return launch_wave_cfg<8, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 2: return launch_wave_cfg<8, 8, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 3: return launch_wave_cfg<8, 2, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 4: return launch_wave_cfg<8, 1, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        // groups of 8 rows: waves per task, ring slots (smallest window), largest shift inside a group, waves per SIMD
+        case 1: return launch_wave_cfg<8, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 2: return launch_wave_cfg<8, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 3: return launch_wave_cfg<8, 2, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 4: return launch_wave_cfg<8, 1, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         // groups of 16 rows
-        case 5: return launch_wave_cfg<16, 4, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 6: return launch_wave_cfg<16, 8, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 7: return launch_wave_cfg<16, 2, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 8: return launch_wave_cfg<16, 16, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 9: return launch_wave_cfg<8, 16, 5, 252, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 5: return launch_wave_cfg<16, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 6: return launch_wave_cfg<16, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 7: return launch_wave_cfg<16, 2, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 8: return launch_wave_cfg<16, 16, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
+        case 9: return launch_wave_cfg<8, 16, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -176,6 +176,34 @@ def test_stage1_at_the_chain_lengths_where_the_kernel_changes(L):
         assert (Topt[b].cpu().numpy() == To).all() and (split[b].cpu().numpy() == sp).all(), (L, b)
 
 
+@pytest.mark.parametrize("variant", [0, 31, 32, 35, 36])
+@pytest.mark.parametrize("scale", [3, 8, 20])
+def test_large_latencies_wide_windows(variant, scale):
+    """Latencies that add up along the chain and are large against a ring slot:
+    windows of three and four copies per row, wide ghost regions, and beyond
+    them the row-by-row path."""
+    cfg = inputs.CONFIGS[4]
+    T, I, base = inputs.make_batch(cfg, seed=21, B=6)
+    T = np.where(T < DPC_INF, T * scale, T).astype(np.int32)
+    qi, qt = inputs.budgets(cfg, base * scale)
+    g = run_gpu(T, I, cfg.P, qi, qt, variant=variant)
+    compare(g, run_oracle(T, I, cfg.P, qi, qt, threads=6), cfg.L, f"latencies x{scale}")
+
+
+@pytest.mark.parametrize("scale", [1, 3, 8])
+def test_device_side_choice_between_group_sizes(scale):
+    """Long, wide tables prepare groups of 16 rows and let the device decide
+    whether they run or the 8-row shape queued behind them does: small
+    latencies (16-row groups run), larger ones (wider windows), and latencies
+    whose 16-layer sums exceed what a group can hold (the 8-row shape runs)."""
+    cfg = inputs.CONFIGS[5]
+    T, I, base = inputs.make_batch(cfg, seed=2, B=3)
+    T = np.where(T < DPC_INF, T * scale, T).astype(np.int32)
+    qi, qt = inputs.budgets(cfg, base)
+    g = run_gpu(T, I, cfg.P, qi, qt, variant=0)
+    compare(g, run_oracle(T, I, cfg.P, qi, qt, threads=3), cfg.L, f"cfg5 shape, latencies x{scale}")
+
+
 def test_bad_queries_and_empty_query_list():
     cfg = inputs.CONFIGS[1]
     T, I, _ = inputs.make_batch(cfg, seed=0)

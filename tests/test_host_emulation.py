@@ -84,6 +84,36 @@ def test_row_by_row_groups_and_missing_candidates(emu, tmp_path, shape):
     _run(emu, tmp_path, np.stack(Ts), np.stack(Is), P, shape)
 
 
+def _additive_tables(rng, B, L, lo, hi):
+    """Latencies that add up along the chain (block latency about the sum of its
+    layers), so that the shifts of one predecessor into a group of rows spread
+    over several hundred columns."""
+    Ts, Is = [], []
+    for _ in range(B):
+        T, I = rand_tables(rng, L, tmax=5, ikind="neg")
+        base = rng.integers(lo, hi + 1, L)
+        for i in range(L + 1):
+            for j in range(i + 1, L + 1):
+                T[i, j] = max(1, int(rng.uniform(0.7, 1.1) * base[i:j].sum()))
+        Ts.append(T)
+        Is.append(I)
+    return np.stack(Ts), np.stack(Is)
+
+
+# spreads of about 300 (three copies per window, two rows ahead), 600 (four
+# copies, one row ahead) and beyond 764 (row by row) for groups of 8 rows;
+# twice that for groups of 16
+# (a table wider than a task also needs ghost columns, at most half a task:
+#  the widest windows are reached with P = 1000, one task per group)
+@pytest.mark.parametrize("shape,lo,hi,P", [(1, 35, 45, 1400), (1, 70, 90, 1000), (1, 55, 65, 1400),
+                                           (5, 15, 22, 1400), (5, 35, 45, 1000), (2, 70, 90, 2100),
+                                           (1, 120, 160, 1400)])
+def test_windows_wider_than_the_smallest_ring_slot(emu, tmp_path, shape, lo, hi, P):
+    rng = np.random.default_rng(503 + lo)
+    T, I = _additive_tables(rng, 2, 19, lo, hi)
+    _run(emu, tmp_path, T, I, P, shape)
+
+
 # ---- the single-launch kernel for small instances (stage 1 + stage 2) ----
 
 def _run_fused(emu_fused, tmp_path, T, I, P, lds_limit):
