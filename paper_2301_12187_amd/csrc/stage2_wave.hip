@@ -16,7 +16,9 @@
 // columns and feeds itself: for predecessor row i it copies the window of
 // that row that ITS columns need, [tW - maxshift_i, tW + 64*U - minshift_i),
 // into a slot of its own ring in LDS (global -> LDS loads, 16 bytes per lane,
-// no registers), NSLOT-1 rows ahead of the row it is relaxing.  Nothing in this
+// no registers), a few rows ahead of the row it is relaxing (the ring holds 5,
+// 3 or 2 slots, sized per task from the largest spread of shifts that the
+// pack kernel found for the group: windows of up to 256 + 764 columns).  Nothing in this
 // part is shared between waves, so there is no workgroup barrier in it: a wave
 // waits only for its own loads, with a counted wait that leaves the loads of
 // the rows ahead in flight.  To make that count exact every row issues the
