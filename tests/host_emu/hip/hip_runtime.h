@@ -136,6 +136,7 @@ template <class T> inline T __hip_atomic_load(const T* p, int order, int) { T v;
 template <class T> inline void __hip_atomic_store(T* p, T v, int order, int) { __atomic_store(p, &v, order); }
 template <class T> inline T __hip_atomic_fetch_add(T* p, T v, int order, int) { return __atomic_fetch_add(p, v, order); }
 inline unsigned atomicAdd(unsigned* p, unsigned v) { return __atomic_fetch_add(p, v, __ATOMIC_RELAXED); }
+inline int atomicAdd(int* p, int v) { return __atomic_fetch_add(p, v, __ATOMIC_RELAXED); }
 inline int atomicMax(int* p, int v)
 {
     int old = __atomic_load_n(p, __ATOMIC_RELAXED);
