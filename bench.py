@@ -297,8 +297,8 @@ def bench_ext(args, np, torch, api, inputs):
 
 def bench_sweep(args, np, torch, api, inputs):
     """Sweep over the normalisation constant: one step = dpc_importance_shift (n_raw tables x
-    n_alpha constants -> B instances) + stage 1 + stage 2 + dpc_front + dpc_backtrack +
-    dpc_chain_latency at A."""
+    n_alpha constants -> B instances) + stage 1 + stage 2 + dpc_front + dpc_front_queries +
+    dpc_backtrack at every point of every trade-off curve + dpc_chain_latency at A."""
     cid = 3 if args.config == 5 else args.config
     cfg = inputs.CONFIGS[cid]
     dev = torch.device("cuda:0")
@@ -308,21 +308,27 @@ def bench_sweep(args, np, torch, api, inputs):
     n_raw = T0.shape[0]
     B = n_raw * n_alpha
     T = np.repeat(T0, n_alpha, axis=0)
-    qi, qt = inputs.budgets(cfg, np.repeat(base, n_alpha, axis=0))
     Td = torch.from_numpy(T).to(dev)
     Ird = torch.from_numpy(I_raw).to(dev)
     ald = torch.from_numpy(alphas).to(dev)
-    qid, qtd = torch.from_numpy(qi).to(dev), torch.from_numpy(qt).to(dev)
-    buf = api.Buffers(B, cfg.L, cfg.P, len(qi), store_K=True)
+    # one query per point of every curve; the list is built on the device, so its
+    # room is fixed (64 points per instance on average) and the unused tail holds
+    # instance -1, which set recovery answers with "bad query" at once
+    qcap = 64 * B
+    qid = torch.full((qcap,), -1, dtype=torch.int32, device=dev)
+    qtd = torch.zeros((qcap,), dtype=torch.int32, device=dev)
+    qn = torch.zeros((1,), dtype=torch.int32, device=dev)
+    buf = api.Buffers(B, cfg.L, cfg.P, qcap, store_K=True)
     Id = torch.empty((B, cfg.L + 1, cfg.L + 1), dtype=torch.float32, device=dev)
     cap = 256
     ft = torch.empty((B, cap), dtype=torch.int32, device=dev)
     fo = torch.empty((B, cap), dtype=torch.float32, device=dev)
     fl = torch.empty((B,), dtype=torch.int32, device=dev)
-    latA = torch.empty((len(qi),), dtype=torch.int32, device=dev)
+    latA = torch.empty((qcap,), dtype=torch.int32, device=dev)
     api.dpc_set_stage2_variant(args.variant)
     stream = torch.cuda.current_stream()
-    names = ["importance_shift", "stage1", "stage2", "front", "backtrack", "chain_latency"]
+    names = ["importance_shift", "stage1", "stage2", "front", "front_queries", "backtrack",
+             "chain_latency"]
 
     def step(ev=None):
         calls = [
@@ -330,6 +336,7 @@ def bench_sweep(args, np, torch, api, inputs):
             lambda: api.dpc_stage1_minplus(Td, buf.Topt, buf.split),
             lambda: api.dpc_stage2_knapsack(buf.Topt, Id, buf.M, buf.K, buf.workspace),
             lambda: api.dpc_front(buf.M, ft, fo, fl),
+            lambda: api.dpc_front_queries(ft, fl, qid, qtd, qn),
             lambda: api.dpc_backtrack(buf.Topt, buf.split, Id, buf.M, buf.K, qid, qtd, buf.A,
                                       buf.A_len, buf.S, buf.S_len, buf.obj, buf.lat, buf.status),
             lambda: api.dpc_chain_latency(Td, qid, buf.A, buf.A_len, latA),
@@ -344,7 +351,7 @@ def bench_sweep(args, np, torch, api, inputs):
     for _ in range(args.warmup):
         step()
     api.dpc_stage2_check(buf.workspace)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for ev in evs:
@@ -363,7 +370,8 @@ def bench_sweep(args, np, torch, api, inputs):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"alpha sweep on {cfg.name}", "raw_tables": n_raw, "alphas": n_alpha,
-                   "B": B, "L": cfg.L, "P": cfg.P, "queries": int(len(qi)), "front_cap": cap,
+                   "B": B, "L": cfg.L, "P": cfg.P, "queries": int(qn.item()), "query_room": qcap,
+                   "front_cap": cap,
                    "stage2_variant": args.variant, "seed": args.seed},
         "stage_ms": seg,
         "feasible_queries": int(ok.sum().item()),
@@ -386,8 +394,13 @@ def bench_sweep(args, np, torch, api, inputs):
         Is = np.stack([oracle.importance_shift(I_raw[b // n_alpha], alphas[b % n_alpha])[0]
                        for b in range(B)])
         To, sp, Mo, Ko = oracle.solve_batch(T, Is, cfg.P, want_K=True, threads=cores)
+        fts = np.full((B, cap), -1, np.int32)
+        fls = np.zeros(B, np.int32)
         for b in range(B):
-            oracle.front(Mo[b, cfg.L], cap)
+            t_, _, n_ = oracle.front(Mo[b, cfg.L], cap)
+            fts[b, :len(t_)] = t_
+            fls[b] = n_
+        qi, qt, _ = oracle.front_queries(fts, fls, qcap)
         for b, t in zip(qi, qt):
             r = oracle.backtrack(To[b], sp[b], Is[b], Mo[b], Ko[b], int(t))
             oracle.chain_latency(T[b], None if r["status"] else r["A"])

@@ -302,6 +302,23 @@ int dpc_front(int32_t B, int32_t L, int32_t P, const float *M, int32_t cap, int3
               float *front_obj, int32_t *front_len, void *stream);
 
 /*
+ * dpc_front_queries - the points of the curves of a batch as one list of
+ * queries (instance, budget), instance by instance, budgets ascending: the
+ * budgets a sweep over T0 has to recover sets for (pass the list to
+ * dpc_backtrack; a budget between two points has the solution of the point
+ * below it).
+ *   front_t, front_len   in   as written by dpc_front with the same cap; an
+ *                             instance contributes min(front_len, cap) points
+ *   qcap                      room in q_inst / q_T0, >= 0
+ *   q_inst, q_T0         out  int32 [qcap]
+ *   q_count              out  int32 [1]   number of queries in all; when it
+ *                             exceeds qcap only the first qcap are written
+ */
+int dpc_front_queries(int32_t B, int32_t cap, const int32_t *front_t, const int32_t *front_len,
+                      int32_t qcap, int32_t *q_inst, int32_t *q_T0, int32_t *q_count,
+                      void *stream);
+
+/*
  * dpc_chain_latency - latency of the network merged at a given ordered set X:
  * the sum of T over consecutive members of 0 -> X -> L, saturating at DPC_INF
  * (the constraint side of Eq. 4 with X in place of S).  With X = S of

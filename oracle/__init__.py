@@ -26,5 +26,6 @@ from .api import (  # noqa: F401
     brute_ext_objective,
     importance_shift,
     front,
+    front_queries,
     chain_latency,
 )

@@ -260,6 +260,8 @@ def _load_sweep():
         lib.oracle_importance_shift.restype = ctypes.c_double
         lib.oracle_front.argtypes = [i32, vp, i32, vp, vp]
         lib.oracle_front.restype = i32
+        lib.oracle_front_queries.argtypes = [i32, i32, vp, vp, i32, vp, vp]
+        lib.oracle_front_queries.restype = i32
         lib.oracle_chain_latency.argtypes = [i32, vp, i32, vp]
         lib.oracle_chain_latency.restype = i32
         lib._sweep_ready = True
@@ -295,3 +297,14 @@ def chain_latency(T, X):
         return _load_sweep().oracle_chain_latency(L, _p(T), -1, None)
     X = np.ascontiguousarray(X, np.int32)
     return _load_sweep().oracle_chain_latency(L, _p(T), len(X), _p(X))
+
+
+def front_queries(front_t, front_len, qcap):
+    """front_t int32 [B][cap], front_len int32 [B] -> (q_inst, q_T0 int32 [min(n, qcap)], n)."""
+    B, cap = front_t.shape
+    _chk(front_t, np.int32, (B, cap))
+    _chk(front_len, np.int32, (B,))
+    qi = np.full(qcap, -1, np.int32)
+    qt = np.full(qcap, -1, np.int32)
+    n = _load_sweep().oracle_front_queries(B, cap, _p(front_t), _p(front_len), qcap, _p(qi), _p(qt))
+    return qi[:min(n, qcap)], qt[:min(n, qcap)], n

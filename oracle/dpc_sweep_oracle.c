@@ -14,6 +14,9 @@
  *                             changes, read off the last row of Algorithm 2's
  *                             table: the (latency, objective) trade-off curve
  *                             that the sweeps over T0 in the experiments walk.
+ *   oracle_front_queries      the points of the curves of a batch as a flat list
+ *                             of (instance, budget) pairs, the budgets a sweep
+ *                             over T0 has to recover sets for.
  *   oracle_chain_latency      the latency of a network merged at a given
  *                             ordered set (left side of the constraint in
  *                             Eq. 4 with the given set in place of S); with
@@ -100,4 +103,26 @@ int32_t oracle_chain_latency(int32_t L, const int32_t *T, int32_t n, const int32
         from = to;
     }
     return (int32_t)total;
+}
+
+/* front_t: int32 [B][cap], front_len: int32 [B] as written by oracle_front for
+ * every instance (lengths may exceed cap: then cap points were stored).  Writes
+ * at most qcap queries, instance by instance, budgets ascending, and returns
+ * how many there are in all. */
+int32_t oracle_front_queries(int32_t B, int32_t cap, const int32_t *front_t,
+                             const int32_t *front_len, int32_t qcap, int32_t *q_inst,
+                             int32_t *q_T0)
+{
+    int32_t n = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t len = front_len[b] < cap ? front_len[b] : cap;
+        for (int32_t k = 0; k < len; ++k) {
+            if (n < qcap) {
+                q_inst[n] = b;
+                q_T0[n] = front_t[(size_t)b * cap + k];
+            }
+            ++n;
+        }
+    }
+    return n;
 }

@@ -24,7 +24,7 @@ EXPORTS = (
     "dpc_set_stage2_variant",
     "dpc_ext_importance_maxplus", "dpc_ext_workspace_bytes", "dpc_ext_knapsack",
     "dpc_ext_check", "dpc_ext_backtrack",
-    "dpc_importance_shift", "dpc_front", "dpc_chain_latency",
+    "dpc_importance_shift", "dpc_front", "dpc_front_queries", "dpc_chain_latency",
     "dpc_stage12_fused_supported", "dpc_stage12_fused",
 )
 
@@ -285,6 +285,8 @@ def _load_sweep():
         lib.dpc_importance_shift.restype = ctypes.c_int
         lib.dpc_front.argtypes = [i32, i32, i32, vp, i32, vp, vp, vp, vp]
         lib.dpc_front.restype = ctypes.c_int
+        lib.dpc_front_queries.argtypes = [i32, i32, vp, vp, i32, vp, vp, vp, vp]
+        lib.dpc_front_queries.restype = ctypes.c_int
         lib.dpc_chain_latency.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
         lib.dpc_chain_latency.restype = ctypes.c_int
         lib._sweep_ready = True
@@ -318,6 +320,17 @@ def dpc_front(M, front_t, front_obj, front_len, stream=None):
         _dev(front_t, torch.int32, (B, cap), "front_t"),
         _dev(front_obj, torch.float32, (B, cap), "front_obj"),
         _dev(front_len, torch.int32, (B,), "front_len"), _stream(stream)))
+
+
+def dpc_front_queries(front_t, front_len, q_inst, q_T0, q_count, stream=None):
+    """front_t int32 [B][cap], front_len int32 [B] -> q_inst, q_T0 int32 [qcap], q_count int32 [1]."""
+    B, cap = front_t.shape
+    qcap = q_inst.shape[0]
+    _check(_load_sweep().dpc_front_queries(
+        B, cap, _dev(front_t, torch.int32, (B, cap), "front_t"),
+        _dev(front_len, torch.int32, (B,), "front_len"), qcap,
+        _dev(q_inst, torch.int32, (qcap,), "q_inst"), _dev(q_T0, torch.int32, (qcap,), "q_T0"),
+        _dev(q_count, torch.int32, (1,), "q_count"), _stream(stream)))
 
 
 def dpc_chain_latency(T, q_inst, X, X_len, lat, stream=None):

@@ -261,6 +261,17 @@ int dpc_front(int32_t B, int32_t L, int32_t P, const float* M, int32_t cap, int3
     return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
 }
 
+int dpc_front_queries(int32_t B, int32_t cap, const int32_t* front_t, const int32_t* front_len,
+                      int32_t qcap, int32_t* q_inst, int32_t* q_T0, int32_t* q_count, void* stream)
+{
+    if (B < 1 || B > 65535 * 1024 || cap < 0 || qcap < 0) return DPC_ERR_SHAPE;
+    if (!front_len || !q_count || (cap > 0 && !front_t) || (qcap > 0 && (!q_inst || !q_T0)))
+        return DPC_ERR_NULL;
+    hipError_t e = dpc::launch_front_queries(B, cap, front_t, front_len, qcap, q_inst, q_T0,
+                                             q_count, (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
 int dpc_chain_latency(int32_t B, int32_t L, const int32_t* T, int32_t Q, const int32_t* q_inst,
                       const int32_t* X, const int32_t* X_len, int32_t* lat, void* stream)
 {

@@ -51,6 +51,9 @@ hipError_t launch_importance_shift(int B, int L, int F, int n_alpha, const float
                                    hipStream_t st);
 hipError_t launch_front(int B, int L, int P, const float* M, int cap, int32_t* front_t,
                         float* front_obj, int32_t* front_len, hipStream_t st);
+hipError_t launch_front_queries(int B, int cap, const int32_t* front_t, const int32_t* front_len,
+                                int qcap, int32_t* q_inst, int32_t* q_T0, int32_t* q_count,
+                                hipStream_t st);
 hipError_t launch_chain_latency(int B, int L, const int32_t* T, int Q, const int32_t* q_inst,
                                 const int32_t* X, const int32_t* X_len, int32_t* lat,
                                 hipStream_t st);

@@ -113,6 +113,84 @@ hipError_t launch_front(int B, int L, int P, const float* M, int cap, int32_t* f
     return hipGetLastError();
 }
 
+// ---- the points of the curves as a query list -------------------------------------
+// Instances are handled in tiles of 1024, FQ_SPLIT workgroups per tile.  Every
+// workgroup first adds up the counts min(front_len, cap) of all earlier tiles
+// (a strided sum, then one reduction), then scans the counts of its tile (wave
+// scan, then the 16 wave totals), and copies its share of the tile's points,
+// one list position per thread and pass (coalesced stores); the instance of a
+// position is found by bisection of the tile's start offsets in LDS.
+constexpr int FQ_SPLIT = 16;
+
+__global__ __launch_bounds__(1024) void front_queries_kernel(
+    int B, int cap, const int32_t* __restrict__ front_t, const int32_t* __restrict__ front_len,
+    int qcap, int32_t* __restrict__ q_inst, int32_t* __restrict__ q_T0,
+    int32_t* __restrict__ q_count)
+{
+    __shared__ long long red[16];
+    __shared__ int wsum[16];
+    __shared__ long long sstart[1024];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b0 = blockIdx.y * 1024;
+    // ---- points of the earlier tiles
+    long long part = 0;
+    for (int b = tid; b < b0; b += 1024) part += max(min(front_len[b], cap), 0);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const int lo = __shfl_xor((int)(part & 0xFFFFFFFFll), d, 64);
+        const int hi = __shfl_xor((int)(part >> 32), d, 64);
+        part += ((long long)hi << 32) | (unsigned int)lo;
+    }
+    if (lane == 0) red[wave] = part;
+    // ---- this tile
+    const int b = b0 + tid;
+    const int n = b < B ? max(min(front_len[b], cap), 0) : 0;
+    int incl = n;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int v = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += v;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    long long base = 0;
+    int before = 0, tile = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        base += red[w];
+        const int v = wsum[w];
+        if (w < wave) before += v;
+        tile += v;
+    }
+    sstart[tid] = base + before + incl - n;
+    __syncthreads();
+    for (long long q = base + (long long)blockIdx.x * 1024 + tid; q < base + tile && q < qcap;
+         q += 1024 * FQ_SPLIT) {
+        int lo = 0, hi = 1023;                            // the last instance that starts at or before q
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (sstart[mid] <= q) lo = mid; else hi = mid - 1;
+        }
+        q_inst[q] = b0 + lo;
+        q_T0[q] = front_t[(size_t)(b0 + lo) * cap + (int)(q - sstart[lo])];
+    }
+    if (tid == 0 && blockIdx.x == 0 && blockIdx.y == gridDim.y - 1) {
+        const long long total = base + tile;
+        *q_count = (int32_t)(total > 0x7FFFFFFFll ? 0x7FFFFFFFll : total);
+    }
+}
+
+hipError_t launch_front_queries(int B, int cap, const int32_t* front_t, const int32_t* front_len,
+                                int qcap, int32_t* q_inst, int32_t* q_T0, int32_t* q_count,
+                                hipStream_t st)
+{
+    const int ntiles = (B + 1023) / 1024;
+    if (ntiles > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(front_queries_kernel, dim3(FQ_SPLIT, ntiles), dim3(1024), 0, st, B, cap,
+                       front_t, front_len, qcap, q_inst, q_T0, q_count);
+    return hipGetLastError();
+}
+
 // ---- latency of a network merged at a given set ---------------------------------
 // One wave per query; lane x adds the blocks that end at members x, x + 64, ...
 // of the chain 0 -> X -> L.  Latencies are non-negative, so the saturating

@@ -127,6 +127,24 @@ def test_front_bit_exact_on_synthetic_rows(P, cap):
         assert (ft[b, k:] == -9).all()
 
 
+@pytest.mark.parametrize("B,cap,qcap", [(1, 4, 10), (37, 11, 1000), (37, 11, 50), (2500, 7, 20000),
+                                        (1030, 0, 10)])
+def test_front_queries_match_the_oracle(B, cap, qcap):
+    rng = np.random.default_rng(B + cap)
+    ft = rng.integers(0, 1000, (B, max(cap, 1))).astype(np.int32)[:, :cap].copy()
+    fl = rng.integers(0, cap + 5, B).astype(np.int32)
+    qi = torch.full((qcap,), -9, dtype=torch.int32, device=DEV)
+    qt = torch.full((qcap,), -9, dtype=torch.int32, device=DEV)
+    qn = torch.full((1,), -9, dtype=torch.int32, device=DEV)
+    api.dpc_front_queries(torch.from_numpy(ft).to(DEV), torch.from_numpy(fl).to(DEV), qi, qt, qn)
+    torch.cuda.synchronize()
+    ri, rt, n = oracle.front_queries(ft, fl, qcap)
+    assert qn.item() == n
+    k = min(n, qcap)
+    assert list(qi[:k].cpu().numpy()) == list(ri) and list(qt[:k].cpu().numpy()) == list(rt)
+    assert (qi[k:] == -9).all() and (qt[k:] == -9).all()
+
+
 def test_chain_latency_sets_saturation_and_markers():
     rng = np.random.default_rng(77)
     B, L = 4, 40

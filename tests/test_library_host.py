@@ -76,6 +76,8 @@ def test_argument_errors_of_the_widened_entry_points():
     assert lib.dpc_front(1, 4, 8, p, -1, p, p, p, None) == SHAPE
     assert lib.dpc_front(1, 4, 8, None, 4, p, p, p, None) == NULL
     assert lib.dpc_front(1, 4, 8, p, 4, None, p, p, None) == NULL
+    assert lib.dpc_front_queries(1, -1, p, p, 4, p, p, p, None) == SHAPE
+    assert lib.dpc_front_queries(1, 4, p, p, 4, p, p, None, None) == NULL
     assert lib.dpc_chain_latency(1, 4, p, -1, p, p, p, p, None) == SHAPE
     assert lib.dpc_chain_latency(1, 4, p, 0, None, None, None, None, None) == 0
     assert lib.dpc_chain_latency(1, 4, p, 3, p, None, p, p, None) == NULL

@@ -159,6 +159,25 @@ def test_front_equals_nondominated_pairs_of_the_enumeration(seed):
     assert [(int(a), float(b)) for a, b in zip(t, o)] == expect
 
 
+def test_front_queries_hand_case_and_concatenation():
+    ft = np.array([[3, 7, 9, -1], [-1, -1, -1, -1], [0, 1, 2, 3], [5, -1, -1, -1]], np.int32)
+    fl = np.array([3, 0, 6, 1], np.int32)               # instance 2 had 6 points, 4 were stored
+    qi, qt, n = oracle.front_queries(ft, fl, 20)
+    assert n == 8
+    assert list(qi) == [0, 0, 0, 2, 2, 2, 2, 3] and list(qt) == [3, 7, 9, 0, 1, 2, 3, 5]
+    qi, qt, n = oracle.front_queries(ft, fl, 5)
+    assert n == 8 and list(qi) == [0, 0, 0, 2, 2] and list(qt) == [3, 7, 9, 0, 1]
+    rng = np.random.default_rng(3)
+    B, cap = 37, 11
+    ft = rng.integers(0, 1000, (B, cap)).astype(np.int32)
+    fl = rng.integers(0, 16, B).astype(np.int32)
+    qi, qt, n = oracle.front_queries(ft, fl, 1000)
+    keep = np.minimum(fl, cap)
+    assert n == keep.sum()
+    assert list(qi) == list(np.repeat(np.arange(B), keep))
+    assert list(qt) == list(np.concatenate([ft[b, :keep[b]] for b in range(B)]))
+
+
 # ---------------- latency of a network merged at a given set ----------------
 
 def test_chain_latency_hand_cases():
