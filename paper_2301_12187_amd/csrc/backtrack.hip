@@ -69,18 +69,30 @@ __global__ __launch_bounds__(64 * BT_WAVES) void backtrack_kernel(
         if (Kb) {
             i = uniform((int)Kb[(size_t)j * P + t]);
         } else {
-            // no stored pointer: the lowest i whose candidate equals the stored cell
+            // no stored pointer: the lowest i whose candidate equals the stored cell.
+            // All predecessors are tested at once (j <= 255: four per lane), the
+            // loads of a step issued together: latencies, then cells and importances.
             const float want = Mb[(size_t)j * P + t];
+            int32_t wv[BT_U];
+            float mv[BT_U], iv[BT_U];
+#pragma unroll
+            for (int u = 0; u < BT_U; ++u) {
+                const int ic = lane + 64 * u;
+                wv[u] = ic < j ? To[ic * ld + j] : DPC_INF;
+            }
+#pragma unroll
+            for (int u = 0; u < BT_U; ++u) {
+                const int ic = lane + 64 * u;
+                const bool ok = ic < j && wv[u] <= t;
+                mv[u] = ok ? Mb[(size_t)ic * P + (t - wv[u])] : -INFINITY;
+                iv[u] = ok ? Ib[ic * ld + j] : -INFINITY;
+            }
             i = DPC_NOARG;                  // unreachable for a table produced by stage 2
-            for (int i0 = 0; i0 < j && i == DPC_NOARG; i0 += 64) {
-                const int ic = i0 + lane;
-                bool hit = false;
-                if (ic < j) {
-                    const int32_t w = To[ic * ld + j];
-                    if (w <= t) hit = Mb[(size_t)ic * P + (t - w)] + Ib[ic * ld + j] == want;
-                }
+#pragma unroll
+            for (int u = BT_U - 1; u >= 0; --u) {
+                const bool hit = lane + 64 * u < j && wv[u] <= t && mv[u] + iv[u] == want;
                 const unsigned long long mask = __ballot(hit);
-                if (mask != 0) i = i0 + __builtin_ctzll(mask);
+                if (mask != 0) i = 64 * u + __builtin_ctzll(mask);
             }
         }
         if (i >= j) break;                  // defensive: never true for stage-2 output
