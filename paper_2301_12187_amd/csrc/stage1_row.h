@@ -54,9 +54,10 @@ __device__ __forceinline__ void stage1_row(int L, const int32_t* __restrict__ Tb
             for (int u = 0; u < S1_U; ++u) {
                 const int l = lane + 64 * u;
                 if (l > m && l <= L) {
-                    // both terms are <= DPC_INF = 2^30 - 1: the sum fits int32
-                    int32_t c = tm + tv[a][u];
-                    c = c > DPC_INF ? DPC_INF : c;
+                    // Both terms are <= DPC_INF = 2^30 - 1: the sum fits int32.  It
+                    // needs no clamp to DPC_INF: the minimum starts there, so a sum
+                    // at or beyond it never replaces anything.
+                    const int32_t c = tm + tv[a][u];
                     if (c < cur[u]) { cur[u] = c; arg[u] = m; }
                 }
             }
