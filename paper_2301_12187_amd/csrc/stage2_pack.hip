@@ -88,10 +88,23 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     if (s2_gate_closed(gate)) return;
     constexpr int H = R / S2_H;            // records per (group, predecessor)
     __shared__ int wd[R][R];
-    __shared__ int smax[256], smin[256];
+    // dynamic LDS, sized by the launch for nt = blockDim.x threads: the columns of
+    // Topt and I that the group reads, nt rows of R + 1 words each, then the
+    // window bounds of every predecessor
+#ifndef DPC_HOST_EMU
+    extern __shared__ __attribute__((aligned(16))) char pack_lds[];
+#else
+    char* const pack_lds = emu::g_dyn_lds;
+#endif
+    const int nt = (int)blockDim.x;
+    int32_t (*sT)[R + 1] = (int32_t (*)[R + 1])pack_lds;
+    float (*sI)[R + 1] = (float (*)[R + 1])(pack_lds + (size_t)nt * (R + 1) * 4);
+    int* const smax = (int*)(pack_lds + (size_t)nt * (R + 1) * 8);
+    int* const smin = smax + nt;
     __shared__ int spread;                 // largest spread of a predecessor's shifts into the group
+    __shared__ int row_by_row;             // the group does not fit a whole-group task
     const int ld = L + 1;
-    const int i = threadIdx.x;             // L <= 255: one thread per predecessor
+    const int i = threadIdx.x;             // one thread per predecessor (L + 1 of them, whole waves)
     const int q = blockIdx.x;
     const int b = blockIdx.y;
     const int j0 = s2_group_first_row(L, R, q);
@@ -103,22 +116,33 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     if (q == 0) {
         // the base case of the recurrence: M[0][t] = +0 for every budget, no arg-max
         float* M0 = M + (size_t)b * ld * P;
-        for (int t = i; t < P; t += 256) M0[t] = 0.0f;
+        for (int t = i; t < P; t += nt) M0[t] = 0.0f;
         if (K) {
             uint8_t* K0 = K + (size_t)b * ld * P;
-            for (int t = i; t < P; t += 256) K0[t] = (uint8_t)DPC_NOARG;
+            for (int t = i; t < P; t += nt) K0[t] = (uint8_t)DPC_NOARG;
         }
     }
     // the R columns j0 .. j0+R-1 of Topt and I, staged through LDS so that the
     // loads run along the rows (R consecutive words per row)
-    __shared__ int32_t sT[256][R + 1];
-    __shared__ float sI[256][R + 1];
-    for (int x = i; x < ld * R; x += 256) {
+    // (nt >= L + 1, so R passes cover the L + 1 rows; the loads of all passes are
+    //  issued before the first is used)
+    int32_t tv[R];
+    float iv[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int x = i + k * nt;
         const int row = x / R, rr = x - row * R;
-        const int j = j0 + rr;
-        if (rr < hq) {
-            sT[row][rr] = To[row * ld + j];
-            sI[row][rr] = Ib[row * ld + j];
+        const bool ok = row < ld && rr < hq;
+        tv[k] = ok ? To[row * ld + j0 + rr] : 0;
+        iv[k] = ok ? Ib[row * ld + j0 + rr] : 0.0f;
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int x = i + k * nt;
+        const int row = x / R, rr = x - row * R;
+        if (row < ld && rr < hq) {
+            sT[row][rr] = tv[k];
+            sI[row][rr] = iv[k];
         }
     }
     __syncthreads();
@@ -163,18 +187,18 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
 #pragma unroll
     for (int h = 0; h < H; ++h) {
         rec[h].pad[0] = (uint32_t)smax[i];
-        rec[h].pad[1] = i + ahead_q < 256 ? (uint32_t)smax[i + ahead_q] : 0u;
-        rec[h].pad[2] = i + ahead_q < 256 ? (uint32_t)smin[i + ahead_q] : 0u;
+        rec[h].pad[1] = i + ahead_q < ld ? (uint32_t)smax[i + ahead_q] : 0u;
+        rec[h].pad[2] = i + ahead_q < ld ? (uint32_t)smin[i + ahead_q] : 0u;
         rec[h].pad[3] = (uint32_t)i;
     }
-    if (i < ld) {
-        const size_t idx = ((size_t)b * NQ + q) * ld + i;
+    // (rows above the group offer it nothing and their records are never read)
+    const bool mine = i < ld && i < j0 + R;
+    const size_t idx = ((size_t)b * NQ + q) * ld + i;
+    if (mine) {
 #pragma unroll
         for (int h = 0; h < H; ++h) recs[idx * H + h] = rec[h];
         infos[idx].mins = mins;
         infos[idx].maxs = maxs;
-#pragma unroll
-        for (int rr = 0; rr < R; ++rr) shifts[idx * H + rr / S2_H].w[rr % S2_H] = wv[rr];
     }
     if (i >= j0 && i < j0 + R) {             // (slots past the group's rows offer nothing)
 #pragma unroll
@@ -185,8 +209,10 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
         // how far to the left of its stored columns each row must be correct
         int need[R];
         int g = 0, hmax = 0;
+#pragma unroll
         for (int rr = R - 1; rr >= 0; --rr) {
             int n = 0;
+#pragma unroll
             for (int r2 = rr + 1; r2 < R; ++r2)
                 if (wd[rr][r2] >= 0) {
                     n = max(n, wd[rr][r2] + need[r2]);
@@ -198,6 +224,13 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
         // a table that fits one task has no strip to its left: no ghost columns
         const bool bad = spread > dspread || hmax > dpad || (P > wcap && g > gmax);
         groups[(size_t)b * NQ + q] = bad ? -1 : s2_group_code(g, spread);
+        row_by_row = bad ? 1 : 0;
+    }
+    __syncthreads();
+    // the shifts themselves are read by the row-by-row path only
+    if (row_by_row && mine) {
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) shifts[idx * H + rr / S2_H].w[rr % S2_H] = wv[rr];
     }
 }
 
@@ -354,11 +387,14 @@ hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt
     S2Info* infos = (S2Info*)(base + lay.info_off);
     S2Shift* shifts = (S2Shift*)(base + lay.shift_off);
     int32_t* groups = (int32_t*)(base + lay.group_off);
+    // one thread per predecessor, whole waves; LDS as laid out in the kernel
+    const int nt = (L + 1 + 63) / 64 * 64;
+    const size_t pack_lds = (size_t)nt * ((size_t)(R + 1) * 8 + 8);
     if (R == 8)
-        hipLaunchKernelGGL(stage2_pack_kernel<8>, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I,
+        hipLaunchKernelGGL(stage2_pack_kernel<8>, dim3(NQ, B), dim3(nt), pack_lds, st, L, P, NQ, Topt, I,
                            recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate);
     else
-        hipLaunchKernelGGL(stage2_pack_kernel<16>, dim3(NQ, B), dim3(256), 0, st, L, P, NQ, Topt, I,
+        hipLaunchKernelGGL(stage2_pack_kernel<16>, dim3(NQ, B), dim3(nt), pack_lds, st, L, P, NQ, Topt, I,
                            recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
