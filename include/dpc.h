@@ -101,8 +101,8 @@ int dpc_stage1_minplus(int32_t B, int32_t L, const int32_t *T, int32_t *Topt,
  *   workspace   device scratch of at least dpc_stage2_workspace_bytes(B, L, P)
  *               bytes, 256-byte aligned, private to this call until the work
  *               queued by it has finished; contents on entry are irrelevant
- *               (the call clears what it needs with a kernel of its own, so it
- *               can be recorded into a HIP graph)
+ *               (the call's own kernels clear what they need, so it can be
+ *               recorded into a HIP graph)
  */
 size_t dpc_stage2_workspace_bytes(int32_t B, int32_t L, int32_t P);
 

@@ -36,15 +36,6 @@ __global__ void stage2_clear_kernel(uint32_t* w, int n)
     if (i < n) w[i] = 0;
 }
 
-// the same for a gated preparation: nothing unless the gate is open, and the
-// word the gate reads is left alone
-__global__ void stage2_clear_gated_kernel(uint32_t* w, int n, S2Gate gate, int keep)
-{
-    if (s2_gate_closed(gate)) return;
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n && i != keep) w[i] = 0;
-}
-
 // Sets the choice word: 1 if more than 2 % of the groups run row by row (a
 // group of 16 rows that does costs about eight times a whole one, groups of 8
 // rows about a tenth more overall), else 0.
@@ -83,10 +74,21 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     int L, int P, int NQ, const int32_t* __restrict__ Topt, const float* __restrict__ I,
     S2Rec* __restrict__ recs, S2Info* __restrict__ infos, S2Shift* __restrict__ shifts,
     int32_t* __restrict__ groups, int gmax, int dspread, int dpad, int wcap, int ahead,
-    float* __restrict__ M, uint8_t* __restrict__ K, S2Gate gate)
+    float* __restrict__ M, uint8_t* __restrict__ K, S2Gate gate, uint32_t* __restrict__ hdr_words,
+    uint32_t* __restrict__ done, int keep_word)
 {
     if (s2_gate_closed(gate)) return;
     constexpr int H = R / S2_H;            // records per (group, predecessor)
+    // What the main kernel expects to find zero: the completion counters of the
+    // R levels of this (group, instance), and, from the first workgroup, the
+    // header (ticket, error; the layout kernel fills in the rest afterwards).
+    // keep_word >= 0: a header word that is left alone (the choice a gated
+    // preparation was made conditional on).
+    if (threadIdx.x < R)
+        done[((size_t)blockIdx.x * R + threadIdx.x) * gridDim.y + blockIdx.y] = 0;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < sizeof(S2Header) / 4 &&
+        (int)threadIdx.x != keep_word)
+        hdr_words[threadIdx.x] = 0;
     __shared__ int wd[R][R];
     // dynamic LDS, sized by the launch for nt = blockDim.x threads: the columns of
     // Topt and I that the group reads, nt rows of R + 1 words each, then the
@@ -369,34 +371,27 @@ hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt
     const int NQ = (L + R - 1) / R;
     const S2Layout lay = s2_layout(B, L, P, R);
     if (lay.nentries > 0x3FFFFFF0LL || lay.maxtasks > 0x3FFFFFF0LL) return hipErrorInvalidValue;
-    const int N = (int)lay.nentries;
     char* base = (char*)workspace;
     S2Header* hdr = (S2Header*)base;
     const S2Gate gate{gated ? &hdr->choice : nullptr, want};
-    const int nwords = (int)(sizeof(S2Header) / 4) + N;
-    if (gated)
-        hipLaunchKernelGGL(stage2_clear_gated_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st,
-                           (uint32_t*)workspace, nwords, gate,
-                           (int)(offsetof(S2Header, choice) / 4));
-    else
-        hipLaunchKernelGGL(stage2_clear_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st,
-                           (uint32_t*)workspace, nwords);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     S2Rec* recs = (S2Rec*)(base + lay.rec_off);
     S2Info* infos = (S2Info*)(base + lay.info_off);
     S2Shift* shifts = (S2Shift*)(base + lay.shift_off);
     int32_t* groups = (int32_t*)(base + lay.group_off);
+    uint32_t* done = (uint32_t*)(base + lay.done_off);
+    const int keep_word = gated ? (int)(offsetof(S2Header, choice) / 4) : -1;
     // one thread per predecessor, whole waves; LDS as laid out in the kernel
     const int nt = (L + 1 + 63) / 64 * 64;
     const size_t pack_lds = (size_t)nt * ((size_t)(R + 1) * 8 + 8);
     if (R == 8)
         hipLaunchKernelGGL(stage2_pack_kernel<8>, dim3(NQ, B), dim3(nt), pack_lds, st, L, P, NQ, Topt, I,
-                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate);
+                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate,
+                           (uint32_t*)hdr, done, keep_word);
     else
         hipLaunchKernelGGL(stage2_pack_kernel<16>, dim3(NQ, B), dim3(nt), pack_lds, st, L, P, NQ, Topt, I,
-                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate);
-    e = hipGetLastError();
+                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate,
+                           (uint32_t*)hdr, done, keep_word);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     S2Gate layout_gate = gate;
     if (decide) {
