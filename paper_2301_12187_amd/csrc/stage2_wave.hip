@@ -101,13 +101,25 @@ __device__ __forceinline__ void relax_cell(float& best, uint32_t& argp, float ca
     else DPC_RELAX_CELL(3);
 }
 #undef DPC_RELAX_CELL
+// the larger of two candidates (never -0, never NaN: the bits of whichever is larger)
+__device__ __forceinline__ float max_cand(float a, float b)
+{
+#ifndef DPC_HOST_EMU
+    float m;
+    asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(a), "v"(b));
+    return m;
+#else
+    return b > a ? b : a;
+#endif
+}
 
 template <int R, int NW, int NSLOT, int DMAX, int WPE, bool STORE_K>
 __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* done,
     const S2Entry* __restrict__ entries, const S2Task* __restrict__ tasks,
     const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos,
-    const S2Shift* __restrict__ shifts, int NQ, long long wait_limit, S2Gate gate)
+    const S2Shift* __restrict__ shifts, int NQ, long long wait_limit, S2Gate gate,
+    const int32_t* __restrict__ Topt, const float* __restrict__ I)
 {
     if (s2_gate_closed(gate)) return;                // (another shape was chosen for this call)
     constexpr int U = 4;                             // columns per lane: one arg-max byte each
@@ -124,6 +136,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     constexpr int DSLOTW = WCAP + DMAX + 4;          // floats per diagonal slot
     constexpr int LDSF = NW * RINGF > 2 * DSLOTW ? NW * RINGF : 2 * DSLOTW;
     constexpr float NINF = -INFINITY;
+    // Two predecessors per step (relax_pair_half) where tasks are long, with a
+    // table of the pairs' operands behind the diagonal slots (resolve_pairs).
+    constexpr int PAIR_TAB = 128 * R;                // entries: pairs below the group x rows
+    constexpr bool PAIRS = STORE_K && R == 16 && (LDSF - 2 * DSLOTW) * 4 >= PAIR_TAB * 8;
     static_assert(R == 8 || R == 16, "one or two records per predecessor");
     static_assert(NSLOT * 512 == S2W_RING, "five slots of the smallest window fill the ring");
     static_assert(WV == 256, "the window sizes in stage2_common.h are for 256 columns per wave");
@@ -374,6 +390,89 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
             }
         };
+        // Two predecessors at once (rows a and a + 1, windows at baseA and baseB):
+        // the larger of their two candidates is offered to the cell, and the byte
+        // that is recorded is the number of the pair (a / 2).  Which of the two it
+        // was is settled once per cell after the last predecessor (resolve_pairs):
+        // 6 instead of 8 vector instructions per two candidates.
+        auto relax_pair_half = [&](auto hh, const char* baseA, const char* baseB, const S2Rec& ra,
+                                   const S2Rec& rb, uint32_t vc) __attribute__((always_inline)) {
+            constexpr int h = decltype(hh)::value;
+            float acur[U], anxt[U], bcur[U], bnxt[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                acur[u] = *(const float*)(baseA + rec_off4(ra, 0) + 256 * u);
+                bcur[u] = *(const float*)(baseB + rec_off4(rb, 0) + 256 * u);
+            }
+#pragma unroll
+            for (int r8 = 0; r8 < S2_H; ++r8) {
+                if (r8 + 1 < S2_H) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        anxt[u] = *(const float*)(baseA + rec_off4(ra, r8 + 1) + 256 * u);
+                        bnxt[u] = *(const float*)(baseB + rec_off4(rb, r8 + 1) + 256 * u);
+                    }
+                }
+                const float ia = ra.imp[r8], ib = rb.imp[r8];
+                float cand[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) cand[u] = max_cand(acur[u] + ia, bcur[u] + ib);
+                relax_cell<0, true>(best[h * S2_H + r8][0], argp[h * S2_H + r8], cand[0], vc);
+                relax_cell<1, true>(best[h * S2_H + r8][1], argp[h * S2_H + r8], cand[1], vc);
+                relax_cell<2, true>(best[h * S2_H + r8][2], argp[h * S2_H + r8], cand[2], vc);
+                relax_cell<3, true>(best[h * S2_H + r8][3], argp[h * S2_H + r8], cand[3], vc);
+#pragma unroll
+                for (int u = 0; u < U; ++u) { acur[u] = anxt[u]; bcur[u] = bnxt[u]; }
+            }
+        };
+        // After the last predecessor below the group every arg-max byte holds a
+        // pair number c (or DPC_NOARG).  The arg-max is 2c if that row's candidate
+        // reproduces the cell bit for bit (the lower index wins a tie), else 2c + 1.
+        // A pair whose second row is not below the group holds its first row alone.
+        // tab[c * R + rr] = (Topt, I)[2c][j0 + rr], filled by the workgroup.  Eight
+        // rows at a time in three passes, so that the loads of a pass are in flight
+        // together: latencies from the table, cells of M, then the comparison.
+        struct PairOp { int32_t w; float imp; };
+        auto resolve_pairs = [&](const PairOp* tab) __attribute__((always_inline)) {
+            // (uniform base plus an unsigned 32-bit byte offset per lane: a pair task
+            //  has a table of M smaller than 4 GB)
+            const char* Mc = (const char*)Mb;
+            constexpr int RB = 2;
+#pragma unroll
+            for (int r0 = 0; r0 < R; r0 += RB) {
+                if (r0 >= hq) break;                   // (row slots past the group's rows hold nothing)
+                float mv[RB][U];
+#pragma unroll
+                for (int p = 0; p < RB; ++p) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const uint32_t c = (argp[r0 + p] >> (8 * u)) & 0xFFu;
+                        const bool has = c != (uint32_t)DPC_NOARG;
+                        const int w = tab[(has ? (int)c : 0) * R + r0 + p].w;
+                        const int tc = min(tS + tl0 + 64 * u, P - 1);   // (cells past the table are never stored)
+                        const bool valid = has && w <= tc;
+                        const unsigned cell = (has ? 2u * c : 0u) * (unsigned)P + (unsigned)(tc - w);
+                        mv[p][u] = valid ? ld_agent((const float*)(Mc + cell * 4u)) : NINF;
+                    }
+                }
+#pragma unroll
+                for (int p = 0; p < RB; ++p) {
+                    uint32_t ids = argp[r0 + p];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const uint32_t c = (argp[r0 + p] >> (8 * u)) & 0xFFu;
+                        if (c != (uint32_t)DPC_NOARG) {
+                            // (a candidate that does not exist gives -inf, never a kept maximum)
+                            const float imp = tab[(int)c * R + r0 + p].imp;
+                            const bool first = mv[p][u] + imp == best[r0 + p][u];
+                            const uint32_t id = first ? 2u * c : 2u * c + 1u;
+                            ids = (ids & ~(0xFFu << (8 * u))) | (id << (8 * u));
+                        }
+                    }
+                    argp[r0 + p] = ids;
+                }
+            }
+        };
         // The same for a one-row task: only row `sub` of the group, at one shift.
         auto relax_one = [&](int i, int slot) __attribute__((always_inline)) {   // (smallest window: 512 floats per slot)
             int w;
@@ -416,6 +515,9 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             }
         };
 
+        // whole group, smallest windows, table of M below 4 GB: two predecessors per step
+        const bool pair_task = PAIRS && full && s2_window_loads(spread) <= 2 &&
+                               (long long)ld * P < (1LL << 30);
         // ---------------- off-diagonal part: rows i < ilimit ----------------
         TMARK(t_b);
         TACC(3, t_a, t_b);
@@ -437,6 +539,76 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 }
             int slot = 0;                              // ring slot of row i
             int ahead = D;                             // ring slot of row i + D
+            if constexpr (PAIRS && NLD == 2) {
+              if (pair_task) {
+                // Two predecessor rows per step.  Row r sits in ring slot r mod 5;
+                // while rows a and a + 1 are relaxed the copies of a + 2, a + 3 and
+                // a + 4 are in flight.  The window of row r + 4 is in the record of
+                // row r (the pack kernel looks 4 rows ahead for these groups).
+                static_assert(NSL == 5 && D == 4, "pairs need five slots");
+                S2Rec A[H], Bn[H];
+#pragma unroll
+                for (int h = 0; h < H; ++h) {
+                    A[h] = brec[h];
+                    Bn[h] = brec[min(1, L) * H + h];
+                }
+                int sa = 0;                            // ring slot of row a
+                int pw_max = 0, pw_min = 0;            // window of row a + 3
+                int a = 0;
+                for (; a + 1 < ilimit; a += 2) {
+                    const int s3 = sa + 3 >= NSL ? sa + 3 - NSL : sa + 3;
+                    const int s4 = sa + 4 >= NSL ? sa + 4 - NSL : sa + 4;
+                    if (a >= 2 && a + 3 < ilimit) {
+                        if (a + 3 == prev_row0) wait_prev();
+                        issue_row(nld_c, a + 3, s3, pw_max, pw_min);
+                    }
+                    if (a + 4 < ilimit) {
+                        if (a + 4 == prev_row0) wait_prev();
+                        issue_row(nld_c, a + 4, s4, (int)A[0].pad[1], (int)A[0].pad[2]);
+                    }
+                    // rows up to min(ilimit, a + 5) - 1 have been issued; a and a + 1 must have landed
+                    wait_vm((min(ilimit, a + 5) - (a + 2)) * NLD);
+                    asm volatile("" ::: "memory");
+                    pw_max = (int)Bn[0].pad[1];
+                    pw_min = (int)Bn[0].pad[2];
+                    const int sb = sa + 1 >= NSL ? 0 : sa + 1;
+                    const int dA = (tS - (int)A[0].pad[0]) & 3;
+                    const int dB = (tS - (int)Bn[0].pad[0]) & 3;
+                    const char* baseA = lbase + (sa * SLOTF + dA) * 4;
+                    const char* baseB = lbase + (sb * SLOTF + dB) * 4;
+                    const uint32_t vc = (uint32_t)a >> 1;
+                    const int na = min(a + 2, L) * H, nb = min(a + 3, L) * H;
+                    if constexpr (H == 1) {
+                        const S2Rec nA = brec[na], nB = brec[nb];
+                        relax_pair_half(std::integral_constant<int, 0>{}, baseA, baseB, A[0], Bn[0], vc);
+                        A[0] = nA;
+                        Bn[0] = nB;
+                    } else {
+                        relax_pair_half(std::integral_constant<int, 0>{}, baseA, baseB, A[0], Bn[0], vc);
+                        const S2Rec nA0 = brec[na], nB0 = brec[nb];
+                        relax_pair_half(std::integral_constant<int, 1>{}, baseA, baseB, A[H - 1],
+                                        Bn[H - 1], vc);
+                        A[H - 1] = brec[na + H - 1];
+                        Bn[H - 1] = brec[nb + H - 1];
+                        A[0] = nA0;
+                        Bn[0] = nB0;
+                    }
+                    sa = sa + 2 >= NSL ? sa + 2 - NSL : sa + 2;
+                }
+                if (a < ilimit) {
+                    // an odd number of rows: the last one is a pair of its own
+                    wait_vm(0);
+                    asm volatile("" ::: "memory");
+                    const int dA = (tS - (int)A[0].pad[0]) & 3;
+                    const char* base = lbase + (sa * SLOTF + dA) * 4;
+                    const uint32_t vc = (uint32_t)a >> 1;
+                    relax_half(std::integral_constant<int, 0>{}, base, A[0], vc);
+                    if constexpr (H == 2)
+                        relax_half(std::integral_constant<int, 1>{}, base, A[H - 1], vc);
+                }
+                return;
+              }
+            }
             if (full) {
                 S2Rec cur[H];
 #pragma unroll
@@ -516,6 +688,30 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             __syncthreads();                           // every ring is idle: the slots below lie over them
             TMARK(t_c2);
             TACC(1, t_c, t_c2);
+            if constexpr (PAIRS) {
+                if (pair_task) {
+                    // operands of the even rows below the group, behind the two slots
+                    PairOp* tab = (PairOp*)(lds + 2 * DSLOTW);
+                    const int32_t* To = Topt + (size_t)b * ld * ld;
+                    const float* Ib = I + (size_t)b * ld * ld;
+                    const int nent = ((j0 + 1) >> 1) * R;          // pairs (2c, 2c + 1) with 2c < j0
+                    constexpr int TRIPS = (PAIR_TAB + NT - 1) / NT;
+                    PairOp o[TRIPS];
+#pragma unroll
+                    for (int k = 0; k < TRIPS; ++k) {
+                        const int en = min(tid + k * NT, nent - 1);
+                        const int c = en / R, rr = en - c * R;
+                        const int x = 2 * c * ld + min(j0 + rr, L);
+                        o[k].w = To[x];
+                        o[k].imp = Ib[x];
+                    }
+#pragma unroll
+                    for (int k = 0; k < TRIPS; ++k)
+                        if (tid + k * NT < nent) tab[tid + k * NT] = o[k];
+                    __syncthreads();
+                    if (!wave_idle) resolve_pairs(tab);
+                }
+            }
             if (tS == 0) {
                 // first strip: what lies to the left of column 0 does not exist
                 for (int x = tid; x < 2 * DMAX; x += NT) {
@@ -618,11 +814,11 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
     if (K)
         hipLaunchKernelGGL((stage2_wave_kernel<R, NW, NSLOT, DMAX, WPE, true>), dim3(grid),
                            dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
-                           infos, shifts, NQ, wait_limit, gate);
+                           infos, shifts, NQ, wait_limit, gate, Topt, I);
     else
         hipLaunchKernelGGL((stage2_wave_kernel<R, NW, NSLOT, DMAX, WPE, false>), dim3(grid),
                            dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
-                           infos, shifts, NQ, wait_limit, gate);
+                           infos, shifts, NQ, wait_limit, gate, Topt, I);
     return hipGetLastError();
 }
 
