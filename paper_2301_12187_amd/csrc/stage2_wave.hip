@@ -429,47 +429,46 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         // pair number c (or DPC_NOARG).  The arg-max is 2c if that row's candidate
         // reproduces the cell bit for bit (the lower index wins a tie), else 2c + 1.
         // A pair whose second row is not below the group holds its first row alone.
-        // tab[c * R + rr] = (Topt, I)[2c][j0 + rr], filled by the workgroup.  Eight
-        // rows at a time in three passes, so that the loads of a pass are in flight
-        // together: latencies from the table, cells of M, then the comparison.
-        struct PairOp { int32_t w; float imp; };
-        auto resolve_pairs = [&](const PairOp* tab) __attribute__((always_inline)) {
+        // tab[c * R + rr] = (4 Topt, I)[2c][j0 + rr], filled by the workgroup (no
+        // candidate: a latency no budget reaches).  Two rows at a time in two
+        // passes, so that the loads of a pass are in flight together.  A cell whose
+        // even candidate does not exist gets +inf to compare with, which equals no
+        // maximum.
+        struct PairOp { int32_t w4; float imp; };
+        auto resolve_pairs = [&](const PairOp* tab, int npairs) __attribute__((always_inline)) {
             // (uniform base plus an unsigned 32-bit byte offset per lane: a pair task
-            //  has a table of M smaller than 4 GB)
+            //  has a table of M smaller than 4 GB and fewer than 2^20 budgets)
             const char* Mc = (const char*)Mb;
+            const uint32_t p8 = 8u * (uint32_t)P;
             constexpr int RB = 2;
 #pragma unroll
             for (int r0 = 0; r0 < R; r0 += RB) {
                 if (r0 >= hq) break;                   // (row slots past the group's rows hold nothing)
                 float mv[RB][U];
+                const PairOp* ent[RB][U];
 #pragma unroll
                 for (int p = 0; p < RB; ++p) {
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const uint32_t c = (argp[r0 + p] >> (8 * u)) & 0xFFu;
-                        const bool has = c != (uint32_t)DPC_NOARG;
-                        const int w = tab[(has ? (int)c : 0) * R + r0 + p].w;
-                        const int tc = min(tS + tl0 + 64 * u, P - 1);   // (cells past the table are never stored)
-                        const bool valid = has && w <= tc;
-                        const unsigned cell = (has ? 2u * c : 0u) * (unsigned)P + (unsigned)(tc - w);
-                        mv[p][u] = valid ? ld_agent((const float*)(Mc + cell * 4u)) : NINF;
+                        const uint32_t c = min((argp[r0 + p] >> (8 * u)) & 0xFFu, (uint32_t)npairs - 1u);
+                        ent[p][u] = tab + (c * R + r0 + p);
+                        const int w4 = ent[p][u]->w4;
+                        const int tc4 = 4 * min(tS + tl0 + 64 * u, P - 1);   // (cells past the table are never stored)
+                        const uint32_t off = __umul24(c, p8) + (uint32_t)(tc4 - w4);
+                        mv[p][u] = w4 <= tc4 ? ld_agent((const float*)(Mc + off)) : INFINITY;
                     }
                 }
 #pragma unroll
                 for (int p = 0; p < RB; ++p) {
-                    uint32_t ids = argp[r0 + p];
+                    uint32_t odd = 0;
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const uint32_t c = (argp[r0 + p] >> (8 * u)) & 0xFFu;
-                        if (c != (uint32_t)DPC_NOARG) {
-                            // (a candidate that does not exist gives -inf, never a kept maximum)
-                            const float imp = tab[(int)c * R + r0 + p].imp;
-                            const bool first = mv[p][u] + imp == best[r0 + p][u];
-                            const uint32_t id = first ? 2u * c : 2u * c + 1u;
-                            ids = (ids & ~(0xFFu << (8 * u))) | (id << (8 * u));
-                        }
+                        const bool first = mv[p][u] + ent[p][u]->imp == best[r0 + p][u];
+                        odd |= first ? 0u : 1u << (8 * u);
                     }
-                    argp[r0 + p] = ids;
+                    // (pair numbers are below 128: a byte with its top bit set is DPC_NOARG and stays)
+                    const uint32_t none = ((argp[r0 + p] & 0x80808080u) >> 7) * 0xFFu;
+                    argp[r0 + p] = ((argp[r0 + p] << 1) & 0xFEFEFEFEu) | odd | none;
                 }
             }
         };
@@ -517,7 +516,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
 
         // whole group, smallest windows, table of M below 4 GB: two predecessors per step
         const bool pair_task = PAIRS && full && s2_window_loads(spread) <= 2 &&
-                               (long long)ld * P < (1LL << 30);
+                               (long long)ld * P < (1LL << 30) && P < (1 << 20);
         // ---------------- off-diagonal part: rows i < ilimit ----------------
         TMARK(t_b);
         TACC(3, t_a, t_b);
@@ -702,14 +701,15 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                         const int en = min(tid + k * NT, nent - 1);
                         const int c = en / R, rr = en - c * R;
                         const int x = 2 * c * ld + min(j0 + rr, L);
-                        o[k].w = To[x];
+                        const int w = To[x];
+                        o[k].w4 = w < P ? 4 * w : 0x7FFFFFFF;
                         o[k].imp = Ib[x];
                     }
 #pragma unroll
                     for (int k = 0; k < TRIPS; ++k)
                         if (tid + k * NT < nent) tab[tid + k * NT] = o[k];
                     __syncthreads();
-                    if (!wave_idle) resolve_pairs(tab);
+                    if (!wave_idle) resolve_pairs(tab, (j0 + 1) >> 1);
                 }
             }
             if (tS == 0) {

@@ -126,6 +126,7 @@ inline void __builtin_amdgcn_s_sleep(int) { std::this_thread::yield(); }
 inline void __builtin_amdgcn_s_waitcnt(int) { wave_sync(); }
 inline long long wall_clock64() { return 0; }
 
+inline unsigned __umul24(unsigned a, unsigned b) { return (a & 0xFFFFFFu) * (b & 0xFFFFFFu); }
 inline int min(int a, int b) { return a < b ? a : b; }
 inline int max(int a, int b) { return a > b ? a : b; }
 inline unsigned min(unsigned a, unsigned b) { return a < b ? a : b; }
