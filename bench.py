@@ -37,7 +37,7 @@ VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9        # 39.3e12
 # HBM bytes (read + written) per stage-2 launch from the rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs summarised in profiles/stage2_wave_kernel_cfg5.md, keyed by
 # (config, variant); None where not measured.
-MEASURED_TRAFFIC = {(5, 0): 5.394e9 + 1.181e9}
+MEASURED_TRAFFIC = {(5, 0): 6.06e9 + 1.181e9}
 
 
 def main():
