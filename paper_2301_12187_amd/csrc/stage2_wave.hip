@@ -824,49 +824,54 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
 
 int g_s2w_shape = 0;    // tuning override, see launch_stage2_wave
 
+// groups of 8 rows (shapes 1-4, 9) or 16 rows (5-8): waves per task, ring slots
+// (smallest window), largest shift inside a group, waves per SIMD
+static hipError_t launch_wave_shape(int shape, int B, int L, int P, const int32_t* Topt, const float* I,
+                                    float* M, uint8_t* K, void* workspace, int num_cu, hipStream_t st,
+                                    bool gated, uint32_t want, bool decide)
+{
+    switch (shape) {
+        case 1: return launch_wave_cfg<8, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 2: return launch_wave_cfg<8, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 3: return launch_wave_cfg<8, 2, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 4: return launch_wave_cfg<8, 1, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 5: return launch_wave_cfg<16, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 6: return launch_wave_cfg<16, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 7: return launch_wave_cfg<16, 2, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 8: return launch_wave_cfg<16, 16, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 9: return launch_wave_cfg<8, 16, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                               uint8_t* K, void* workspace, int num_cu, hipStream_t st)
 {
     // a window cell may read up to three floats past the end of a row
     if (P < 16) return hipErrorInvalidValue;
+    if (g_s2w_shape != 0)
+        return launch_wave_shape(g_s2w_shape, B, L, P, Topt, I, M, K, workspace, num_cu, st, false, 0u, false);
     // Task shape.  The narrowest task that covers a narrow table; wide tables
     // take 1024 or 2048 columns per task.  Groups of 16 rows halve the number
     // of times every row of M is read back, which is what bounds long, wide
-    // tables; short or narrow ones are faster with 8 rows (less recomputation
-    // at strip edges, windows that fit more often).  Measured on the L=53,
-    // L=100 and L=200 workloads.
-    int shape = g_s2w_shape;
-    if (shape == 0) {
-        if (P <= 256) shape = 4;
-        else if (P <= 512) shape = 3;
-        else if (P <= 1536) shape = 1;
-        else shape = (L >= 128 && P >= 8192) ? 5 : 2;
-    }
-    if (g_s2w_shape == 0 && shape == 5) {
-        // Groups of 16 rows need the shifts of 16 consecutive layers to fit a
-        // window and a ghost region; whether they do is only known on the
-        // device.  Prepare them, let the device decide, and queue the 8-row
-        // shape behind it: of the two main kernels one returns at once.
-        hipError_t e = launch_wave_cfg<16, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st,
-                                                         false, 0u, true);
-        if (e != hipSuccess) return e;
-        return launch_wave_cfg<8, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, true,
-                                                1u, false);
-    }
-    switch (shape) {
-        // groups of 8 rows: waves per task, ring slots (smallest window), largest shift inside a group, waves per SIMD
-        case 1: return launch_wave_cfg<8, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 2: return launch_wave_cfg<8, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 3: return launch_wave_cfg<8, 2, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 4: return launch_wave_cfg<8, 1, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        // groups of 16 rows
-        case 5: return launch_wave_cfg<16, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 6: return launch_wave_cfg<16, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 7: return launch_wave_cfg<16, 2, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 8: return launch_wave_cfg<16, 16, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        case 9: return launch_wave_cfg<8, 16, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st);
-        default: return hipErrorInvalidValue;
-    }
+    // tables, and they take two predecessors per step, which pays once a chain
+    // has some length; a table of 2049 to 4096 budgets is then one 16-wave task
+    // per group, with no strip edges at all.  Measured on the L=53, L=100 and
+    // L=200 workloads and on the 109-layer chains of the extended solver.
+    const int narrow = P <= 256 ? 4 : P <= 512 ? 3 : P <= 1536 ? 1 : 2;
+    int wide = 0;
+    if (L >= 128 && P >= 8192) wide = 5;
+    else if (L >= 64 && P > 2048 && P <= 4096) wide = 8;
+    else if (L >= 64 && P > 512 && P <= 1536) wide = 5;
+    if (wide == 0)
+        return launch_wave_shape(narrow, B, L, P, Topt, I, M, K, workspace, num_cu, st, false, 0u, false);
+    // Groups of 16 rows need the shifts of 16 consecutive layers to fit a window
+    // and a ghost region; whether they do is only known on the device.  Prepare
+    // them, let the device decide, and queue the 8-row shape behind it: of the
+    // two main kernels one returns at once.
+    hipError_t e = launch_wave_shape(wide, B, L, P, Topt, I, M, K, workspace, num_cu, st, false, 0u, true);
+    if (e != hipSuccess) return e;
+    return launch_wave_shape(narrow, B, L, P, Topt, I, M, K, workspace, num_cu, st, true, 1u, false);
 }
 
 }  // namespace dpc

@@ -176,7 +176,7 @@ def test_stage1_at_the_chain_lengths_where_the_kernel_changes(L):
         assert (Topt[b].cpu().numpy() == To).all() and (split[b].cpu().numpy() == sp).all(), (L, b)
 
 
-@pytest.mark.parametrize("variant", [0, 31, 32, 35, 36])
+@pytest.mark.parametrize("variant", [0, 31, 32, 35, 36, 38])
 @pytest.mark.parametrize("scale", [3, 8, 20])
 def test_large_latencies_wide_windows(variant, scale):
     """Latencies that add up along the chain and are large against a ring slot:
@@ -227,7 +227,7 @@ def test_config3_batch(variant):
     compare(g, r, cfg.L, cfg.name)
 
 
-@pytest.mark.parametrize("variant", VARIANTS + [24, 26, 31, 32, 35])
+@pytest.mark.parametrize("variant", VARIANTS + [24, 26, 31, 32, 35, 38])
 def test_config4_batch(variant):
     cfg = inputs.CONFIGS[4]
     T, I, base = inputs.make_batch(cfg, seed=0)
