@@ -851,18 +851,22 @@ hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const fl
     if (P < 16) return hipErrorInvalidValue;
     if (g_s2w_shape != 0)
         return launch_wave_shape(g_s2w_shape, B, L, P, Topt, I, M, K, workspace, num_cu, st, false, 0u, false);
-    // Task shape.  The narrowest task that covers a narrow table; wide tables
-    // take 1024 or 2048 columns per task.  Groups of 16 rows halve the number
-    // of times every row of M is read back, which is what bounds long, wide
-    // tables, and they take two predecessors per step, which pays once a chain
-    // has some length; a table of 2049 to 4096 budgets is then one 16-wave task
-    // per group, with no strip edges at all.  Measured on the L=53, L=100 and
-    // L=200 workloads and on the 109-layer chains of the extended solver.
+    // Task shape.  Groups of 8 rows: the narrowest task that covers a narrow
+    // table, 2048 columns per task for wide ones.  Chains of 64 layers and more
+    // run in groups of 16 rows where the table is wider than 512 budgets: they
+    // halve the number of times every row of M is read back and take two
+    // predecessors per step.  Their tasks are 1024 columns wide, except where
+    // one task of 8 or 16 waves covers the whole width and there are instances
+    // enough to fill the chip with such tasks (no strip edges at all then).
+    // Measured on the L=53, L=100 and L=200 workloads at 1000 to 16000 budgets
+    // and on the 109-layer chains of the extended solver.
     const int narrow = P <= 256 ? 4 : P <= 512 ? 3 : P <= 1536 ? 1 : 2;
     int wide = 0;
-    if (L >= 128 && P >= 8192) wide = 5;
-    else if (L >= 64 && P > 2048 && P <= 4096) wide = 8;
-    else if (L >= 64 && P > 512 && P <= 1536) wide = 5;
+    if (L >= 64 && P > 512) {
+        if (P > 1536 && P <= 2048 && 2LL * B >= num_cu) wide = 6;
+        else if (P > 2048 && P <= 4096 && B >= num_cu) wide = 8;
+        else wide = 5;
+    }
     if (wide == 0)
         return launch_wave_shape(narrow, B, L, P, Topt, I, M, K, workspace, num_cu, st, false, 0u, false);
     // Groups of 16 rows need the shifts of 16 consecutive layers to fit a window

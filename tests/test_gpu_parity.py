@@ -204,6 +204,24 @@ def test_device_side_choice_between_group_sizes(scale):
     compare(g, run_oracle(T, I, cfg.P, qi, qt, threads=3), cfg.L, f"cfg5 shape, latencies x{scale}")
 
 
+@pytest.mark.parametrize("P,B", [(2000, 128), (3000, 256), (3000, 16), (6000, 24)])
+def test_default_shape_by_width_and_batch(P, B):
+    """The default kernel choice at widths between the named workloads: one
+    task of 8 or of 16 waves per group where the batch fills the chip, strips
+    of 1024 columns otherwise."""
+    import dataclasses
+    cfg = dataclasses.replace(inputs.CONFIGS[4], P=P, B=B)
+    T, I, base = inputs.make_batch(cfg, seed=5)
+    qi, qt = inputs.budgets(cfg, base)
+    g = run_gpu(T, I, cfg.P, qi, qt, variant=0)
+    sample = np.arange(0, cfg.B, max(1, cfg.B // 6))
+    sel = np.isin(qi, sample)
+    r = run_oracle(T[sample], I[sample], cfg.P, np.searchsorted(sample, qi[sel]), qt[sel],
+                   threads=16)
+    gs = {k: (v[sample] if k in ("Topt", "split", "M", "K") else v[sel]) for k, v in g.items()}
+    compare(gs, r, cfg.L, f"L=100 P={P} B={B}")
+
+
 def test_bad_queries_and_empty_query_list():
     cfg = inputs.CONFIGS[1]
     T, I, _ = inputs.make_batch(cfg, seed=0)
