@@ -35,6 +35,16 @@
 // A row that offers no candidate to the group is fetched all the same; its
 // importances are -inf in the records, so it never wins.
 //
+// With groups of 16 rows and back-pointers stored, the rows below the group
+// are taken two at a time: a cell is offered the larger of the two rows'
+// candidates, the byte that is kept is the number of the pair, and which of the
+// two rows it was is settled once per cell when the last row below the group is
+// done, by looking the even row's candidate up again (relax_pair_half,
+// resolve_pairs).  Values and arg-max indices are those of the one-at-a-time
+// update: the maximum of two candidates has the bits of whichever is larger,
+// a strict comparison against the running maximum keeps the first pair that
+// attains it, and inside the pair the lower row wins a tie.
+//
 // The diagonal part (predecessors inside the group) is shared by the waves of
 // the workgroup as in the tiled family: a finished row goes to one of two LDS
 // slots (laid over the rings, which are idle by then) from which the rows
