@@ -114,6 +114,34 @@ def test_denormals_and_signed_zero(variant):
     compare(g, r, L, "denormals / zeros")
 
 
+@pytest.mark.parametrize("variant", [0, 35, 36, 38])
+@pytest.mark.parametrize("L,P,tmax", [(17, 300, 5), (33, 1100, 9), (40, 2500, 30), (70, 600, 3),
+                                      (255, 700, 2)])
+def test_ties_between_the_rows_of_a_pair_of_predecessors(L, P, tmax, variant):
+    """Groups of 16 rows take the rows below them two at a time and settle the
+    arg-max inside a pair afterwards: small integer importances give exact
+    ties inside pairs, between pairs and with the group's own rows; an odd
+    number of rows below a group, excluded blocks, zero latencies, a batch of
+    mixed kinds, denormals and zeros of both signs."""
+    rng = np.random.default_rng(4000 + L)
+    B = 5
+    Ts, Is = [], []
+    for b in range(B):
+        T, I = rand_tables(rng, L, tmax=tmax, inf_frac=0.25 if b % 2 else 0.0,
+                           ikind=("int", "int", "mixed", "neg", "int")[b], tmin=0 if b == 1 else 1)
+        if b == 4:
+            I[np.triu_indices(L + 1, k=1)] = np.float32(-0.0)      # every candidate ties
+            I[0, 1:] = np.float32(0.0)
+        if b == 2:
+            I = (I * np.float32(1e-39)).astype(np.float32)         # denormal sums
+        Ts.append(T)
+        Is.append(I)
+    T, I = np.stack(Ts), np.stack(Is)
+    qi, qt = _all_budgets(B, P, step=max(1, P // 60))
+    g = run_gpu(T, I, P, qi, qt, variant=variant)
+    compare(g, run_oracle(T, I, P, qi, qt), L, f"pairs L={L} P={P} variant {variant}")
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_without_stored_backpointers(variant):
     cfg = inputs.CONFIGS[2]

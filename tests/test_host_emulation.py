@@ -84,6 +84,16 @@ def test_row_by_row_groups_and_missing_candidates(emu, tmp_path, shape):
     _run(emu, tmp_path, np.stack(Ts), np.stack(Is), P, shape)
 
 
+@pytest.mark.parametrize("L,P", [(70, 260), (255, 40)])
+def test_pairs_of_predecessors_long_chain(emu, tmp_path, L, P):
+    """Groups of 16 rows with many rows below them (the five ring slots wrap
+    many times, odd and even counts, the largest table of pair operands), with
+    integer importances: exact ties inside and between pairs."""
+    rng = np.random.default_rng(504 + L)
+    T, I = rand_tables(rng, L, tmax=3, inf_frac=0.2, ikind="int")
+    _run(emu, tmp_path, T[None], I[None], P, 5)
+
+
 def _additive_tables(rng, B, L, lo, hi):
     """Latencies that add up along the chain (block latency about the sum of its
     layers), so that the shifts of one predecessor into a group of rows spread
