@@ -712,7 +712,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                         const int c = en / R, rr = en - c * R;
                         const int x = 2 * c * ld + min(j0 + rr, L);
                         const int w = To[x];
-                        o[k].w4 = w < P ? 4 * w : 0x7FFFFFFF;
+                        o[k].w4 = w >= 0 && w < P ? 4 * w : 0x7FFFFFFF;   // (the pack kernel's rule)
                         o[k].imp = Ib[x];
                     }
 #pragma unroll
