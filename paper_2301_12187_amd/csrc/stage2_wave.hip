@@ -819,7 +819,18 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
     // resident workgroups per compute unit: WPE waves per SIMD, 4 SIMDs
     constexpr int wg_per_cu = (WPE * 4) / NW;
     static_assert(wg_per_cu >= 1, "a workgroup must fit one compute unit");
-    const int grid = num_cu * wg_per_cu;
+    int grid = num_cu * wg_per_cu;
+    // A table that fits one task per row group is B independent chains of
+    // tasks.  Two workgroups per chain are what can work at once (one finishes a
+    // group while the next has started on the rows below it); more only wait,
+    // and once the chip is half full one per chain is faster.  Any number is
+    // safe: a ticket only ever waits for lower tickets.  Measured at L=53,
+    // P=1000: 512 instances 0.42 -> 0.26 ms, 256 instances 0.28 -> 0.22 ms.
+    if (P <= WCAP) {
+        const long long n = B;
+        const long long fit = std::min(2 * n, std::max(n, (long long)grid / 2));
+        if (fit < grid) grid = (int)fit;
+    }
     const long long wait_limit = 500000000LL;      // 5 s of the 100 MHz wall clock
     if (K)
         hipLaunchKernelGGL((stage2_wave_kernel<R, NW, NSLOT, DMAX, WPE, true>), dim3(grid),
