@@ -122,6 +122,16 @@ __device__ __forceinline__ float max_cand(float a, float b)
     return b > a ? b : a;
 #endif
 }
+// the running maximum against two candidates at once
+__device__ __forceinline__ void max_cand2(float& best, float a, float b)
+{
+#ifndef DPC_HOST_EMU
+    asm("v_max3_f32 %0, %0, %1, %2" : "+v"(best) : "v"(a), "v"(b));
+#else
+    best = a > best ? a : best;
+    best = b > best ? b : best;
+#endif
+}
 
 template <int R, int NW, int NSLOT, int DMAX, int WPE, bool STORE_K>
 __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
@@ -149,7 +159,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     // Two predecessors per step (relax_pair_half) where tasks are long, with a
     // table of the pairs' operands behind the diagonal slots (resolve_pairs).
     constexpr int PAIR_TAB = 128 * R;                // entries: pairs below the group x rows
-    constexpr bool PAIRS = STORE_K && R == 16 && (LDSF - 2 * DSLOTW) * 4 >= PAIR_TAB * 8;
+    constexpr bool PAIRS = R == 16 && (!STORE_K || (LDSF - 2 * DSLOTW) * 4 >= PAIR_TAB * 8);
     static_assert(R == 8 || R == 16, "one or two records per predecessor");
     static_assert(NSLOT * 512 == S2W_RING, "five slots of the smallest window fill the ring");
     static_assert(WV == 256, "the window sizes in stage2_common.h are for 256 columns per wave");
@@ -424,13 +434,20 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     }
                 }
                 const float ia = ra.imp[r8], ib = rb.imp[r8];
-                float cand[U];
+                if constexpr (STORE_K) {
+                    float cand[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) cand[u] = max_cand(acur[u] + ia, bcur[u] + ib);
-                relax_cell<0, true>(best[h * S2_H + r8][0], argp[h * S2_H + r8], cand[0], vc);
-                relax_cell<1, true>(best[h * S2_H + r8][1], argp[h * S2_H + r8], cand[1], vc);
-                relax_cell<2, true>(best[h * S2_H + r8][2], argp[h * S2_H + r8], cand[2], vc);
-                relax_cell<3, true>(best[h * S2_H + r8][3], argp[h * S2_H + r8], cand[3], vc);
+                    for (int u = 0; u < U; ++u) cand[u] = max_cand(acur[u] + ia, bcur[u] + ib);
+                    relax_cell<0, true>(best[h * S2_H + r8][0], argp[h * S2_H + r8], cand[0], vc);
+                    relax_cell<1, true>(best[h * S2_H + r8][1], argp[h * S2_H + r8], cand[1], vc);
+                    relax_cell<2, true>(best[h * S2_H + r8][2], argp[h * S2_H + r8], cand[2], vc);
+                    relax_cell<3, true>(best[h * S2_H + r8][3], argp[h * S2_H + r8], cand[3], vc);
+                } else {
+                    // values only: one three-way maximum per two candidates
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        max_cand2(best[h * S2_H + r8][u], acur[u] + ia, bcur[u] + ib);
+                }
 #pragma unroll
                 for (int u = 0; u < U; ++u) { acur[u] = anxt[u]; bcur[u] = bnxt[u]; }
             }
@@ -697,7 +714,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             __syncthreads();                           // every ring is idle: the slots below lie over them
             TMARK(t_c2);
             TACC(1, t_c, t_c2);
-            if constexpr (PAIRS) {
+            if constexpr (PAIRS && STORE_K) {
                 if (pair_task) {
                     // operands of the even rows below the group, behind the two slots
                     PairOp* tab = (PairOp*)(lds + 2 * DSLOTW);
