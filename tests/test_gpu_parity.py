@@ -142,6 +142,19 @@ def test_ties_between_the_rows_of_a_pair_of_predecessors(L, P, tmax, variant):
     compare(g, run_oracle(T, I, P, qi, qt), L, f"pairs L={L} P={P} variant {variant}")
 
 
+def test_table_with_more_budgets_than_the_pair_step_takes():
+    """Beyond 2^20 budgets the 16-row kernel falls back to one predecessor per
+    step (its pair settlement works with 24-bit products): same results."""
+    rng = np.random.default_rng(4100)
+    L, P = 17, (1 << 20) + 37
+    T, I = rand_tables(rng, L, tmax=60000, inf_frac=0.1, ikind="int")
+    T, I = T[None], I[None]
+    qt = np.array([0, 5, 70001, 400000, P - 1], np.int32)
+    qi = np.zeros_like(qt)
+    g = run_gpu(T, I, P, qi, qt, variant=35)
+    compare(g, run_oracle(T, I, P, qi, qt), L, "P > 2^20")
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_without_stored_backpointers(variant):
     cfg = inputs.CONFIGS[2]
