@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the two-stage depth-compression DP on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--variant 0]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--shape 0]
 
 One step = one pass of the whole hot path over one batch of synthetic input
 that is already resident in HBM: dpc_stage1_minplus, dpc_stage2_knapsack,
@@ -19,8 +19,17 @@ target is quoted on.  Prints ONE JSON line.
                (the 157.3 TFLOP/s fp32 vector figure without the FMA and
                packed factors of 2).  Duration from HIP events on the launch
                stream around dpc_stage2_knapsack in every timed step.
-  cpu_baseline the CPU oracle, as it stands, on a bounded sample of instances
-               of the same workload, one instance per host thread.
+               `frac` counts 4 lane-ops per candidate whatever the kernel
+               issues; `variant_floor_ops` / `frac_of_variant_floor` count
+               what the main loop of the kernel shape that ran needs at
+               least, `issued_valu_per_relax` what the counters saw.
+  cpu_baseline the CPU oracle, as it stands, on every instance and query of the
+               same workload, one instance per host thread (`cores` threads
+               of `host_cores`).
+  parity       the GPU buffers of the last timed step against that oracle
+               run, element by element, tolerance 0; a mismatch makes the
+               exit status 1.
+  per_config   (default run only) workloads 1-4 timed and checked the same way.
 """
 import argparse
 import json
@@ -34,10 +43,132 @@ if ROOT not in sys.path:
 
 METRIC = "DP relax-ops/sec (B·L²·P) + batch solve latency ms, 1×MI355X"
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9        # 39.3e12
-# HBM bytes (read + written) per stage-2 launch from the rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs summarised in profiles/stage2_wave_kernel_cfg5.md, keyed by
-# (config, variant); None where not measured.
-MEASURED_TRAFFIC = {(5, 0): 6.06e9 + 1.181e9}
+# Figures that come from the committed rocprofv3 summaries, not from this run
+# (counters cannot be read from inside the process): HBM bytes per stage-2
+# launch (FETCH_SIZE / WRITE_SIZE runs) and VALU instructions issued per
+# candidate (SQ_INSTS_VALU x 64 lanes / exact candidates), keyed by config.
+PROFILED = {
+    5: {"file": "profiles/stage2_wave_kernel_cfg5.md", "traffic_bytes": 6.06e9 + 1.181e9,
+        "issued_valu_per_relax": 3.98},
+}
+
+
+def variant_floor_ops(L, P, store_K):
+    """VALU instructions per candidate that the main loop of the kernel shape the
+    library picks for (L, P) cannot go below: 16-row groups take two predecessor
+    rows per step (2 adds + 1 max + compare + 2 selects per two candidates = 3 with
+    back-pointers, 2 adds + 1 three-way max = 1.5 without); 8-row groups take one
+    (add, compare, 2 selects = 4; add, max = 2)."""
+    pairs = L >= 64 and P > 512
+    if store_K:
+        return 3.0 if pairs else 4.0
+    return 1.5 if pairs else 2.0
+
+
+class Workload:
+    """One named workload resident on the GPU, with its buffers."""
+
+    def __init__(self, cid, seed, store_K, torch, api, inputs):
+        self.cfg = cfg = inputs.CONFIGS[cid]
+        dev = torch.device("cuda:0")
+        self.T, self.I, base = inputs.make_batch(cfg, seed=seed)
+        self.qi, self.qt = inputs.budgets(cfg, base)
+        self.Td, self.Id = torch.from_numpy(self.T).to(dev), torch.from_numpy(self.I).to(dev)
+        self.qid, self.qtd = torch.from_numpy(self.qi).to(dev), torch.from_numpy(self.qt).to(dev)
+        self.buf = api.Buffers(cfg.B, cfg.L, cfg.P, len(self.qi), store_K=store_K)
+
+
+def time_workload(w, args, torch, api, np, steps, warmup, fused=False, graph=False):
+    """W untimed and K timed steps of the whole path; -> (ms per step by the host
+    clock around the K steps, per-stage ms from events on the launch stream)."""
+    buf, stream = w.buf, torch.cuda.current_stream()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record(stream)
+        if fused:
+            if ev:
+                ev[1].record(stream)         # (stage 1 runs inside the one kernel)
+            api.dpc_stage12_fused(w.Td, w.Id, buf.Topt, buf.split, buf.M, buf.K)
+        else:
+            api.dpc_stage1_minplus(w.Td, buf.Topt, buf.split)
+            if ev:
+                ev[1].record(stream)
+            api.dpc_stage2_knapsack(buf.Topt, w.Id, buf.M, buf.K, buf.workspace, shape=args.shape)
+        if ev:
+            ev[2].record(stream)
+        api.dpc_backtrack(buf.Topt, buf.split, w.Id, buf.M, buf.K, w.qid, w.qtd, buf.A, buf.A_len,
+                          buf.S, buf.S_len, buf.obj, buf.lat, buf.status)
+        if ev:
+            ev[3].record(stream)
+
+    for _ in range(warmup):
+        step()
+    api.dpc_stage2_check(buf.workspace)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    if graph:
+        # (per-stage events are recorded inside the graph once; the replays are timed as a whole)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        g.replay()
+        torch.cuda.synchronize()
+        stream = torch.cuda.current_stream()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            evs[k][0].record(stream)
+            g.replay()
+            for x in (1, 2, 3):
+                evs[k][x].record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        t0 = time.perf_counter()
+        for k in range(steps):
+            step(evs[k])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    api.dpc_stage2_check(buf.workspace)
+    ms_step = (t1 - t0) * 1e3 / steps
+    seg = [[e[x].elapsed_time(e[x + 1]) for e in evs] for x in range(3)]
+    stage_ms = {"stage1": float(np.mean(seg[0])), "stage2": float(np.mean(seg[1])),
+                "stage2_min": float(np.min(seg[1])), "backtrack": float(np.mean(seg[2]))}
+    return ms_step, stage_ms
+
+
+def oracle_leg(w, np, oracle, cores, want_K):
+    """The oracle, as it stands, on every instance and query of the workload (one
+    instance per host thread), timed; then the GPU buffers of the last step
+    against it, element by element, tolerance 0.  -> (seconds, parity dict)."""
+    cfg, buf = w.cfg, w.buf
+    tc0 = time.perf_counter()
+    To, sp, Mo, Ko = oracle.solve_batch(w.T, w.I, cfg.P, want_K=True, threads=cores)
+    res = [oracle.backtrack(To[b], sp[b], w.I[b], Mo[b], Ko[b] if want_K else None, int(t))
+           for b, t in zip(w.qi, w.qt)]
+    tc1 = time.perf_counter()
+    bad = 0
+    bad += int((buf.Topt.cpu().numpy() != To).sum()) + int((buf.split.cpu().numpy() != sp).sum())
+    for b in range(cfg.B):                       # instance by instance: the tables are large
+        bad += int((buf.M[b].cpu().numpy().view(np.uint32) != Mo[b].view(np.uint32)).sum())
+        if buf.K is not None:
+            bad += int((buf.K[b].cpu().numpy() != Ko[b]).sum())
+    g = {k: getattr(buf, k).cpu().numpy() for k in ("A", "S", "A_len", "S_len", "obj", "lat", "status")}
+    qbad = 0
+    for q, r in enumerate(res):
+        same = (g["status"][q] == r["status"] and g["A_len"][q] == r["A_len"]
+                and g["S_len"][q] == r["S_len"] and g["lat"][q] == r["lat"]
+                and g["obj"][q:q + 1].view(np.uint32)[0] == np.array([r["obj"]], np.float32).view(np.uint32)[0])
+        if same and r["status"] == 0:
+            same = (list(g["A"][q][:r["A_len"]]) == list(r["A"])
+                    and list(g["S"][q][:r["S_len"]]) == list(r["S"]))
+        qbad += 0 if same else 1
+    cells = cfg.B * (cfg.L + 1) * cfg.P
+    parity = {"instances": cfg.B, "queries": len(res), "table_cells": cells,
+              "compared": "Topt, split, M" + (", K" if buf.K is not None else "") +
+                          "; status, A, S, objective, latency of every query",
+              "mismatches": bad + qbad}
+    return tc1 - tc0, parity
 
 
 def main():
@@ -46,9 +177,13 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5)
-    ap.add_argument("--variant", type=int, default=0, help="stage-2 kernel family (0 auto)")
+    ap.add_argument("--shape", type=int, default=0,
+                    help="stage-2 kernel shape through the test hook (0 = the library's choice)")
     ap.add_argument("--no-K", action="store_true", help="do not store back-pointers")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-cpu", action="store_true",
+                    help="skip the cpu_baseline leg and the parity check against it")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the timings of workloads 1-4 that follow the headline one")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--ext", action="store_true",
                     help="time the extended solver (Appendix B: Algorithms 1, 3, 4 and set "
@@ -90,80 +225,27 @@ def main():
         return bench_ext(args, np, torch, api, inputs)
     if args.sweep:
         return bench_sweep(args, np, torch, api, inputs)
-    cfg = inputs.CONFIGS[args.config]
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    T, I, base = inputs.make_batch(cfg, seed=args.seed)
-    qi, qt = inputs.budgets(cfg, base)
-    Td, Id = torch.from_numpy(T).to(dev), torch.from_numpy(I).to(dev)
-    qid, qtd = torch.from_numpy(qi).to(dev), torch.from_numpy(qt).to(dev)
-    buf = api.Buffers(cfg.B, cfg.L, cfg.P, len(qi), store_K=not args.no_K)
-    api.dpc_set_stage2_variant(args.variant)
-    stream = torch.cuda.current_stream()
+    torch.cuda.set_device(torch.device("cuda:0"))
+    store_K = not args.no_K
+    host_cores = os.cpu_count() or 1
+    cores = min(16, host_cores)                  # the GPU machine gives one job 16 cores' worth
+    w = Workload(args.config, args.seed, store_K, torch, api, inputs)
+    cfg = w.cfg
 
     if args.fused and not api.dpc_stage12_fused_supported(cfg.L, cfg.P):
         print(f"bench.py --fused: L = {cfg.L}, P = {cfg.P} is outside the single-launch path",
               file=sys.stderr)
         sys.exit(2)
 
-    def step(ev=None):
-        if ev:
-            ev[0].record(stream)
-        if args.fused:
-            if ev:
-                ev[1].record(stream)         # (stage 1 runs inside the one kernel)
-            api.dpc_stage12_fused(Td, Id, buf.Topt, buf.split, buf.M, buf.K)
-        else:
-            api.dpc_stage1_minplus(Td, buf.Topt, buf.split)
-            if ev:
-                ev[1].record(stream)
-            api.dpc_stage2_knapsack(buf.Topt, Id, buf.M, buf.K, buf.workspace)
-        if ev:
-            ev[2].record(stream)
-        api.dpc_backtrack(buf.Topt, buf.split, Id, buf.M, buf.K, qid, qtd, buf.A, buf.A_len,
-                          buf.S, buf.S_len, buf.obj, buf.lat, buf.status)
-        if ev:
-            ev[3].record(stream)
-
-    for _ in range(args.warmup):
-        step()
-    api.dpc_stage2_check(buf.workspace)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    if args.graph:
-        # (per-stage events are recorded inside the graph once; the replays are timed as a whole)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        graph.replay()
-        torch.cuda.synchronize()
-        stream = torch.cuda.current_stream()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            evs[k][0].record(stream)
-            graph.replay()
-            for x in (1, 2, 3):
-                evs[k][x].record(stream)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    else:
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            step(evs[k])
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    api.dpc_stage2_check(buf.workspace)
-
-    ms_step = (t1 - t0) * 1e3 / args.steps
-    s1 = [e[0].elapsed_time(e[1]) for e in evs]
-    s2 = [e[1].elapsed_time(e[2]) for e in evs]
-    s3 = [e[2].elapsed_time(e[3]) for e in evs]
+    ms_step, stage_ms = time_workload(w, args, torch, api, np, args.steps, args.warmup,
+                                      fused=args.fused, graph=args.graph)
     exact = inputs.relax_ops_exact(cfg.B, cfg.L, cfg.P)
     nominal = inputs.relax_ops_nominal(cfg.B, cfg.L, cfg.P)
-    s2_avg = float(np.mean(s2))
-    ops_per_relax = 2 if args.no_K else 4
+    s2_avg = stage_ms["stage2"]
+    ops_per_relax = 4 if store_K else 2
     achieved = ops_per_relax * exact / (s2_avg * 1e-3)
-    n_ok = int((buf.status == 0).sum().item())
+    floor_ops = variant_floor_ops(cfg.L, cfg.P, store_K)
+    prof = PROFILED.get(args.config) if (store_K and args.shape == 0 and not args.fused) else None
 
     out = {
         "metric": METRIC,
@@ -179,47 +261,76 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "L": cfg.L, "P": cfg.P,
-                   "queries": int(len(qi)), "store_K": not args.no_K,
-                   "stage2_variant": args.variant, "fused_stage12": bool(args.fused),
+                   "queries": int(len(w.qi)), "store_K": store_K,
+                   "stage2_shape": args.shape, "fused_stage12": bool(args.fused),
                    "graph_replay": bool(args.graph),
                    "seed": args.seed},
         "exact_relax_ops_per_s": exact / (ms_step * 1e-3),
         "stage2_exact_relax_ops_per_s": exact / (s2_avg * 1e-3),
-        "stage_ms": {"stage1": float(np.mean(s1)), "stage2": s2_avg,
-                     "stage2_min": float(np.min(s2)), "backtrack": float(np.mean(s3))},
-        "feasible_queries": n_ok,
+        "stage_ms": stage_ms,
+        "feasible_queries": int((w.buf.status == 0).sum().item()),
+        "host_cores": host_cores,
         "roofline": {
             "bound": "alu", "kernel": "stage 2 (dpc_stage2_knapsack)",
             "achieved": achieved / 1e12, "peak": VALU_PEAK_LANE_OPS / 1e12,
             "unit": "TOP/s", "frac": achieved / VALU_PEAK_LANE_OPS,
+            # `frac` counts the update one candidate at a time (add, compare, two
+            # selects); the kernel shape that ran issues fewer in its main loop:
             "ops_per_relax": ops_per_relax,
-            "traffic": MEASURED_TRAFFIC.get((args.config, args.variant)),
+            "variant_floor_ops": floor_ops,
+            "frac_of_variant_floor": floor_ops * exact / (s2_avg * 1e-3) / VALU_PEAK_LANE_OPS,
+            "issued_valu_per_relax": prof["issued_valu_per_relax"] if prof else None,
+            "traffic": prof["traffic_bytes"] if prof else None,
+            "traffic_source": (prof["file"] + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not this run)")
+                              if prof else None,
         },
     }
 
+    ok = True
     if not args.no_cpu:
         import oracle
-        cores = min(16, os.cpu_count() or 1)
-        nb = min(cfg.B, cores)
-        # about 10-30 s of CPU work: whole instances, one per thread
-        per_inst = inputs.relax_ops_exact(1, cfg.L, cfg.P)
-        while nb * per_inst < 2e10 and nb < cfg.B:
-            nb += cores
-        nb = min(nb, cfg.B)
-        sel = qi < nb
-        tc0 = time.perf_counter()
-        To, sp, Mo, Ko = oracle.solve_batch(T[:nb], I[:nb], cfg.P, want_K=not args.no_K,
-                                            threads=cores)
-        for b, t in zip(qi[sel], qt[sel]):
-            oracle.backtrack(To[b], sp[b], I[b], Mo[b], None if Ko is None else Ko[b], int(t))
-        tc1 = time.perf_counter()
+        secs, parity = oracle_leg(w, np, oracle, cores, store_K)
         out["cpu_baseline"] = {
-            "value": inputs.relax_ops_nominal(nb, cfg.L, cfg.P) / (tc1 - tc0),
-            "unit": "relax-ops/s", "cores": min(cores, nb), "kind": "oracle",
-            "sample": f"{nb} of {cfg.B} instances of {cfg.name}, all stages, "
-                      f"{tc1 - tc0:.2f} s wall",
+            "value": nominal / secs, "unit": "relax-ops/s", "cores": min(cores, cfg.B),
+            "host_cores": host_cores, "kind": "oracle",
+            "sample": f"all {cfg.B} instances and {len(w.qi)} queries of {cfg.name}, all stages, "
+                      f"{secs:.2f} s wall",
         }
+        out["parity"] = parity
+        ok = ok and parity["mismatches"] == 0
+
+    if not args.no_per_config and args.config == 5 and not (args.fused or args.graph):
+        # the other four workloads, timed the same way (and checked the same way)
+        del w
+        torch.cuda.empty_cache()
+        per = {}
+        for cid in (1, 2, 3, 4):
+            wc = Workload(cid, args.seed, store_K, torch, api, inputs)
+            c = wc.cfg
+            ms_c, st_c = time_workload(wc, args, torch, api, np, args.steps, args.warmup)
+            ex = inputs.relax_ops_exact(c.B, c.L, c.P)
+            fl = variant_floor_ops(c.L, c.P, store_K)
+            rate = ex / (st_c["stage2"] * 1e-3)
+            per[str(cid)] = {
+                "workload": c.name, "ms_step": ms_c, "stage_ms": st_c,
+                "nominal_relax_per_s": inputs.relax_ops_nominal(c.B, c.L, c.P) / (ms_c * 1e-3),
+                "stage2_exact_relax_per_s": rate,
+                "frac": ops_per_relax * rate / VALU_PEAK_LANE_OPS,
+                "variant_floor_ops": fl, "frac_of_variant_floor": fl * rate / VALU_PEAK_LANE_OPS,
+            }
+            if not args.no_cpu:
+                import oracle
+                secs, parity = oracle_leg(wc, np, oracle, cores, store_K)
+                per[str(cid)]["cpu_oracle_s"] = secs
+                per[str(cid)]["parity"] = parity
+                ok = ok and parity["mismatches"] == 0
+            del wc
+            torch.cuda.empty_cache()
+        out["per_config"] = per
     print(json.dumps(out))
+    if not ok:
+        print("bench.py: the GPU results differ from the oracle's", file=sys.stderr)
+        sys.exit(1)
 
 
 def bench_ext(args, np, torch, api, inputs):
@@ -238,7 +349,6 @@ def bench_ext(args, np, torch, api, inputs):
     Td, Id = torch.from_numpy(T).to(dev), torch.from_numpy(I4).to(dev)
     qid, qtd = torch.from_numpy(qi).to(dev), torch.from_numpy(qt).to(dev)
     buf = api.ExtBuffers(cfg.B, cfg.L, cfg.P, len(qi))
-    api.dpc_set_stage2_variant(args.variant)
     stream = torch.cuda.current_stream()
     for _ in range(args.warmup):
         api.ext_solve(Td, Id, qid, qtd, buf)
@@ -271,7 +381,7 @@ def bench_ext(args, np, torch, api, inputs):
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "extended solver on " + cfg.name, "B": cfg.B, "L": cfg.L, "P": cfg.P,
-                   "queries": int(len(qi)), "stage2_variant": args.variant, "seed": args.seed},
+                   "queries": int(len(qi)), "seed": args.seed},
         "stage_ms": {"stage1": float(np.mean(seg[0])), "importance_maxplus": float(np.mean(seg[1])),
                      "knapsack": s2, "backtrack": float(np.mean(seg[3]))},
         "feasible_queries": int((buf.status == 0).sum().item()),
@@ -325,7 +435,6 @@ def bench_sweep(args, np, torch, api, inputs):
     fo = torch.empty((B, cap), dtype=torch.float32, device=dev)
     fl = torch.empty((B,), dtype=torch.int32, device=dev)
     latA = torch.empty((qcap,), dtype=torch.int32, device=dev)
-    api.dpc_set_stage2_variant(args.variant)
     stream = torch.cuda.current_stream()
     names = ["importance_shift", "stage1", "stage2", "front", "front_queries", "backtrack",
              "chain_latency"]
@@ -372,7 +481,7 @@ def bench_sweep(args, np, torch, api, inputs):
         "config": {"workload": f"alpha sweep on {cfg.name}", "raw_tables": n_raw, "alphas": n_alpha,
                    "B": B, "L": cfg.L, "P": cfg.P, "queries": int(qn.item()), "query_room": qcap,
                    "front_cap": cap,
-                   "stage2_variant": args.variant, "seed": args.seed},
+                   "seed": args.seed},
         "stage_ms": seg,
         "feasible_queries": int(ok.sum().item()),
         "mean_front_points": float(fl.float().mean().item()),

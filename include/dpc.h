@@ -217,25 +217,6 @@ int dpc_ext_backtrack(int32_t B, int32_t L, int32_t P, const int32_t *Topt,
 const char *dpc_status_string(int code);
 
 /*
- * Tuning knob for measurements: selects the stage-2 kernel family.
- *   0  automatic (default): the wave-window family, task shape chosen from
- *      the problem size; tables narrower than 16 budgets use the tiled family
- *   1  row-at-a-time kernels reading M from global memory (one launch per row)
- *   2  persistent LDS-tiled kernel (windows shared by a workgroup), strip
- *      shape chosen from the problem size
- *   21..26  the same with a fixed task shape (threads x columns per thread,
- *       window buffers): 256x1, 256x2, 256x4 (2 buffers), 512x2, 1024x2,
- *       512x2 (2 buffers)
- *   3  persistent kernel with wave-private windows, same choice as 0
- *   31..39  the same with a fixed task shape (rows per group x waves per
- *       task, 256 columns per wave): 8x4, 8x8, 8x2, 8x1, 16x4, 16x8, 16x2,
- *       16x16, 8x16
- * Returns the previous value, or DPC_ERR_SHAPE for an unknown one.  Results
- * are bit-identical for every choice.  Process-wide, not thread-safe.
- */
-int dpc_set_stage2_variant(int variant);
-
-/*
  * ---- Small instances: stage 1 and stage 2 in one launch ----
  *
  * dpc_stage12_fused computes exactly what dpc_stage1_minplus followed by

@@ -21,12 +21,16 @@ DPC_OK = 0
 EXPORTS = (
     "dpc_stage1_minplus", "dpc_stage2_workspace_bytes", "dpc_stage2_knapsack",
     "dpc_stage2_check", "dpc_backtrack", "dpc_status_string",
-    "dpc_set_stage2_variant",
     "dpc_ext_importance_maxplus", "dpc_ext_workspace_bytes", "dpc_ext_knapsack",
     "dpc_ext_check", "dpc_ext_backtrack",
     "dpc_importance_shift", "dpc_front", "dpc_front_queries", "dpc_chain_latency",
     "dpc_stage12_fused_supported", "dpc_stage12_fused",
 )
+
+# exported for tests and measurements only (csrc/dpc_hooks.h), not part of include/dpc.h
+HOOKS = ("dpc_stage2_knapsack_shape",)
+SHAPE_ROWS = 1             # one launch per row
+SHAPE_WAVE_BASE = 30       # + task shape of the persistent kernel, see csrc/dpc_hooks.h
 
 _lib = None
 
@@ -59,8 +63,8 @@ def load():
     lib.dpc_backtrack.restype = ctypes.c_int
     lib.dpc_status_string.argtypes = [ctypes.c_int]
     lib.dpc_status_string.restype = ctypes.c_char_p
-    lib.dpc_set_stage2_variant.argtypes = [ctypes.c_int]
-    lib.dpc_set_stage2_variant.restype = ctypes.c_int
+    lib.dpc_stage2_knapsack_shape.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, sz, i32, vp]
+    lib.dpc_stage2_knapsack_shape.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -97,18 +101,22 @@ def dpc_stage2_workspace_bytes(B, L, P):
     return int(load().dpc_stage2_workspace_bytes(B, L, P))
 
 
-def dpc_stage2_knapsack(Topt, I, M, K, workspace, stream=None):
-    """Topt int32, I float32 [B][L+1][L+1] -> M float32, K uint8 or None [B][L+1][P]."""
+def dpc_stage2_knapsack(Topt, I, M, K, workspace, stream=None, shape=0):
+    """Topt int32, I float32 [B][L+1][L+1] -> M float32, K uint8 or None [B][L+1][P].
+    shape != 0 goes through the test hook dpc_stage2_knapsack_shape (a fixed kernel shape)."""
     B, ld, _ = Topt.shape
     P = M.shape[2]
     if not (isinstance(workspace, torch.Tensor) and workspace.is_cuda
             and workspace.dtype == torch.uint8 and workspace.is_contiguous()):
         raise DpcError("workspace: expected a contiguous uint8 GPU tensor")
-    _check(load().dpc_stage2_knapsack(
-        B, ld - 1, P, _dev(Topt, torch.int32, (B, ld, ld), "Topt"),
-        _dev(I, torch.float32, (B, ld, ld), "I"), _dev(M, torch.float32, (B, ld, P), "M"),
-        None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"),
-        ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+    args = [B, ld - 1, P, _dev(Topt, torch.int32, (B, ld, ld), "Topt"),
+            _dev(I, torch.float32, (B, ld, ld), "I"), _dev(M, torch.float32, (B, ld, P), "M"),
+            None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"),
+            ctypes.c_void_p(workspace.data_ptr()), workspace.numel()]
+    if shape:
+        _check(load().dpc_stage2_knapsack_shape(*args, int(shape), _stream(stream)))
+    else:
+        _check(load().dpc_stage2_knapsack(*args, _stream(stream)))
 
 
 def dpc_stage2_check(workspace, stream=None):
@@ -135,13 +143,6 @@ def dpc_backtrack(Topt, split, I, M, K, q_inst, q_T0, A, A_len, S, S_len, obj, l
         _dev(status, torch.int32, (Q,), "status"), _stream(stream)))
 
 
-def dpc_set_stage2_variant(variant):
-    prev = load().dpc_set_stage2_variant(int(variant))
-    if prev < 0:
-        _check(prev)
-    return prev
-
-
 class Buffers:
     """Device buffers for one problem shape, allocated once and reused."""
 
@@ -164,11 +165,11 @@ class Buffers:
         self.status = torch.empty((Q,), dtype=torch.int32, device=dev)
 
 
-def solve(T, I, q_inst, q_T0, buf: Buffers, stream=None):
+def solve(T, I, q_inst, q_T0, buf: Buffers, stream=None, shape=0):
     """The whole path on device tensors: stage 1, stage 2, set recovery.
     Queues the three calls on `stream` and returns without waiting."""
     dpc_stage1_minplus(T, buf.Topt, buf.split, stream)
-    dpc_stage2_knapsack(buf.Topt, I, buf.M, buf.K, buf.workspace, stream)
+    dpc_stage2_knapsack(buf.Topt, I, buf.M, buf.K, buf.workspace, stream, shape)
     dpc_backtrack(buf.Topt, buf.split, I, buf.M, buf.K, q_inst, q_T0, buf.A, buf.A_len,
                   buf.S, buf.S_len, buf.obj, buf.lat, buf.status, stream)
 

@@ -1,9 +1,8 @@
 // C-ABI entry points of libdpc.so: argument checks and kernel launches.
 #include "dpc_internal.h"
+#include "dpc_hooks.h"
 
 namespace {
-
-int g_stage2_variant = 0;
 
 int num_compute_units()
 {
@@ -42,28 +41,6 @@ bool shape_ok(int B, int L, int P)
            (int64_t)B * (L + 1) * (int64_t)P < ((int64_t)1 << 40);
 }
 
-// the stage-2 kernel family selected by dpc_set_stage2_variant, on checked arguments
-int stage2_dispatch(int B, int L, int P, const int32_t* Topt, const float* I, float* M, uint8_t* K,
-                    void* workspace, hipStream_t stream)
-{
-    hipError_t e;
-    if (g_stage2_variant == 1) {
-        // the row family uses no workspace; clear the header so that a later
-        // dpc_stage2_check reads "no error"
-        e = dpc::launch_clear_words(workspace, 2, stream);
-        if (e == hipSuccess) e = dpc::launch_stage2_rows(B, L, P, Topt, I, M, K, stream);
-    } else {
-        const int ncu = num_compute_units();
-        if (ncu <= 0) return DPC_ERR_HIP;
-        // the wave-window family reads whole 16-byte cells: narrow tables stay tiled
-        const bool wave = (g_stage2_variant == 0 || g_stage2_variant == 3 || g_stage2_variant > 30) &&
-                          P >= 16 && P < (1 << 29);   // (byte offsets inside a row are 32-bit there)
-        e = wave ? dpc::launch_stage2_wave(B, L, P, Topt, I, M, K, workspace, ncu, stream)
-                 : dpc::launch_stage2_tiled(B, L, P, Topt, I, M, K, workspace, ncu, stream);
-    }
-    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
-}
-
 // layout of the extended solver's workspace: the two virtual tables, then the
 // stage-2 workspace of the chain of 2L+2 virtual layers
 struct ExtLayout { size_t tv_off, iv_off, s2_off, total; };
@@ -83,6 +60,32 @@ bool ext_shape_ok(int B, int L, int P) { return L >= 1 && L <= DPC_EXT_MAX_L && 
 
 }  // namespace
 
+namespace dpc {
+
+int stage2_run(int B, int L, int P, const int32_t* Topt, const float* I, float* M, uint8_t* K,
+               void* workspace, int shape, hipStream_t stream)
+{
+    hipError_t e;
+    // The wave-window family copies whole 16-byte cells of a row and keeps byte
+    // offsets inside a row in 32 bits: tables narrower than 16 budgets (and
+    // absurdly wide ones) are solved row by row, one launch per row.
+    const bool rows = shape == DPC_SHAPE_ROWS || P < 16 || P >= (1 << 29);
+    if (rows) {
+        // this family uses no workspace; clear the header so that a later
+        // dpc_stage2_check reads "no error"
+        e = launch_clear_words(workspace, 2, stream);
+        if (e == hipSuccess) e = launch_stage2_rows(B, L, P, Topt, I, M, K, stream);
+    } else {
+        const int ncu = num_compute_units();
+        if (ncu <= 0) return DPC_ERR_HIP;
+        e = launch_stage2_wave(B, L, P, Topt, I, M, K, workspace, ncu,
+                               shape == 0 ? 0 : shape - DPC_SHAPE_WAVE_BASE, stream);
+    }
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+}  // namespace dpc
+
 extern "C" {
 
 const char* dpc_status_string(int code)
@@ -96,18 +99,6 @@ const char* dpc_status_string(int code)
         case DPC_ERR_TIMEOUT: return "DPC_ERR_TIMEOUT: a bounded in-kernel wait ran out";
         default: return "unknown libdpc status";
     }
-}
-
-int dpc_set_stage2_variant(int variant)
-{
-    if (!((variant >= 0 && variant <= 3) || (variant >= 21 && variant <= 26) ||
-          (variant >= 31 && variant <= 39)))
-        return DPC_ERR_SHAPE;
-    int prev = g_stage2_variant;
-    g_stage2_variant = variant;
-    dpc::g_s2_shape = variant > 20 && variant < 30 ? variant - 20 : 0;
-    dpc::g_s2w_shape = variant > 30 ? variant - 30 : 0;
-    return prev;
 }
 
 int dpc_stage1_minplus(int32_t B, int32_t L, const int32_t* T, int32_t* Topt, uint8_t* split,
@@ -133,7 +124,21 @@ int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, co
     if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
     if (workspace_bytes < dpc_stage2_workspace_bytes(B, L, P) || ((uintptr_t)workspace & 255))
         return DPC_ERR_WORKSPACE;
-    return stage2_dispatch(B, L, P, Topt, I, M, K, workspace, (hipStream_t)stream);
+    return dpc::stage2_run(B, L, P, Topt, I, M, K, workspace, 0, (hipStream_t)stream);
+}
+
+int dpc_stage2_knapsack_shape(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const float* I,
+                              float* M, uint8_t* K, void* workspace, size_t workspace_bytes,
+                              int32_t shape, void* stream)
+{
+    if (!Topt || !I || !M || !workspace) return DPC_ERR_NULL;
+    if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
+    if (shape != 0 && shape != DPC_SHAPE_ROWS &&
+        !dpc::stage2_wave_shape_known(shape - DPC_SHAPE_WAVE_BASE))
+        return DPC_ERR_SHAPE;
+    if (workspace_bytes < dpc_stage2_workspace_bytes(B, L, P) || ((uintptr_t)workspace & 255))
+        return DPC_ERR_WORKSPACE;
+    return dpc::stage2_run(B, L, P, Topt, I, M, K, workspace, shape, (hipStream_t)stream);
 }
 
 int dpc_stage2_check(const void* workspace, void* stream)
@@ -144,7 +149,7 @@ int dpc_stage2_check(const void* workspace, void* stream)
                        (hipStream_t)stream) != hipSuccess)
         return DPC_ERR_HIP;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DPC_ERR_HIP;
-    return dpc::stage2_tiled_error(head) ? DPC_ERR_TIMEOUT : DPC_OK;
+    return head[1] != 0 ? DPC_ERR_TIMEOUT : DPC_OK;     // (the error word of the header)
 }
 
 int dpc_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const uint8_t* split,
@@ -192,7 +197,7 @@ int dpc_ext_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const
     float* Iv = (float*)(base + lay.iv_off);
     hipError_t e = dpc::launch_ext_expand(B, L, Topt, Iopt, Tv, Iv, (hipStream_t)stream);
     if (e != hipSuccess) return DPC_ERR_HIP;
-    return stage2_dispatch(B, 2 * L + 2, P, Tv, Iv, D, Kx, base + lay.s2_off, (hipStream_t)stream);
+    return dpc::stage2_run(B, 2 * L + 2, P, Tv, Iv, D, Kx, base + lay.s2_off, 0, (hipStream_t)stream);
 }
 
 int dpc_ext_check(int32_t B, int32_t L, int32_t P, const void* workspace, void* stream)

@@ -14,14 +14,15 @@ hipError_t launch_stage2_rows(int B, int L, int P, const int32_t* Topt, const fl
 // zero `nwords` 32-bit words with a small kernel (safe to record into a HIP graph)
 hipError_t launch_clear_words(void* p, int nwords, hipStream_t st);
 size_t stage2_workspace_bytes(int B, int L, int P);
-hipError_t launch_stage2_tiled(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
-                               uint8_t* K, void* workspace, int num_cu, hipStream_t st);
+// shape 0: task shape chosen from the problem size; otherwise a fixed one
+// (stage2_wave_shape_known), for tests and measurements
 hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
-                              uint8_t* K, void* workspace, int num_cu, hipStream_t st);
-extern int g_s2w_shape;  // the same for the wave-window family, 1..5
-extern int g_s2_shape;   // 0 = choose the strip shape from the problem size, 1..5 = force it
-// reads the error word out of a host copy of the first 8 workspace bytes
-int stage2_tiled_error(const void* workspace_host_copy);
+                              uint8_t* K, void* workspace, int num_cu, int shape, hipStream_t st);
+bool stage2_wave_shape_known(int shape);
+// Stage 2 on checked arguments with the kernel family `shape` selects (see
+// dpc_hooks.h; 0 = the default choice).  Returns a DPC_* code.
+int stage2_run(int B, int L, int P, const int32_t* Topt, const float* I, float* M, uint8_t* K,
+               void* workspace, int shape, hipStream_t st);
 hipError_t launch_backtrack(int B, int L, int P, const int32_t* Topt, const uint8_t* split,
                             const float* I, const float* M, const uint8_t* K, int Q,
                             const int32_t* q_inst, const int32_t* q_T0, int32_t* A,

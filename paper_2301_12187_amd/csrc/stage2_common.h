@@ -11,13 +11,12 @@ namespace dpc {
 typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr int S2_H = 8;            // rows per operand record; a group has 8 or 16 rows
-constexpr int S2_R = 8;            // rows per group of the LDS-tiled family
 
 struct S2Header {
     uint32_t ticket;
     uint32_t error;
     uint32_t total;                // number of tasks, written by the layout kernel
-    uint32_t pad[29];              // (phase timers of instrumented builds)
+    uint32_t pad[29];
     float ninf[4];                 // byte 128: sixteen bytes of -inf, the source of window
                                    // cells that lie below column 0 (layout kernel)
     uint32_t choice;               // which of two prepared shapes runs (launch_stage2_decide)

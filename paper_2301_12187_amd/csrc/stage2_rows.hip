@@ -4,8 +4,9 @@
 // candidate only when strictly greater, which yields the lowest arg-max.
 // Topt[i][j] and I[i][j] are wave-uniform (scalar loads); M[i][t - Topt[i][j]]
 // is a shifted, contiguous window of row i: coalesced.  Every row comes from
-// global memory, so this family is bound by L2 / HBM reads; it is the simple
-// fallback and the baseline the tiled kernel is measured against.
+// global memory, so this family is bound by L2 / HBM reads; it serves tables
+// narrower than 16 budgets, which the persistent family does not take, and as
+// a plain cross-check of it in the tests.
 #include "dpc_internal.h"
 
 namespace dpc {

@@ -2,11 +2,11 @@
 // recurrence Eq. 7 of the paper): M[j][t] = max_i fl32(M[i][t - Topt[i][j]] +
 // I[i][j]), lowest arg-max.
 //
-// Tasks, ghost columns, ticket order, completion counters and the row-by-row
-// fallback are those of the LDS-tiled family (stage2_tiled.hip): a task is
-// (instance, group of R = 8 or 16 rows, strip of WCAP = NW*256 columns), it
-// keeps the R x WCAP running (maximum, arg-max) pairs in registers, reads rows
-// below its group from global memory and writes its own rows.  Every row of M
+// Tasks.  The rows 1..L of an instance are cut into groups of R = 8 or 16
+// rows, the budget axis into strips of WCAP = NW*256 columns.  A task is
+// (instance, row group, strip): it keeps the R x WCAP running (maximum,
+// arg-max) pairs in registers, reads rows below its group from global memory
+// and writes its own rows, so it carries no state from task to task.  Every row of M
 // is read back once per group above it, and that traffic, not the arithmetic,
 // bounds the kernel when tables are wide: hence the tall groups.  To fit 16
 // rows x 4 columns per lane the arg-max indices are kept as bytes, four to a
@@ -46,23 +46,12 @@
 // attains it, and inside the pair the lower row wins a tie.
 //
 // The diagonal part (predecessors inside the group) is shared by the waves of
-// the workgroup as in the tiled family: a finished row goes to one of two LDS
+// the workgroup: a finished row goes to one of two LDS
 // slots (laid over the rings, which are idle by then) from which the rows
 // below it are relaxed, one workgroup barrier per row.
 #include "stage2_common.h"
 
 namespace dpc {
-
-// Optional phase timers (build with -DDPC_S2_TIMERS): lane 0 of wave 0 of every
-// workgroup accumulates wall-clock ticks (100 MHz) per phase and adds them to
-// the spare words of the workspace header.
-#ifdef DPC_S2_TIMERS
-#define TMARK(var) const long long var = wall_clock64()
-#define TACC(slot, a, b) do { if (tid == 0) tacc[slot] += (b) - (a); } while (0)
-#else
-#define TMARK(var) do {} while (0)
-#define TACC(slot, a, b) do {} while (0)
-#endif
 
 // One relaxation of one cell: if cand > best then best = cand and byte BYTE of
 // argp = vi (vi < 256), i.e. Eq. 7's max with the lowest arg-max kept when
@@ -178,13 +167,8 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     int* const sh_word = (int*)lds;                  // ticket broadcast (the rings are idle then)
 
     const int total = (int)hdr->total;
-#ifdef DPC_S2_TIMERS
-    long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const long long tkernel0 = wall_clock64();
-#endif
     int publish = -1;                              // entry of the task this workgroup just finished
     for (;;) {
-        TMARK(t_a);
         // ---- wave 0: count the finished task as complete, take the next ticket
         //      and look up its task.  All of it is wave-uniform code (one lane
         //      only issues the atomics and writes the result), so that the
@@ -244,14 +228,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         const int prev_row0 = __builtin_amdgcn_readfirstlane(sh_word[5]);
         const int spread = __builtin_amdgcn_readfirstlane(sh_word[6]);
         __syncthreads();
-#ifdef DPC_S2_TIMERS
-        if (e < 0 && tid == 0) {
-            tacc[7] = wall_clock64() - tkernel0;
-            for (int q = 0; q < 8; ++q)
-                atomicAdd((unsigned long long*)&hdr->pad[1 + 2 * q], (unsigned long long)tacc[q]);
-            atomicAdd(&hdr->pad[21], 1u);
-        }
-#endif
         if (e < 0) return;                         // no ticket left, or a wait ran out: all leave
         const int level = e / B;
         const int b = e - level * B;
@@ -545,8 +521,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         const bool pair_task = PAIRS && full && s2_window_loads(spread) <= 2 &&
                                (long long)ld * P < (1LL << 30) && P < (1 << 20);
         // ---------------- off-diagonal part: rows i < ilimit ----------------
-        TMARK(t_b);
-        TACC(3, t_a, t_b);
         // The part itself, compiled once per window size: NLD copies of 256 floats
         // per row, S2W_RING / (256 NLD) ring slots, D = slots - 1 rows ahead.
         auto offdiag = [&](auto nld_c) __attribute__((always_inline)) {
@@ -640,7 +614,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
 #pragma unroll
                 for (int h = 0; h < H; ++h) cur[h] = brec[h];
                 for (int i = 0; i < ilimit; ++i) {
-                    TMARK(ta);
                     const int inext = min(i + 1, L) * H;
                     // the loads of the D rows ahead stay in flight; past the last
                     // row there is nothing left to start and nothing to leave
@@ -652,11 +625,9 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                         wait_vm(0);
                     }
                     asm volatile("" ::: "memory");             // row i has landed
-                    TMARK(tb);
                     const int delta = (tS - (int)cur[0].pad[0]) & 3;   // alignment slack of the window
                     const char* base = lbase + (slot * SLOTF + delta) * 4;
                     const uint32_t vi = cur[0].pad[3];
-#ifndef DPC_S2_NORELAX                                         // (timing experiments only)
                     if constexpr (H == 1) {
                         const S2Rec nxt = brec[inext];
                         relax_half(std::integral_constant<int, 0>{}, base, cur[0], vi);
@@ -670,10 +641,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                         cur[H - 1] = brec[inext + H - 1];
                         cur[0] = nxt0;
                     }
-#endif
-                    TMARK(tc);
-                    TACC(0, ta, tb);
-                    TACC(2, tb, tc);
                     ahead = slot;
                     slot = slot + 1 == NSL ? 0 : slot + 1;
                 }
@@ -702,7 +669,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             else if (nld == 3) offdiag(std::integral_constant<int, 3>{});
             else offdiag(std::integral_constant<int, 4>{});
         }
-        TMARK(t_c);
         if (!full) {
             // ---------------- a one-row task only has its row to store ----------------
 #pragma unroll
@@ -712,8 +678,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             }
         } else {
             __syncthreads();                           // every ring is idle: the slots below lie over them
-            TMARK(t_c2);
-            TACC(1, t_c, t_c2);
             if constexpr (PAIRS && STORE_K) {
                 if (pair_task) {
                     // operands of the even rows below the group, behind the two slots
@@ -792,16 +756,11 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 }
             }
         }
-
-        TMARK(t_d);
-        TACC(4, t_c, t_d);
         // ---- the task is complete once every wave's stores are acknowledged;
         //      wave 0 publishes it at the top of the loop
         wait_vm(0);
         __syncthreads();                               // (also: the LDS is free again)
         publish = e;
-        TMARK(t_e);
-        TACC(5, t_d, t_e);
     }
 }
 
@@ -860,9 +819,7 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
     return hipGetLastError();
 }
 
-int g_s2w_shape = 0;    // tuning override, see launch_stage2_wave
-
-// groups of 8 rows (shapes 1-4, 9) or 16 rows (5-8): waves per task, ring slots
+// groups of 8 rows (shapes 1-4) or 16 rows (5, 6, 8): waves per task, ring slots
 // (smallest window), largest shift inside a group, waves per SIMD
 static hipError_t launch_wave_shape(int shape, int B, int L, int P, const int32_t* Topt, const float* I,
                                     float* M, uint8_t* K, void* workspace, int num_cu, hipStream_t st,
@@ -875,20 +832,22 @@ static hipError_t launch_wave_shape(int shape, int B, int L, int P, const int32_
         case 4: return launch_wave_cfg<8, 1, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
         case 5: return launch_wave_cfg<16, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
         case 6: return launch_wave_cfg<16, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
-        case 7: return launch_wave_cfg<16, 2, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
         case 8: return launch_wave_cfg<16, 16, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
-        case 9: return launch_wave_cfg<8, 16, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
         default: return hipErrorInvalidValue;
     }
 }
 
+bool stage2_wave_shape_known(int shape) { return (shape >= 1 && shape <= 6) || shape == 8; }
+
+// shape 0: chosen from the problem size (below); otherwise one of the task
+// shapes of launch_wave_shape, whatever the size (tests and measurements)
 hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
-                              uint8_t* K, void* workspace, int num_cu, hipStream_t st)
+                              uint8_t* K, void* workspace, int num_cu, int shape, hipStream_t st)
 {
     // a window cell may read up to three floats past the end of a row
     if (P < 16) return hipErrorInvalidValue;
-    if (g_s2w_shape != 0)
-        return launch_wave_shape(g_s2w_shape, B, L, P, Topt, I, M, K, workspace, num_cu, st, false, 0u, false);
+    if (shape != 0)
+        return launch_wave_shape(shape, B, L, P, Topt, I, M, K, workspace, num_cu, st, false, 0u, false);
     // Task shape.  Groups of 8 rows: the narrowest task that covers a narrow
     // table, 2048 columns per task for wide ones.  Chains of 64 layers and more
     // run in groups of 16 rows where the table is wider than 512 budgets: they

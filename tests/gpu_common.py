@@ -8,8 +8,9 @@ from paper_2301_12187_amd import api
 from helpers import bits
 
 
-def run_gpu(T, I, P, q_inst, q_T0, store_K=True, variant=0, fused=False):
-    """numpy in -> dict of numpy outputs from the HIP path."""
+def run_gpu(T, I, P, q_inst, q_T0, store_K=True, shape=0, fused=False):
+    """numpy in -> dict of numpy outputs from the HIP path.  shape: 0 = the library's own
+    choice of stage-2 kernel, else a fixed one through the test hook (csrc/dpc_hooks.h)."""
     B, ld, _ = T.shape
     L = ld - 1
     dev = torch.device("cuda:0")
@@ -26,15 +27,11 @@ def run_gpu(T, I, P, q_inst, q_T0, store_K=True, variant=0, fused=False):
     buf.split.fill_(0xEE)
     buf.A.fill_(-9)
     buf.S.fill_(-9)
-    prev = api.dpc_set_stage2_variant(variant)
-    try:
-        if fused:                      # stage 1 + stage 2 in one launch, then set recovery
-            api.solve_fused(Td, Id, qi, qt, buf)
-        else:
-            api.solve(Td, Id, qi, qt, buf)
-            api.dpc_stage2_check(buf.workspace)
-    finally:
-        api.dpc_set_stage2_variant(prev)
+    if fused:                          # stage 1 + stage 2 in one launch, then set recovery
+        api.solve_fused(Td, Id, qi, qt, buf)
+    else:
+        api.solve(Td, Id, qi, qt, buf, shape=shape)
+        api.dpc_stage2_check(buf.workspace)
     torch.cuda.synchronize()
     out = dict(Topt=buf.Topt.cpu().numpy(), split=buf.split.cpu().numpy(),
                M=buf.M.cpu().numpy(), K=None if buf.K is None else buf.K.cpu().numpy(),

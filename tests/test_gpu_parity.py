@@ -11,9 +11,8 @@ from gpu_common import compare, run_gpu, run_oracle
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [1, 2, 3]
-SHAPES = [21, 22, 23, 24, 25, 26,      # every task shape of the tiled kernel
-          31, 32, 33, 34, 35, 36, 37, 38, 39]  # ... of the wave-window kernel
+VARIANTS = [0, 1]                            # the library's own choice; one launch per row
+SHAPES = [31, 32, 33, 34, 35, 36, 38]        # every task shape of the persistent kernel
 
 
 def _all_budgets(B, P, step=1):
@@ -28,7 +27,7 @@ def test_config_single_instance(cid, variant):
     cfg = inputs.CONFIGS[cid]
     T, I, base = inputs.make_batch(cfg, seed=0)
     qi, qt = _all_budgets(1, cfg.P)             # cfg2 sweeps every budget; do it for cfg1 too
-    g = run_gpu(T, I, cfg.P, qi, qt, variant=variant)
+    g = run_gpu(T, I, cfg.P, qi, qt, shape=variant)
     r = run_oracle(T, I, cfg.P, qi, qt)
     compare(g, r, cfg.L, cfg.name)
 
@@ -50,7 +49,7 @@ def test_tiny_tie_rich_instances(seed, variant):
         Is.append(I)
     T, I = np.stack(Ts), np.stack(Is)
     qi, qt = _all_budgets(B, P)
-    g = run_gpu(T, I, P, qi, qt, variant=variant)
+    g = run_gpu(T, I, P, qi, qt, shape=variant)
     r = run_oracle(T, I, P, qi, qt)
     compare(g, r, L, f"tiny seed {seed} L={L} P={P}")
 
@@ -69,7 +68,7 @@ def test_ragged_shapes_span_several_tiles(variant):
             Is.append(I)
         T, I = np.stack(Ts), np.stack(Is)
         qi, qt = _all_budgets(B, P, step=max(1, P // 50))
-        g = run_gpu(T, I, P, qi, qt, variant=variant)
+        g = run_gpu(T, I, P, qi, qt, shape=variant)
         r = run_oracle(T, I, P, qi, qt)
         compare(g, r, L, f"ragged B={B} L={L} P={P}")
 
@@ -93,7 +92,7 @@ def test_wide_shift_spread_and_infeasible_blocks(variant):
     T, I = np.stack(Ts), np.stack(Is)
     qi, qt = _all_budgets(B, P, step=37)
     # stage 2 is fed the oracle-independent GPU Topt, as in the real path
-    g = run_gpu(T, I, P, qi, qt, variant=variant)
+    g = run_gpu(T, I, P, qi, qt, shape=variant)
     r = run_oracle(T, I, P, qi, qt)
     compare(g, r, L, "wide shifts")
 
@@ -108,7 +107,7 @@ def test_denormals_and_signed_zero(variant):
     I[0] = (I[0] * np.float32(1e-39)).astype(np.float32)      # denormal importances
     I[1][np.triu_indices(L + 1, k=1)] = np.float32(-0.0)
     qi, qt = _all_budgets(B, P, step=7)
-    g = run_gpu(T, I, P, qi, qt, variant=variant)
+    g = run_gpu(T, I, P, qi, qt, shape=variant)
     r = run_oracle(T, I, P, qi, qt)
     assert np.any((np.abs(r["M"][0]) > 0) & (np.abs(r["M"][0]) < 1.1754944e-38))
     compare(g, r, L, "denormals / zeros")
@@ -138,7 +137,7 @@ def test_ties_between_the_rows_of_a_pair_of_predecessors(L, P, tmax, variant):
         Is.append(I)
     T, I = np.stack(Ts), np.stack(Is)
     qi, qt = _all_budgets(B, P, step=max(1, P // 60))
-    g = run_gpu(T, I, P, qi, qt, variant=variant)
+    g = run_gpu(T, I, P, qi, qt, shape=variant)
     compare(g, run_oracle(T, I, P, qi, qt), L, f"pairs L={L} P={P} variant {variant}")
 
 
@@ -151,7 +150,7 @@ def test_table_with_more_budgets_than_the_pair_step_takes():
     T, I = T[None], I[None]
     qt = np.array([0, 5, 70001, 400000, P - 1], np.int32)
     qi = np.zeros_like(qt)
-    g = run_gpu(T, I, P, qi, qt, variant=35)
+    g = run_gpu(T, I, P, qi, qt, shape=35)
     compare(g, run_oracle(T, I, P, qi, qt), L, "P > 2^20")
 
 
@@ -160,7 +159,7 @@ def test_without_stored_backpointers(variant):
     cfg = inputs.CONFIGS[2]
     T, I, base = inputs.make_batch(cfg, seed=3)
     qi, qt = _all_budgets(1, cfg.P, step=9)
-    g = run_gpu(T, I, cfg.P, qi, qt, store_K=False, variant=variant)
+    g = run_gpu(T, I, cfg.P, qi, qt, store_K=False, shape=variant)
     r = run_oracle(T, I, cfg.P, qi, qt)
     compare(g, r, cfg.L, "K == NULL")
 
@@ -184,7 +183,7 @@ def test_without_stored_backpointers_shapes_and_special_values(variant):
             I[0] = (I[0] * np.float32(1e-39)).astype(np.float32)
             I[1][np.triu_indices(L + 1, k=1)] = np.float32(-0.0)
         qi, qt = _all_budgets(B, P, step=max(1, P // 40))
-        g = run_gpu(T, I, P, qi, qt, store_K=False, variant=variant)
+        g = run_gpu(T, I, P, qi, qt, store_K=False, shape=variant)
         compare(g, run_oracle(T, I, P, qi, qt), L, f"K == NULL, {kind}")
 
 
@@ -194,7 +193,7 @@ def test_config5_shape_without_stored_backpointers():
     cfg = inputs.CONFIGS[5]
     T, I, base = inputs.make_batch(cfg, seed=0, B=4)
     qi, qt = inputs.budgets(cfg, base)
-    g = run_gpu(T, I, cfg.P, qi, qt, store_K=False, variant=35)
+    g = run_gpu(T, I, cfg.P, qi, qt, store_K=False, shape=35)
     compare(g, run_oracle(T, I, cfg.P, qi, qt, threads=4), cfg.L, "cfg5 shape, K == NULL")
 
 
@@ -227,7 +226,7 @@ def test_large_latencies_wide_windows(variant, scale):
     T, I, base = inputs.make_batch(cfg, seed=21, B=6)
     T = np.where(T < DPC_INF, T * scale, T).astype(np.int32)
     qi, qt = inputs.budgets(cfg, base * scale)
-    g = run_gpu(T, I, cfg.P, qi, qt, variant=variant)
+    g = run_gpu(T, I, cfg.P, qi, qt, shape=variant)
     compare(g, run_oracle(T, I, cfg.P, qi, qt, threads=6), cfg.L, f"latencies x{scale}")
 
 
@@ -241,7 +240,7 @@ def test_device_side_choice_between_group_sizes(scale):
     T, I, base = inputs.make_batch(cfg, seed=2, B=3)
     T = np.where(T < DPC_INF, T * scale, T).astype(np.int32)
     qi, qt = inputs.budgets(cfg, base)
-    g = run_gpu(T, I, cfg.P, qi, qt, variant=0)
+    g = run_gpu(T, I, cfg.P, qi, qt, shape=0)
     compare(g, run_oracle(T, I, cfg.P, qi, qt, threads=3), cfg.L, f"cfg5 shape, latencies x{scale}")
 
 
@@ -254,13 +253,9 @@ def test_default_shape_by_width_and_batch(P, B):
     cfg = dataclasses.replace(inputs.CONFIGS[4], P=P, B=B)
     T, I, base = inputs.make_batch(cfg, seed=5)
     qi, qt = inputs.budgets(cfg, base)
-    g = run_gpu(T, I, cfg.P, qi, qt, variant=0)
-    sample = np.arange(0, cfg.B, max(1, cfg.B // 6))
-    sel = np.isin(qi, sample)
-    r = run_oracle(T[sample], I[sample], cfg.P, np.searchsorted(sample, qi[sel]), qt[sel],
-                   threads=16)
-    gs = {k: (v[sample] if k in ("Topt", "split", "M", "K") else v[sel]) for k, v in g.items()}
-    compare(gs, r, cfg.L, f"L=100 P={P} B={B}")
+    g = run_gpu(T, I, cfg.P, qi, qt, shape=0)
+    # every instance and every query
+    compare(g, run_oracle(T, I, cfg.P, qi, qt, threads=16), cfg.L, f"L=100 P={P} B={B}")
 
 
 def test_bad_queries_and_empty_query_list():
@@ -278,46 +273,45 @@ def test_bad_queries_and_empty_query_list():
 
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_config3_batch(variant):
-    cfg = inputs.CONFIGS[3]
-    T, I, base = inputs.make_batch(cfg, seed=0)
-    qi, qt = inputs.budgets(cfg, base)
-    g = run_gpu(T, I, cfg.P, qi, qt, variant=variant)
-    r = run_oracle(T, I, cfg.P, qi, qt, threads=16)
+    cfg, T, I, qi, qt, r = _config_oracle(3)
+    g = run_gpu(T, I, cfg.P, qi, qt, shape=variant)
     compare(g, r, cfg.L, cfg.name)
 
 
-@pytest.mark.parametrize("variant", VARIANTS + [24, 26, 31, 32, 35, 38])
+_ORACLE_CACHE = {}
+
+
+def _config_oracle(cid):
+    """Inputs, queries and the oracle's results for ALL instances and queries of
+    a named workload, computed once per test session."""
+    if cid not in _ORACLE_CACHE:
+        cfg = inputs.CONFIGS[cid]
+        T, I, base = inputs.make_batch(cfg, seed=0)
+        qi, qt = inputs.budgets(cfg, base)
+        _ORACLE_CACHE.clear()                      # (one workload's tables at a time: they are large)
+        _ORACLE_CACHE[cid] = (cfg, T, I, qi, qt, run_oracle(T, I, cfg.P, qi, qt, threads=16))
+    return _ORACLE_CACHE[cid]
+
+
+@pytest.mark.parametrize("variant", VARIANTS + [31, 32, 35, 38])
 def test_config4_batch(variant):
-    cfg = inputs.CONFIGS[4]
-    T, I, base = inputs.make_batch(cfg, seed=0)
-    qi, qt = inputs.budgets(cfg, base)
-    g = run_gpu(T, I, cfg.P, qi, qt, variant=variant)
-    # the oracle on a sample of instances (full table each)
-    sample = np.arange(0, cfg.B, 8)
-    sel = np.isin(qi, sample)
-    r = run_oracle(T[sample], I[sample], cfg.P, np.searchsorted(sample, qi[sel]), qt[sel],
-                   threads=16)
-    gs = {k: (v[sample] if k in ("Topt", "split", "M", "K") else v[sel]) for k, v in g.items()}
-    compare(gs, r, cfg.L, cfg.name)
+    """All 256 instances and all 1280 queries, element by element."""
+    cfg, T, I, qi, qt, r = _config_oracle(4)
+    g = run_gpu(T, I, cfg.P, qi, qt, shape=variant)
+    compare(g, r, cfg.L, cfg.name)
 
 
-def test_config5_full_size_sampled_instances():
+@pytest.mark.parametrize("store_K", [True, False])
+def test_config5_full_size_every_instance(store_K):
     """The launch configuration bench.py times (all 64 instances, default
-    kernel choice); the oracle recomputes a sample of whole instances."""
-    cfg = inputs.CONFIGS[5]
-    T, I, base = inputs.make_batch(cfg, seed=0)
-    qi, qt = inputs.budgets(cfg, base)
-    g = run_gpu(T, I, cfg.P, qi, qt, variant=0)
-    sample = np.array([0, 9, 18, 27, 36, 45, 54, 63])
-    sel = np.isin(qi, sample)
-    r = run_oracle(T[sample], I[sample], cfg.P, np.searchsorted(sample, qi[sel]), qt[sel],
-                   threads=16)
-    gs = {k: (v[sample] if k in ("Topt", "split", "M", "K") else v[sel]) for k, v in g.items()}
-    compare(gs, r, cfg.L, cfg.name)
+    kernel choice), with and without stored back-pointers: every cell of every
+    instance and every one of the 10 240 queries against the oracle."""
+    cfg, T, I, qi, qt, r = _config_oracle(5)
+    g = run_gpu(T, I, cfg.P, qi, qt, shape=0, store_K=store_K)
+    compare(g, r, cfg.L, cfg.name)
     # properties that hold for every instance at any size
     M = g["M"]
     assert not np.isnan(M).any()
-    fin = np.isfinite(M[:, cfg.L, :])
     for b in range(cfg.B):
         row = M[b, cfg.L]
         first = int(g["Topt"][b, 0, cfg.L])
@@ -325,6 +319,7 @@ def test_config5_full_size_sampled_instances():
         assert (np.diff(row[first:]) >= 0).all()
     ok = g["status"] == 0
     assert (g["lat"][ok] <= qt[ok]).all()
+    _ORACLE_CACHE.clear()
 
 
 def test_repeated_runs_are_bitwise_identical():

@@ -12,8 +12,8 @@ from paper_2301_12187_amd import api
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "dpc.h")).read()
+def _declared_functions(path=os.path.join(ROOT, "include", "dpc.h")):
+    text = open(path).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(dpc_[a-z0-9_]+)\s*\(", text)))
 
@@ -24,6 +24,11 @@ def test_header_functions_are_exported():
     lib = api.load()
     for n in names:
         assert getattr(lib, n) is not None
+    # the test hook is exported too, but declared in an internal header only
+    hooks = _declared_functions(os.path.join(ROOT, "paper_2301_12187_amd", "csrc", "dpc_hooks.h"))
+    assert set(hooks) == set(api.HOOKS)
+    for n in hooks:
+        assert getattr(lib, n) is not None and n not in names
 
 
 def test_argument_errors_are_reported_before_any_launch():
@@ -49,7 +54,8 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.dpc_backtrack(1, 4, 8, p, p, p, p, p, 0, *args, None) == 0     # nothing to do
     assert lib.dpc_backtrack(1, 4, 8, None, p, p, p, p, 3, *args, None) == NULL
     assert lib.dpc_backtrack(1, 4, 8, p, p, p, p, None, 3, p, None, *([p] * 8), None) == NULL
-    assert lib.dpc_set_stage2_variant(7) == SHAPE
+    assert lib.dpc_stage2_knapsack_shape(4, 50, 1000, p, p, p, p, p, need, 7, None) == SHAPE
+    assert lib.dpc_stage2_knapsack_shape(4, 50, 1000, p, p, p, p, p, need, 37, None) == SHAPE
     assert b"DPC_ERR_NULL" in lib.dpc_status_string(NULL)
     assert lib.dpc_status_string(12345)
 
