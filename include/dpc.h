@@ -111,6 +111,32 @@ int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t *Topt,
                         size_t workspace_bytes, void *stream);
 
 /*
+ * dpc_stage2_knapsack for callers that cannot allocate device memory or hand
+ * over a workspace: code running under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  (This entry point exists for those
+ * callers; it computes nothing the one above does not.)  The workspace is a
+ * fixed array of DPC_STATIC_WORKSPACE_BYTES of device memory inside the
+ * library, one per GPU, held until the process ends.  The call allocates and
+ * frees nothing; its first use on a GPU looks the array's address up once.
+ *   - Arguments, outputs and results are those of dpc_stage2_knapsack, bit
+ *     for bit, without `workspace` and `workspace_bytes`.
+ *   - Shapes whose dpc_stage2_workspace_bytes(B, L, P) exceeds
+ *     DPC_STATIC_WORKSPACE_BYTES are refused with DPC_ERR_WORKSPACE and
+ *     nothing is queued (the five named workloads of this repository fit:
+ *     the largest, B=1024, L=53, P=1000, needs 46.5 MiB).
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap on
+ *     a GPU (different streams, no ordering between them) race on it and must
+ *     not be made; calls on one stream, or ordered by events, are fine.  What
+ *     a call leaves in the array is cleared by the next call's own kernels.
+ *   - A bounded wait that ran out (see dpc_stage2_check) is not reported by
+ *     this variant.
+ */
+#define DPC_STATIC_WORKSPACE_BYTES (48u << 20)
+
+int dpc_stage2_knapsack_static(int32_t B, int32_t L, int32_t P, const int32_t *Topt,
+                               const float *I, float *M, uint8_t *K, void *stream);
+
+/*
  * Waits for `stream` and reports whether the last dpc_stage2_knapsack that
  * used `workspace` ran to completion: DPC_OK, DPC_ERR_TIMEOUT if a bounded
  * wait inside the kernel expired (a defect or a lost device, never an input

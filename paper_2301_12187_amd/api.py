@@ -21,6 +21,7 @@ DPC_OK = 0
 EXPORTS = (
     "dpc_stage1_minplus", "dpc_stage2_workspace_bytes", "dpc_stage2_knapsack",
     "dpc_stage2_check", "dpc_backtrack", "dpc_status_string",
+    "dpc_stage2_knapsack_static",
     "dpc_ext_importance_maxplus", "dpc_ext_workspace_bytes", "dpc_ext_knapsack",
     "dpc_ext_check", "dpc_ext_backtrack",
     "dpc_importance_shift", "dpc_front", "dpc_front_queries", "dpc_chain_latency",
@@ -56,6 +57,8 @@ def load():
     lib.dpc_stage2_workspace_bytes.restype = sz
     lib.dpc_stage2_knapsack.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.dpc_stage2_knapsack.restype = ctypes.c_int
+    lib.dpc_stage2_knapsack_static.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.dpc_stage2_knapsack_static.restype = ctypes.c_int
     lib.dpc_stage2_check.argtypes = [vp, vp]
     lib.dpc_stage2_check.restype = ctypes.c_int
     lib.dpc_backtrack.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp,
@@ -117,6 +120,20 @@ def dpc_stage2_knapsack(Topt, I, M, K, workspace, stream=None, shape=0):
         _check(load().dpc_stage2_knapsack_shape(*args, int(shape), _stream(stream)))
     else:
         _check(load().dpc_stage2_knapsack(*args, _stream(stream)))
+
+
+DPC_STATIC_WORKSPACE_BYTES = 48 << 20
+
+
+def dpc_stage2_knapsack_static(Topt, I, M, K, stream=None):
+    """dpc_stage2_knapsack on the library's own fixed workspace (no allocation, no
+    workspace argument); shapes that need more than DPC_STATIC_WORKSPACE_BYTES raise."""
+    B, ld, _ = Topt.shape
+    P = M.shape[2]
+    _check(load().dpc_stage2_knapsack_static(
+        B, ld - 1, P, _dev(Topt, torch.int32, (B, ld, ld), "Topt"),
+        _dev(I, torch.float32, (B, ld, ld), "I"), _dev(M, torch.float32, (B, ld, P), "M"),
+        None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"), _stream(stream)))
 
 
 def dpc_stage2_check(workspace, stream=None):
