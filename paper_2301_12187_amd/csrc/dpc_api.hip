@@ -73,7 +73,7 @@ int stage2_run(int B, int L, int P, const int32_t* Topt, const float* I, float* 
     if (rows) {
         // this family uses no workspace; clear the header so that a later
         // dpc_stage2_check reads "no error"
-        e = launch_clear_words(workspace, 2, stream);
+        e = launch_clear_words(workspace, S2_HEADER_WORDS, stream);
         if (e == hipSuccess) e = launch_stage2_rows(B, L, P, Topt, I, M, K, stream);
     } else {
         const int ncu = num_compute_units();
@@ -144,12 +144,12 @@ int dpc_stage2_knapsack_shape(int32_t B, int32_t L, int32_t P, const int32_t* To
 int dpc_stage2_check(const void* workspace, void* stream)
 {
     if (!workspace) return DPC_ERR_NULL;
-    uint32_t head[2] = {0, 0};
-    if (hipMemcpyAsync(head, workspace, sizeof(head), hipMemcpyDeviceToHost,
-                       (hipStream_t)stream) != hipSuccess)
+    uint32_t word = 0;
+    if (hipMemcpyAsync(&word, (const char*)workspace + dpc::S2_ERROR_WORD_OFFSET, sizeof(word),
+                       hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess)
         return DPC_ERR_HIP;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DPC_ERR_HIP;
-    return head[1] != 0 ? DPC_ERR_TIMEOUT : DPC_OK;     // (the error word of the header)
+    return word != 0 ? DPC_ERR_TIMEOUT : DPC_OK;
 }
 
 int dpc_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const uint8_t* split,

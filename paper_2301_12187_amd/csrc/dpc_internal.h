@@ -14,6 +14,9 @@ hipError_t launch_stage2_rows(int B, int L, int P, const int32_t* Topt, const fl
 // zero `nwords` 32-bit words with a small kernel (safe to record into a HIP graph)
 hipError_t launch_clear_words(void* p, int nwords, hipStream_t st);
 size_t stage2_workspace_bytes(int B, int L, int P);
+// byte offset, in a stage-2 workspace, of the word a kernel sets when a bounded wait ran out
+constexpr size_t S2_ERROR_WORD_OFFSET = 148;
+constexpr int S2_HEADER_WORDS = 64;
 // shape 0: task shape chosen from the problem size; otherwise a fixed one
 // (stage2_wave_shape_known), for tests and measurements
 hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const float* I, float* M,

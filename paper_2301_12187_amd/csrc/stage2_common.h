@@ -3,6 +3,7 @@
 // records and the task table, and the small kernels that build them.
 #pragma once
 #include <algorithm>
+#include <cstddef>
 #include <type_traits>
 #include "dpc_internal.h"
 
@@ -13,16 +14,17 @@ typedef __attribute__((address_space(3))) void lds_void;
 constexpr int S2_H = 8;            // rows per operand record; a group has 8 or 16 rows
 
 struct S2Header {
-    uint32_t ticket;
-    uint32_t error;
-    uint32_t total;                // number of tasks, written by the layout kernel
-    uint32_t pad[29];
+    uint32_t ticket;               // next ticket.  Alone in its 128 bytes: the atomics on it share
+    uint32_t pad0[31];             // a cache line with nothing that waiting waves poll
     float ninf[4];                 // byte 128: sixteen bytes of -inf, the source of window
                                    // cells that lie below column 0 (layout kernel)
     uint32_t choice;               // which of two prepared shapes runs (launch_stage2_decide)
-    uint32_t pad2[27];
+    uint32_t error;                // set when a bounded wait ran out (dpc_stage2_check)
+    uint32_t total;                // number of tasks, written by the layout kernel
+    uint32_t pad1[25];
 };
 static_assert(sizeof(S2Header) == 256, "header is one 256-byte block");
+static_assert(offsetof(S2Header, error) == S2_ERROR_WORD_OFFSET, "dpc_stage2_check reads this word");
 
 // A launch can be made conditional on the header's `choice` word: its kernels
 // return at once unless the word equals `want` (word == nullptr: unconditional).
@@ -90,7 +92,7 @@ S2Layout s2_layout(int B, int L, int P, int R);
 // runs whole (ghost width <= gmax, every spread <= dspread, every shift inside
 // the group <= dpad) or row by row, and lays out the task table for strips of
 // `wcap` columns.  `ahead`: see S2Rec::pad; a negative value asks for
-// min(-ahead, s2_rows_ahead(spread of the group)).
+// min(-ahead, s2_rows_ahead(ringf, spread of the group)).
 // gated: every kernel returns at once unless the header's choice word equals
 // `want` (the word survives this call's clearing).  decide: after packing, the
 // choice word is set to 1 if more than 2 % of the groups have to run row by
@@ -98,7 +100,7 @@ S2Layout s2_layout(int B, int L, int P, int R);
 // else to 0; the layout kernel that follows is then gated on 0.
 hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt, const float* I,
                                  float* M, uint8_t* K, void* workspace, int gmax, int dspread,
-                                 int dpad, int wcap, int ahead, hipStream_t st,
+                                 int dpad, int wcap, int ahead, int ringf, hipStream_t st,
                                  bool gated = false, uint32_t want = 0, bool decide = false);
 
 // What the pack kernel records about a group that runs whole: ghost width
@@ -107,15 +109,29 @@ __host__ __device__ __forceinline__ int s2_group_code(int ghost, int spread) { r
 __host__ __device__ __forceinline__ int s2_group_ghost(int code) { return code & 0xFFF; }
 __host__ __device__ __forceinline__ int s2_group_spread(int code) { return code >> 12; }
 
-// The wave-window kernel keeps, per wave, a ring of S2W_RING floats in LDS.  A
-// window of 256 columns plus `spread` (plus 3 of alignment slack) takes
-// s2_window_loads() copies of 256 floats; the ring then holds 5, 3 or 2 such
-// slots, and the kernel copies 4, 2 or 1 rows ahead of the one it relaxes.
-constexpr int S2W_RING = 2560;
-constexpr int S2W_MAX_SPREAD = 764;        // four copies per row at most
-__host__ __device__ __forceinline__ int s2_window_loads(int spread) { return (256 + spread + 3 + 255) >> 8; }
-__host__ __device__ __forceinline__ int s2_ring_slots(int spread) { return S2W_RING / (256 * s2_window_loads(spread)); }
-__host__ __device__ __forceinline__ int s2_rows_ahead(int spread) { return s2_ring_slots(spread) - 1; }
+// The wave-window kernel keeps, per wave, a ring of `ringf` floats in LDS (2560
+// for groups of 16 rows, 1920 for groups of 8: a compile-time constant of the
+// kernel).  A window of 256 columns plus `spread` (plus 3 of alignment slack)
+// is copied in units of 128 floats (a copy instruction moves 256 floats with
+// all lanes or 128 with the lower half of the wave).  The ring holds 5, 3 or 2
+// slots, chosen per task from the spread the pack kernel found for the group,
+// each as large as the ring allows (3 or 4 units with five slots), and the
+// kernel copies 4, 2 or 1 rows ahead of the one it relaxes.
+constexpr int S2W_UNIT = 128;
+__host__ __device__ __forceinline__ int s2_units_needed(int spread) { return (256 + spread + 3 + S2W_UNIT - 1) / S2W_UNIT; }
+// largest slot, in units, when the ring is cut into `slots` slots (8 units at most)
+__host__ __device__ constexpr int s2_slot_units_max(int ringf, int slots)
+{
+    return ringf / (S2W_UNIT * slots) < 8 ? ringf / (S2W_UNIT * slots) : 8;
+}
+__host__ __device__ __forceinline__ int s2_ring_slots(int ringf, int spread)
+{
+    const int need = s2_units_needed(spread);
+    return need <= s2_slot_units_max(ringf, 5) ? 5 : need <= s2_slot_units_max(ringf, 3) ? 3 : 2;
+}
+__host__ __device__ __forceinline__ int s2_rows_ahead(int ringf, int spread) { return s2_ring_slots(ringf, spread) - 1; }
+// the largest spread a whole-group task can take (two slots)
+__host__ __device__ constexpr int s2_max_spread(int ringf) { return S2W_UNIT * s2_slot_units_max(ringf, 2) - 259; }
 
 // Row groups.  Rows 1..L are cut into NQ = ceil(L / R) groups of R rows; when R
 // does not divide L the FIRST group is the short one (it has next to no
@@ -179,7 +195,9 @@ __device__ __forceinline__ void wait_vm(int later)
         case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
         case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
         case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
-        default: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+        case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+        case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
+        default: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
     }
 }
 

@@ -73,7 +73,7 @@ template <int R>
 __global__ __launch_bounds__(256) void stage2_pack_kernel(
     int L, int P, int NQ, const int32_t* __restrict__ Topt, const float* __restrict__ I,
     S2Rec* __restrict__ recs, S2Info* __restrict__ infos, S2Shift* __restrict__ shifts,
-    int32_t* __restrict__ groups, int gmax, int dspread, int dpad, int wcap, int ahead,
+    int32_t* __restrict__ groups, int gmax, int dspread, int dpad, int wcap, int ahead, int ringf,
     float* __restrict__ M, uint8_t* __restrict__ K, S2Gate gate, uint32_t* __restrict__ hdr_words,
     uint32_t* __restrict__ done, int keep_word)
 {
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     __syncthreads();
     // ahead < 0: the kernel sizes its ring slots by the group's spread and
     // works -ahead rows ahead at most, fewer when the slots are large
-    const int ahead_q = ahead >= 0 ? ahead : min(-ahead, s2_rows_ahead(spread));
+    const int ahead_q = ahead >= 0 ? ahead : min(-ahead, s2_rows_ahead(ringf, spread));
 #pragma unroll
     for (int h = 0; h < H; ++h) {
         rec[h].pad[0] = (uint32_t)smax[i];
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
 
 hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt, const float* I,
                                  float* M, uint8_t* K, void* workspace, int gmax, int dspread,
-                                 int dpad, int wcap, int ahead, hipStream_t st, bool gated,
+                                 int dpad, int wcap, int ahead, int ringf, hipStream_t st, bool gated,
                                  uint32_t want, bool decide)
 {
     if (R != 8 && R != 16) return hipErrorInvalidValue;
@@ -385,11 +385,11 @@ hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt
     const size_t pack_lds = (size_t)nt * ((size_t)(R + 1) * 8 + 8);
     if (R == 8)
         hipLaunchKernelGGL(stage2_pack_kernel<8>, dim3(NQ, B), dim3(nt), pack_lds, st, L, P, NQ, Topt, I,
-                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate,
+                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, ringf, M, K, gate,
                            (uint32_t*)hdr, done, keep_word);
     else
         hipLaunchKernelGGL(stage2_pack_kernel<16>, dim3(NQ, B), dim3(nt), pack_lds, st, L, P, NQ, Topt, I,
-                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, M, K, gate,
+                           recs, infos, shifts, groups, gmax, dspread, dpad, wcap, ahead, ringf, M, K, gate,
                            (uint32_t*)hdr, done, keep_word);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -17,8 +17,8 @@
 // that row that ITS columns need, [tW - maxshift_i, tW + 64*U - minshift_i),
 // into a slot of its own ring in LDS (global -> LDS loads, 16 bytes per lane,
 // no registers), a few rows ahead of the row it is relaxing (the ring holds 5,
-// 3 or 2 slots, sized per task from the largest spread of shifts that the
-// pack kernel found for the group: windows of up to 256 + 764 columns).  Nothing in this
+// 3 or 2 slots of a whole number of 128-float units, sized per task from the
+// largest spread of shifts that the pack kernel found for the group).  Nothing in this
 // part is shared between waves, so there is no workgroup barrier in it: a wave
 // waits only for its own loads, with a counted wait that leaves the loads of
 // the rows ahead in flight.  To make that count exact every row issues the
@@ -122,7 +122,19 @@ __device__ __forceinline__ void max_cand2(float& best, float a, float b)
 #endif
 }
 
-template <int R, int NW, int NSLOT, int DMAX, int WPE, bool STORE_K>
+// global -> LDS copy of 16 bytes per lane, made by the lanes for which `active`
+// holds (one instruction whatever the mask, as long as some lane is active):
+// lane l writes dst + 16 l bytes
+__device__ __forceinline__ void lds_load16_if(bool active, const float* src, float* dst)
+{
+#ifndef DPC_HOST_EMU
+    if (active) __builtin_amdgcn_global_load_lds(src, (lds_void*)dst, 16, 0, DMA_AGENT_SCOPE);
+#else
+    emu::global_load_lds_if(active, src, dst, 16);
+#endif
+}
+
+template <int R, int NW, int RINGF, int DMAX, int WPE, bool STORE_K>
 __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     int B, int L, int P, float* M, uint8_t* K, S2Header* hdr, uint32_t* done,
     const S2Entry* __restrict__ entries, const S2Task* __restrict__ tasks,
@@ -136,12 +148,11 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     constexpr int NT = NW * 64;
     constexpr int WV = 64 * U;                       // columns per wave
     constexpr int WCAP = NW * WV;                    // columns per task
-    // Per wave a ring of S2W_RING floats: a window holds WV + spread columns
-    // plus 3 of alignment slack and takes 2, 3 or 4 copies of 256 floats, so
-    // the ring has 5, 3 or 2 slots and the wave works 4, 2 or 1 rows ahead
-    // (chosen per task from the spread the pack kernel found for the group).
+    // Per wave a ring of RINGF floats: a window holds WV + spread columns plus
+    // 3 of alignment slack, in units of 128 floats; the ring has 5, 3 or 2
+    // slots and the wave works 4, 2 or 1 rows ahead (chosen per task from the
+    // spread the pack kernel found for the group).
     // DMAX: pad in front of a diagonal slot = largest shift inside a group.
-    constexpr int RINGF = S2W_RING;                  // floats per wave
     constexpr int DSLOTW = WCAP + DMAX + 4;          // floats per diagonal slot
     constexpr int LDSF = NW * RINGF > 2 * DSLOTW ? NW * RINGF : 2 * DSLOTW;
     constexpr float NINF = -INFINITY;
@@ -150,7 +161,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     constexpr int PAIR_TAB = 128 * R;                // entries: pairs below the group x rows
     constexpr bool PAIRS = R == 16 && (!STORE_K || (LDSF - 2 * DSLOTW) * 4 >= PAIR_TAB * 8);
     static_assert(R == 8 || R == 16, "one or two records per predecessor");
-    static_assert(NSLOT * 512 == S2W_RING, "five slots of the smallest window fill the ring");
+    static_assert(RINGF >= 5 * 3 * S2W_UNIT, "five slots of the smallest window fit the ring");
     static_assert(WV == 256, "the window sizes in stage2_common.h are for 256 columns per wave");
     static_assert(DMAX % 4 == 0, "diagonal slots stay 16-byte aligned");
     __shared__ __attribute__((aligned(16))) float lds[LDSF];
@@ -196,14 +207,17 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     const uint32_t need = (uint32_t)ent.prev2_cnt;
                     const uint32_t* flag = &done[ent.prev2];
                     const long long start = wall_clock64();
-                    while (ld_uniform(flag) < need) {
-                        if (ld_uniform(&hdr->error) != 0) { ok = 0; break; }
-                        if (wall_clock64() - start > wait_limit) {
-                            if (lane == 0)
-                                __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-                            ok = 0;
-                            break;
+                    for (uint32_t spin = 0; ld_uniform(flag) < need; ++spin) {
+                        // (the error word and the clock are looked at now and then only)
+                        if ((spin & 15u) == 15u) {
+                            if (ld_uniform(&hdr->error) != 0) { ok = 0; break; }
+                            if (wall_clock64() - start > wait_limit) {
+                                if (lane == 0)
+                                    __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+                                ok = 0;
+                                break;
+                            }
                         }
                         __builtin_amdgcn_s_sleep(2);
                     }
@@ -317,14 +331,18 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             }
         };
 
-        // Start the copy of the window of row i into ring slot `slot`: exactly
-        // NLD loads, every lane active.
-        auto issue_row = [&](auto nld_c, int i, int slot, int maxs, int mins) __attribute__((always_inline)) {
-            constexpr int NLD = decltype(nld_c)::value;
-            constexpr int SLOTF = NLD * 256;
+        // Start the copy of the window of row i into ring slot `slot` of KU units
+        // of 128 floats: exactly (KU + 1) / 2 copy instructions, whatever the row
+        // (whole copies of 256 floats by all lanes, and for an odd KU one of 128
+        // floats by the lower half of the wave).
+        auto issue_row = [&](auto ku_c, int i, int slot, int maxs, int mins) __attribute__((always_inline)) {
+            constexpr int KU = decltype(ku_c)::value;
+            constexpr int SLOTF = KU * S2W_UNIT;
+            constexpr int NFULL = KU / 2;
+            constexpr bool HALF = (KU & 1) != 0;
             const int lo = tW - maxs;
             const int lo4 = lo & ~3;                               // floor to a multiple of 4
-            const int n4 = (WV + maxs - mins + (lo - lo4) + 3) & ~3;   // cells needed, in floats
+            const int n4 = (WV + maxs - mins + (lo - lo4) + 3) & ~3;   // cells needed, in floats (<= SLOTF)
             const int last = min(tmaxg, lo4 + n4 - 4);             // last cell worth fetching
             const float* row = Mb + (size_t)i * P;
             float* dst = ring + slot * SLOTF;
@@ -334,19 +352,27 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 const char* base = (const char*)(row + lo4);
                 const unsigned lastoff = (unsigned)(last - lo4) * 4u;
 #pragma unroll
-                for (int k = 0; k < NLD; ++k) {
+                for (int k = 0; k < NFULL; ++k) {
                     const unsigned off = min((unsigned)(1024 * k + 16 * lane), lastoff);
                     __builtin_amdgcn_global_load_lds((const float*)(base + off),
                                                      (lds_void*)(dst + 256 * k), 16, 0,
                                                      DMA_AGENT_SCOPE);
                 }
+                if constexpr (HALF) {
+                    const unsigned off = min((unsigned)(1024 * NFULL + 16 * lane), lastoff);
+                    lds_load16_if(lane < 32, (const float*)(base + off), dst + 256 * NFULL);
+                }
             } else {
 #pragma unroll
-                for (int k = 0; k < NLD; ++k) {
+                for (int k = 0; k < NFULL; ++k) {
                     const int tp = min(lo4 + 256 * k + 4 * lane, last);
                     const float* src = tp < 0 ? ninf : row + tp;
                     __builtin_amdgcn_global_load_lds(src, (lds_void*)(dst + 256 * k), 16, 0,
                                                      DMA_AGENT_SCOPE);
+                }
+                if constexpr (HALF) {
+                    const int tp = min(lo4 + 256 * NFULL + 4 * lane, last);
+                    lds_load16_if(lane < 32, tp < 0 ? ninf : row + tp, dst + 256 * NFULL);
                 }
             }
         };
@@ -476,13 +502,13 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             }
         };
         // The same for a one-row task: only row `sub` of the group, at one shift.
-        auto relax_one = [&](int i, int slot) __attribute__((always_inline)) {   // (smallest window: 512 floats per slot)
+        auto relax_one = [&](int i, int slot, int slotf) __attribute__((always_inline)) {
             int w;
             float imp;
             one_row_of(i, w, imp);
             if (w < 0) return;
             const int delta = (tS - w) & 3;
-            const float* base = (const float*)(lbase + (slot * 512 + delta) * 4);
+            const float* base = (const float*)(lbase + (slot * slotf + delta) * 4);
             float cand[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) cand[u] = base[64 * u] + imp;
@@ -505,30 +531,34 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         auto wait_prev = [&]() __attribute__((always_inline)) {
             const uint32_t* flag = &done[prev];
             const long long start = wall_clock64();
-            while (ld_uniform(flag) < prev_cnt) {
-                if (ld_uniform(&hdr->error) != 0) break;
-                if (wall_clock64() - start > wait_limit) {
-                    if (lane == 0)
-                        __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-                    break;
+            for (uint32_t spin = 0; ld_uniform(flag) < prev_cnt; ++spin) {
+                if ((spin & 15u) == 15u) {
+                    if (ld_uniform(&hdr->error) != 0) break;
+                    if (wall_clock64() - start > wait_limit) {
+                        if (lane == 0)
+                            __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
                 }
                 __builtin_amdgcn_s_sleep(2);
             }
         };
 
         // whole group, smallest windows, table of M below 4 GB: two predecessors per step
-        const bool pair_task = PAIRS && full && s2_window_loads(spread) <= 2 &&
+        const bool pair_task = PAIRS && full && s2_ring_slots(RINGF, spread) == 5 &&
                                (long long)ld * P < (1LL << 30) && P < (1 << 20);
         // ---------------- off-diagonal part: rows i < ilimit ----------------
-        // The part itself, compiled once per window size: NLD copies of 256 floats
-        // per row, S2W_RING / (256 NLD) ring slots, D = slots - 1 rows ahead.
-        auto offdiag = [&](auto nld_c) __attribute__((always_inline)) {
-            constexpr int NLD = decltype(nld_c)::value;
-            constexpr int SLOTF = NLD * 256;
-            constexpr int NSL = S2W_RING / SLOTF;
+        // The part itself, compiled once per ring geometry: NSL slots of KU units,
+        // NLD copy instructions per row, D = NSL - 1 rows ahead.
+        auto offdiag = [&](auto nld_c, auto nsl_c) __attribute__((always_inline)) {
+            constexpr int KU = decltype(nld_c)::value;
+            constexpr int NSL = decltype(nsl_c)::value;
+            constexpr int NLD = (KU + 1) / 2;
+            constexpr int SLOTF = KU * S2W_UNIT;
             constexpr int D = NSL - 1;
-            static_assert(D >= 1 && D * NLD <= 8, "the counted wait covers at most 8 loads");
+            static_assert(NSL * SLOTF <= RINGF, "the slots fit the ring");
+            static_assert(D >= 1 && D * NLD <= 10, "the counted wait covers at most 10 loads");
 #pragma unroll
             for (int d = 0; d < D; ++d)
                 if (d < ilimit) {
@@ -539,13 +569,12 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 }
             int slot = 0;                              // ring slot of row i
             int ahead = D;                             // ring slot of row i + D
-            if constexpr (PAIRS && NLD == 2) {
+            if constexpr (PAIRS && NSL == 5) {
               if (pair_task) {
                 // Two predecessor rows per step.  Row r sits in ring slot r mod 5;
                 // while rows a and a + 1 are relaxed the copies of a + 2, a + 3 and
                 // a + 4 are in flight.  The window of row r + 4 is in the record of
                 // row r (the pack kernel looks 4 rows ahead for these groups).
-                static_assert(NSL == 5 && D == 4, "pairs need five slots");
                 S2Rec A[H], Bn[H];
 #pragma unroll
                 for (int h = 0; h < H; ++h) {
@@ -644,7 +673,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     ahead = slot;
                     slot = slot + 1 == NSL ? 0 : slot + 1;
                 }
-            } else if constexpr (NLD == 2) {
+            } else if constexpr (NSL == 5) {
                 // (a one-row task has one shift per predecessor: the smallest window)
                 for (int i = 0; i < ilimit; ++i) {
                     if (i + D < ilimit) {
@@ -657,17 +686,21 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                         wait_vm(0);
                     }
                     asm volatile("" ::: "memory");
-                    relax_one(i, slot);
+                    relax_one(i, slot, SLOTF);
                     ahead = slot;
                     slot = slot + 1 == NSL ? 0 : slot + 1;
                 }
             }
         };
         if (!wave_idle) {
-            const int nld = s2_window_loads(full ? spread : 0);   // copies of 256 floats per row: 2..4
-            if (nld <= 2) offdiag(std::integral_constant<int, 2>{});
-            else if (nld == 3) offdiag(std::integral_constant<int, 3>{});
-            else offdiag(std::integral_constant<int, 4>{});
+            // as many slots as hold the windows of the task: 5, 3 or 2, each as large as the ring allows
+            constexpr int U5 = s2_slot_units_max(RINGF, 5), U3 = s2_slot_units_max(RINGF, 3),
+                          U2 = s2_slot_units_max(RINGF, 2);
+            const int need = s2_units_needed(full ? spread : 0);
+            using std::integral_constant;
+            if (need <= U5) offdiag(integral_constant<int, U5>{}, integral_constant<int, 5>{});
+            else if (need <= U3) offdiag(integral_constant<int, U3>{}, integral_constant<int, 3>{});
+            else offdiag(integral_constant<int, U2>{}, integral_constant<int, 2>{});
         }
         if (!full) {
             // ---------------- a one-row task only has its row to store ----------------
@@ -766,7 +799,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
 
 // gated / want / decide: see launch_stage2_prepare; the main kernel is gated on
 // `want` when either is set
-template <int R, int NW, int NSLOT, int DMAX, int WPE>
+template <int R, int NW, int RINGF, int DMAX, int WPE>
 static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
                                   uint8_t* K, void* workspace, int num_cu, hipStream_t st,
                                   bool gated = false, uint32_t want = 0, bool decide = false)
@@ -787,8 +820,8 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
     // group runs row by row), and the chain of shifts must fit the pad in front
     // of a diagonal slot
     const int gmax = std::min(DMAX, WCAP / 2);
-    hipError_t e = launch_stage2_prepare(B, L, P, R, Topt, I, M, K, workspace, gmax, S2W_MAX_SPREAD,
-                                         DMAX, WCAP, -(NSLOT - 1), st, gated, want, decide);
+    hipError_t e = launch_stage2_prepare(B, L, P, R, Topt, I, M, K, workspace, gmax, s2_max_spread(RINGF),
+                                         DMAX, WCAP, -4, RINGF, st, gated, want, decide);
     if (e != hipSuccess) return e;
     const S2Gate gate{gated || decide ? &hdr->choice : nullptr, want};
 
@@ -798,41 +831,39 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
     int grid = num_cu * wg_per_cu;
     // A table that fits one task per row group is B independent chains of
     // tasks.  Two workgroups per chain are what can work at once (one finishes a
-    // group while the next has started on the rows below it); more only wait,
-    // and once the chip is half full one per chain is faster.  Any number is
-    // safe: a ticket only ever waits for lower tickets.  Measured at L=53,
-    // P=1000: 512 instances 0.42 -> 0.26 ms, 256 instances 0.28 -> 0.22 ms.
+    // group while the next has started on the rows below it); more only wait.
+    // Any number is safe: a ticket only ever waits for lower tickets.
     if (P <= WCAP) {
         const long long n = B;
-        const long long fit = std::min(2 * n, std::max(n, (long long)grid / 2));
+        const long long fit = 2 * n;
         if (fit < grid) grid = (int)fit;
     }
     const long long wait_limit = 500000000LL;      // 5 s of the 100 MHz wall clock
     if (K)
-        hipLaunchKernelGGL((stage2_wave_kernel<R, NW, NSLOT, DMAX, WPE, true>), dim3(grid),
+        hipLaunchKernelGGL((stage2_wave_kernel<R, NW, RINGF, DMAX, WPE, true>), dim3(grid),
                            dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
                            infos, shifts, NQ, wait_limit, gate, Topt, I);
     else
-        hipLaunchKernelGGL((stage2_wave_kernel<R, NW, NSLOT, DMAX, WPE, false>), dim3(grid),
+        hipLaunchKernelGGL((stage2_wave_kernel<R, NW, RINGF, DMAX, WPE, false>), dim3(grid),
                            dim3(NW * 64), 0, st, B, L, P, M, K, hdr, done, entries, tasks, recs,
                            infos, shifts, NQ, wait_limit, gate, Topt, I);
     return hipGetLastError();
 }
 
-// groups of 8 rows (shapes 1-4) or 16 rows (5, 6, 8): waves per task, ring slots
-// (smallest window), largest shift inside a group, waves per SIMD
+// groups of 8 rows (shapes 1-4) or 16 rows (5, 6, 8): waves per task, floats of a
+// wave's ring, largest shift inside a group, waves per SIMD
 static hipError_t launch_wave_shape(int shape, int B, int L, int P, const int32_t* Topt, const float* I,
                                     float* M, uint8_t* K, void* workspace, int num_cu, hipStream_t st,
                                     bool gated, uint32_t want, bool decide)
 {
     switch (shape) {
-        case 1: return launch_wave_cfg<8, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
-        case 2: return launch_wave_cfg<8, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
-        case 3: return launch_wave_cfg<8, 2, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
-        case 4: return launch_wave_cfg<8, 1, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
-        case 5: return launch_wave_cfg<16, 4, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
-        case 6: return launch_wave_cfg<16, 8, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
-        case 8: return launch_wave_cfg<16, 16, 5, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 1: return launch_wave_cfg<8, 4, 1920, 764, 5>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 2: return launch_wave_cfg<8, 8, 1920, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 3: return launch_wave_cfg<8, 2, 1920, 764, 5>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 4: return launch_wave_cfg<8, 1, 1920, 764, 5>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 5: return launch_wave_cfg<16, 4, 2560, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 6: return launch_wave_cfg<16, 8, 2560, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
+        case 8: return launch_wave_cfg<16, 16, 2560, 764, 4>(B, L, P, Topt, I, M, K, workspace, num_cu, st, gated, want, decide);
         default: return hipErrorInvalidValue;
     }
 }

@@ -36,7 +36,7 @@ int main(int argc, char** argv)
     const hipError_t e = dpc::launch_stage2_wave(B, L, P, Topt.data(), I.data(), M, K, ws, 1, shape, nullptr);
     if (e != hipSuccess) { std::fprintf(stderr, "launch failed\n"); return 3; }
     if (std::getenv("EMU_DUMP_HEADER")) { for (int x = 0; x < 40; ++x) std::fprintf(stderr, "%08x ", ((uint32_t*)ws)[x]); std::fprintf(stderr, "\n"); }
-    if (((uint32_t*)ws)[1] != 0) { std::fprintf(stderr, "error word set\n"); return 4; }
+    if (((uint32_t*)ws)[dpc::S2_ERROR_WORD_OFFSET / 4] != 0) { std::fprintf(stderr, "error word set\n"); return 4; }
     f = std::fopen(argv[2], "wb");
     std::fwrite(M, 4, cells, f);
     std::fwrite(K, 1, cells, f);

@@ -193,3 +193,20 @@ inline void __builtin_amdgcn_global_load_lds(const void* src, void* ldsbase, int
     }
     std::memcpy(dst, src, (size_t)size);
 }
+
+namespace emu {
+// the same by the lanes for which `active` holds; every lane of the wave calls it
+inline void global_load_lds_if(bool active, const void* src, void* ldsbase, int size)
+{
+    wave_sync();
+    if (!active) return;
+    const int lane = (int)threadIdx.x & 63;
+    char* dst = (char*)ldsbase + lane * size;
+    check_global(src, (size_t)size, "global -> LDS source");
+    if (dst < g_lds_lo || dst + size > g_lds_hi) {
+        std::fprintf(stderr, "EMU: global -> LDS destination outside the LDS array\n");
+        std::abort();
+    }
+    std::memcpy(dst, src, (size_t)size);
+}
+}  // namespace emu
