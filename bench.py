@@ -48,8 +48,12 @@ VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9        # 39.3e12
 # launch (FETCH_SIZE / WRITE_SIZE runs) and VALU instructions issued per
 # candidate (SQ_INSTS_VALU x 64 lanes / exact candidates), keyed by config.
 PROFILED = {
-    5: {"file": "profiles/stage2_wave_kernel_cfg5.md", "traffic_bytes": 6.06e9 + 1.181e9,
-        "issued_valu_per_relax": 3.98},
+    3: {"file": "profiles/stage2_cfg3.md", "traffic_bytes": 0.563e9 + 0.293e9,
+        "issued_valu_per_relax": 5.00},
+    4: {"file": "profiles/stage2_cfg4.md", "traffic_bytes": 1.839e9,
+        "issued_valu_per_relax": 4.18},
+    5: {"file": "profiles/stage2_wave_kernel_cfg5.md", "traffic_bytes": 7.219e9,
+        "issued_valu_per_relax": 4.00},
 }
 
 
@@ -318,6 +322,10 @@ def main():
                 "frac": ops_per_relax * rate / VALU_PEAK_LANE_OPS,
                 "variant_floor_ops": fl, "frac_of_variant_floor": fl * rate / VALU_PEAK_LANE_OPS,
             }
+            if store_K and args.shape == 0 and cid in PROFILED:
+                per[str(cid)]["issued_valu_per_relax"] = PROFILED[cid]["issued_valu_per_relax"]
+                per[str(cid)]["traffic"] = PROFILED[cid]["traffic_bytes"]
+                per[str(cid)]["traffic_source"] = PROFILED[cid]["file"] + " (rocprofv3 --pmc, not this run)"
             if not args.no_cpu:
                 import oracle
                 secs, parity = oracle_leg(wc, np, oracle, cores, store_K)
