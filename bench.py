@@ -86,10 +86,21 @@ def time_workload(w, args, torch, api, np, steps, warmup, fused=False, graph=Fal
     """W untimed and K timed steps of the whole path; -> (ms per step by the host
     clock around the K steps, per-stage ms from events on the launch stream)."""
     buf, stream = w.buf, torch.cuda.current_stream()
+    one_launch = fused and 0 < len(w.qi) <= api.ONE_LAUNCH_QUERIES_PER_INSTANCE * w.cfg.B
 
     def step(ev=None):
         if ev:
             ev[0].record(stream)
+        if fused and one_launch:
+            # the whole path in one kernel: its time is reported as stage 2
+            if ev:
+                ev[1].record(stream)
+            api.dpc_solve_fused(w.Td, w.Id, buf.Topt, buf.split, buf.M, buf.K, w.qid, w.qtd, buf.A,
+                                buf.A_len, buf.S, buf.S_len, buf.obj, buf.lat, buf.status)
+            if ev:
+                ev[2].record(stream)
+                ev[3].record(stream)
+            return
         if fused:
             if ev:
                 ev[1].record(stream)         # (stage 1 runs inside the one kernel)
@@ -138,6 +149,15 @@ def time_workload(w, args, torch, api, np, steps, warmup, fused=False, graph=Fal
     seg = [[e[x].elapsed_time(e[x + 1]) for e in evs] for x in range(3)]
     stage_ms = {"stage1": float(np.mean(seg[0])), "stage2": float(np.mean(seg[1])),
                 "stage2_min": float(np.min(seg[1])), "backtrack": float(np.mean(seg[2]))}
+    # The same K steps once more without the per-stage events in the stream: on
+    # the small workloads the four event records of a step take as long as a kernel.
+    if not graph:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            step()
+        torch.cuda.synchronize()
+        stage_ms["step_without_events"] = (time.perf_counter() - t0) * 1e3 / steps
     return ms_step, stage_ms
 
 
@@ -196,8 +216,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="record the step into a HIP graph once and time its replays")
     ap.add_argument("--fused", action="store_true",
-                    help="stage 1 + stage 2 in one launch (dpc_stage12_fused; small instances: "
-                         "L <= 63, P <= 2048)")
+                    help="the single-launch path for small instances (L <= 63, P <= 2048): "
+                         "dpc_solve_fused when there are few queries per instance, else "
+                         "dpc_stage12_fused + dpc_backtrack")
     ap.add_argument("--sweep", action="store_true",
                     help="time a sweep over the normalisation constant alpha: shift, solve, "
                          "trade-off curves, set recovery, latency merged at A (cfg3 shape by default)")
@@ -332,6 +353,14 @@ def main():
                 per[str(cid)]["cpu_oracle_s"] = secs
                 per[str(cid)]["parity"] = parity
                 ok = ok and parity["mismatches"] == 0
+            if cid in (1, 2) and api.dpc_stage12_fused_supported(c.L, c.P):
+                # the single-launch path for small instances, timed and checked the same way
+                ms_f, st_f = time_workload(wc, args, torch, api, np, args.steps, args.warmup, fused=True)
+                per[str(cid)]["single_launch_path"] = {"ms_step": ms_f, "stage_ms": st_f}
+                if not args.no_cpu:
+                    _, parity_f = oracle_leg(wc, np, oracle, cores, store_K)
+                    per[str(cid)]["single_launch_path"]["parity"] = parity_f
+                    ok = ok and parity_f["mismatches"] == 0
             del wc
             torch.cuda.empty_cache()
         out["per_config"] = per

@@ -265,6 +265,23 @@ int dpc_stage12_fused(int32_t B, int32_t L, int32_t P, const int32_t *T, const f
                       int32_t *Topt, uint8_t *split, float *M, uint8_t *K, void *stream);
 
 /*
+ * dpc_solve_fused - the whole path (Algorithms 1 and 2 and the set recovery of
+ * dpc_backtrack) in ONE launch: dpc_stage12_fused, after which the workgroup of
+ * an instance goes on to answer the queries that name that instance, one wave
+ * per query at a time.  Outputs are those of dpc_stage12_fused followed by
+ * dpc_backtrack, bit for bit (a query that names no instance gets
+ * DPC_Q_BAD_QUERY as there).  It saves a launch when there are few queries
+ * per instance (one network, one budget: the paper's use); with many queries
+ * per instance the separate dpc_backtrack, which spreads them over the whole
+ * chip, is faster.  Shapes as for dpc_stage12_fused; Q >= 0 (0: no queries).
+ */
+int dpc_solve_fused(int32_t B, int32_t L, int32_t P, const int32_t *T, const float *I,
+                    int32_t *Topt, uint8_t *split, float *M, uint8_t *K, int32_t Q,
+                    const int32_t *q_inst, const int32_t *q_T0, int32_t *A, int32_t *A_len,
+                    int32_t *S, int32_t *S_len, float *obj, int32_t *lat, int32_t *status,
+                    void *stream);
+
+/*
  * ---- Steps around the solver in a sweep over hyper-parameters ----
  *
  * dpc_importance_shift - the normalisation of the paper's appendix "Evaluating

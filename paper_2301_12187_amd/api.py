@@ -25,7 +25,7 @@ EXPORTS = (
     "dpc_ext_importance_maxplus", "dpc_ext_workspace_bytes", "dpc_ext_knapsack",
     "dpc_ext_check", "dpc_ext_backtrack",
     "dpc_importance_shift", "dpc_front", "dpc_front_queries", "dpc_chain_latency",
-    "dpc_stage12_fused_supported", "dpc_stage12_fused",
+    "dpc_stage12_fused_supported", "dpc_stage12_fused", "dpc_solve_fused",
 )
 
 # exported for tests and measurements only (csrc/dpc_hooks.h), not part of include/dpc.h
@@ -375,6 +375,8 @@ def _load_fused():
         lib.dpc_stage12_fused_supported.restype = ctypes.c_int
         lib.dpc_stage12_fused.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         lib.dpc_stage12_fused.restype = ctypes.c_int
+        lib.dpc_solve_fused.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, i32] + [vp] * 10
+        lib.dpc_solve_fused.restype = ctypes.c_int
         lib._fused_ready = True
     return lib
 
@@ -395,8 +397,40 @@ def dpc_stage12_fused(T, I, Topt, split, M, K, stream=None):
         None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"), _stream(stream)))
 
 
-def solve_fused(T, I, q_inst, q_T0, buf: "Buffers", stream=None):
-    """dpc_stage12_fused + dpc_backtrack into the buffers of `buf`."""
+def dpc_solve_fused(T, I, Topt, split, M, K, q_inst, q_T0, A, A_len, S, S_len, obj, lat, status,
+                    stream=None):
+    """Stage 1, stage 2 and set recovery in one launch (small instances)."""
+    B, ld, _ = T.shape
+    L, P, Q = ld - 1, M.shape[2], q_inst.shape[0]
+    shp = (B, ld, ld)
+    i32 = torch.int32
+    _check(_load_fused().dpc_solve_fused(
+        B, L, P, _dev(T, i32, shp, "T"), _dev(I, torch.float32, shp, "I"),
+        _dev(Topt, i32, shp, "Topt"), _dev(split, torch.uint8, shp, "split"),
+        _dev(M, torch.float32, (B, ld, P), "M"),
+        None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"), Q,
+        _dev(q_inst, i32, (Q,), "q_inst"), _dev(q_T0, i32, (Q,), "q_T0"),
+        _dev(A, i32, (Q, L), "A"), _dev(A_len, i32, (Q,), "A_len"),
+        _dev(S, i32, (Q, L), "S"), _dev(S_len, i32, (Q,), "S_len"),
+        _dev(obj, torch.float32, (Q,), "obj"), _dev(lat, i32, (Q,), "lat"),
+        _dev(status, i32, (Q,), "status"), _stream(stream)))
+
+
+# queries per instance up to which the single launch beats a separate dpc_backtrack
+ONE_LAUNCH_QUERIES_PER_INSTANCE = 32
+
+
+def solve_fused(T, I, q_inst, q_T0, buf: "Buffers", stream=None, one_launch=None):
+    """The small-instance path into the buffers of `buf`: one launch (dpc_solve_fused)
+    when there are few queries per instance, else dpc_stage12_fused + dpc_backtrack.
+    one_launch: True / False to force either."""
+    Q = q_inst.shape[0]
+    if one_launch is None:
+        one_launch = 0 < Q <= ONE_LAUNCH_QUERIES_PER_INSTANCE * T.shape[0]
+    if one_launch and Q > 0:
+        dpc_solve_fused(T, I, buf.Topt, buf.split, buf.M, buf.K, q_inst, q_T0, buf.A, buf.A_len,
+                        buf.S, buf.S_len, buf.obj, buf.lat, buf.status, stream)
+        return
     dpc_stage12_fused(T, I, buf.Topt, buf.split, buf.M, buf.K, stream)
     dpc_backtrack(buf.Topt, buf.split, I, buf.M, buf.K, q_inst, q_T0, buf.A, buf.A_len, buf.S,
                   buf.S_len, buf.obj, buf.lat, buf.status, stream)

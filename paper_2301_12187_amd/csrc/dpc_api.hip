@@ -239,8 +239,27 @@ int dpc_stage12_fused(int32_t B, int32_t L, int32_t P, const int32_t* T, const f
     const int lds = lds_per_workgroup();
     if (lds <= 0) return DPC_ERR_HIP;
     if (!dpc::fused_small_supported(L, P, lds)) return DPC_ERR_SHAPE;
-    hipError_t e = dpc::launch_fused_small(B, L, P, T, I, Topt, split, M, K, lds,
-                                           (hipStream_t)stream);
+    hipError_t e = dpc::launch_fused_small(B, L, P, T, I, Topt, split, M, K, lds, 0, nullptr, nullptr,
+                                           nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                           nullptr, (hipStream_t)stream);
+    return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+
+int dpc_solve_fused(int32_t B, int32_t L, int32_t P, const int32_t* T, const float* I, int32_t* Topt,
+                    uint8_t* split, float* M, uint8_t* K, int32_t Q, const int32_t* q_inst,
+                    const int32_t* q_T0, int32_t* A, int32_t* A_len, int32_t* S, int32_t* S_len,
+                    float* obj, int32_t* lat, int32_t* status, void* stream)
+{
+    if (Q < 0) return DPC_ERR_SHAPE;
+    if (!T || !I || !Topt || !split || !M) return DPC_ERR_NULL;
+    if (Q > 0 && (!q_inst || !q_T0 || !A || !A_len || !S || !S_len || !obj || !lat || !status))
+        return DPC_ERR_NULL;
+    if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
+    const int lds = lds_per_workgroup();
+    if (lds <= 0) return DPC_ERR_HIP;
+    if (!dpc::fused_small_supported(L, P, lds)) return DPC_ERR_SHAPE;
+    hipError_t e = dpc::launch_fused_small(B, L, P, T, I, Topt, split, M, K, lds, Q, q_inst, q_T0, A,
+                                           A_len, S, S_len, obj, lat, status, (hipStream_t)stream);
     return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
 }
 

@@ -46,8 +46,12 @@ hipError_t launch_ext_backtrack(int B, int L, int P, const int32_t* Topt, const 
 
 // stage 1 + stage 2 in one launch for small instances; lds_limit = LDS bytes a workgroup may use
 bool fused_small_supported(int L, int P, int lds_limit);
+// Q > 0: the queries are answered in the same launch (each by the workgroup of its instance)
 hipError_t launch_fused_small(int B, int L, int P, const int32_t* T, const float* I, int32_t* Topt,
-                              uint8_t* split, float* M, uint8_t* K, int lds_limit, hipStream_t st);
+                              uint8_t* split, float* M, uint8_t* K, int lds_limit, int Q,
+                              const int32_t* q_inst, const int32_t* q_T0, int32_t* A, int32_t* A_len,
+                              int32_t* S, int32_t* S_len, float* obj, int32_t* lat, int32_t* status,
+                              hipStream_t st);
 
 // sweep steps: importance normalisation, trade-off curve, latency of a given merge set
 hipError_t launch_importance_shift(int B, int L, int F, int n_alpha, const float* I_raw,

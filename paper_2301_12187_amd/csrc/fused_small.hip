@@ -16,6 +16,13 @@
 //     at a time, started before the work on the resident rows.
 // A row costs one barrier.  Candidates are visited in ascending i and replace
 // the maximum only when strictly greater: the lowest arg-max is kept.
+//
+// With a query list (dpc_solve_fused) the workgroup goes on, in the same
+// launch, to recover the sets of the queries that name its instance: its waves
+// share the list in chunks of 64 queries, a lane per query finds the ones that
+// are the workgroup's, and the wave walks them one after the other
+// (backtrack_walk.h) through tables that the workgroup itself has just written.
+#include "backtrack_walk.h"
 #include "stage1_row.h"
 #include "stage2_common.h"
 
@@ -37,16 +44,32 @@ inline int lds_address(char* p) { return (int)(p - emu::g_dyn_lds); }
 #endif
 
 constexpr int FS_RING = 3;                      // LDS slots shared by the rows past the resident ones
+constexpr int FS_LIST = 64;                     // entries of a wave's set lists (L <= 63)
+constexpr int FS_LIST_BYTES = 16 * 2 * FS_LIST * 4;   // static LDS of the query phase: 16 waves, two lists
+
+// the query list of dpc_solve_fused (Q == 0: none)
+struct FsQueries {
+    int Q;
+    const int32_t* q_inst;
+    const int32_t* q_T0;
+    int32_t* A;
+    int32_t* A_len;
+    int32_t* S;
+    int32_t* S_len;
+    float* obj;
+    int32_t* lat;
+    int32_t* status;
+};
 
 // NR: rows of M that stay in LDS for good (rows 0 .. NR-1).  When NR < L+1 the
 // rows from NR on share FS_RING more slots, row i in slot NR + (i - NR) % 3: a
 // target row j reads rows j-1 and j-2 there (the third slot is the one row j
 // itself is written to) and the rows NR .. j-3 from the output array in global
 // memory.
-template <int U, bool STORE_K>
+template <int U, bool STORE_K, bool QUERIES>
 __global__ __launch_bounds__(1024) void fused_small_kernel(
-    int L, int P, int NR, const int32_t* __restrict__ T, const float* __restrict__ I,
-    int32_t* __restrict__ Topt, uint8_t* __restrict__ split, float* M, uint8_t* K)
+    int B, int L, int P, int NR, const int32_t* __restrict__ T, const float* __restrict__ I,
+    int32_t* Topt, uint8_t* split, float* M, uint8_t* K, FsQueries qs)
 {
 #ifndef DPC_HOST_EMU
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -228,6 +251,32 @@ __global__ __launch_bounds__(1024) void fused_small_kernel(
         }
         __syncthreads();
     }
+
+    if constexpr (QUERIES) {
+        // ---------------- set recovery for the queries of this instance ----------------
+        // Every wave has waited for its stores (the tables are complete at the
+        // level all compute units share) before any wave reads them back.
+        __shared__ int32_t lists[16][2][FS_LIST];
+        wait_vm(0);
+        __syncthreads();
+        const int nchunks = (qs.Q + 63) / 64;
+        for (int c = wave; c < nchunks; c += nw) {
+            const int q = c * 64 + lane;
+            const int qb = q < qs.Q ? qs.q_inst[q] : -2;
+            // a query that names no instance is answered ("bad query") by workgroup 0
+            const bool mine = q < qs.Q && (qb == b || (b == 0 && (qb < 0 || qb >= B)));
+            unsigned long long todo = __ballot(mine);
+            while (todo != 0) {
+                const int l = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const int qq = c * 64 + l;
+                backtrack_query<true>(qq, bt_uniform(qs.q_inst[qq]), bt_uniform(qs.q_T0[qq]), B, L, P,
+                                      Topt, split, I, M, STORE_K ? K : nullptr, qs.A, qs.A_len, qs.S,
+                                      qs.S_len, qs.obj, qs.lat, qs.status, lists[wave][0],
+                                      lists[wave][1], lane);
+            }
+        }
+    }
 }
 
 // LDS bytes with `nslots` slots for rows of M (their space also holds the copy
@@ -250,31 +299,42 @@ static int fs_slots(int L, int P, int lds_limit)
 bool fused_small_supported(int L, int P, int lds_limit)
 {
     if (L < 1 || L > 63 || P < 1 || P > 2048) return false;
+    lds_limit -= FS_LIST_BYTES;                         // (the query phase's lists are static LDS)
     const int n = fs_slots(L, P, lds_limit);
     // every row resident, or at least one resident row and the shared slots
     return (n == L + 1 || n >= 1 + FS_RING) && fs_lds_bytes(L, P, n) <= (size_t)lds_limit;
 }
 
+// Q == 0: stage 1 and stage 2 only; otherwise the queries are answered in the same launch
 hipError_t launch_fused_small(int B, int L, int P, const int32_t* T, const float* I, int32_t* Topt,
-                              uint8_t* split, float* M, uint8_t* K, int lds_limit, hipStream_t st)
+                              uint8_t* split, float* M, uint8_t* K, int lds_limit, int Q,
+                              const int32_t* q_inst, const int32_t* q_T0, int32_t* A, int32_t* A_len,
+                              int32_t* S, int32_t* S_len, float* obj, int32_t* lat, int32_t* status,
+                              hipStream_t st)
 {
     if (!fused_small_supported(L, P, lds_limit)) return hipErrorInvalidValue;
+    lds_limit -= FS_LIST_BYTES;
     const int nslots = fs_slots(L, P, lds_limit);
     const int NR = nslots == L + 1 ? nslots : nslots - FS_RING;
     const size_t lds = fs_lds_bytes(L, P, nslots);
     const int U = P > 1024 ? 2 : 1;
     // a thread per column (two when P > 1024), and at least a wave per source row of stage 1
     const int NT = std::min(1024, std::max(((P + U - 1) / U + 63) / 64 * 64, 64 * (L + 1)));
+    const FsQueries qs{Q, q_inst, q_T0, A, A_len, S, S_len, obj, lat, status};
     auto go = [&](auto kernel) {
         // (more than 64 KB of dynamic LDS has to be asked for)
         hipError_t e = hipFuncSetAttribute((const void*)kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kernel, dim3(B), dim3(NT), lds, st, L, P, NR, T, I, Topt, split, M, K);
+        hipLaunchKernelGGL(kernel, dim3(B), dim3(NT), lds, st, B, L, P, NR, T, I, Topt, split, M, K, qs);
         return hipGetLastError();
     };
-    if (U == 1) return K ? go(fused_small_kernel<1, true>) : go(fused_small_kernel<1, false>);
-    return K ? go(fused_small_kernel<2, true>) : go(fused_small_kernel<2, false>);
+    if (Q > 0) {
+        if (U == 1) return K ? go(fused_small_kernel<1, true, true>) : go(fused_small_kernel<1, false, true>);
+        return K ? go(fused_small_kernel<2, true, true>) : go(fused_small_kernel<2, false, true>);
+    }
+    if (U == 1) return K ? go(fused_small_kernel<1, true, false>) : go(fused_small_kernel<1, false, false>);
+    return K ? go(fused_small_kernel<2, true, false>) : go(fused_small_kernel<2, false, false>);
 }
 
 }  // namespace dpc

@@ -8,7 +8,7 @@ from paper_2301_12187_amd import api
 from helpers import bits
 
 
-def run_gpu(T, I, P, q_inst, q_T0, store_K=True, shape=0, fused=False):
+def run_gpu(T, I, P, q_inst, q_T0, store_K=True, shape=0, fused=False, one_launch=None):
     """numpy in -> dict of numpy outputs from the HIP path.  shape: 0 = the library's own
     choice of stage-2 kernel, else a fixed one through the test hook (csrc/dpc_hooks.h)."""
     B, ld, _ = T.shape
@@ -28,7 +28,7 @@ def run_gpu(T, I, P, q_inst, q_T0, store_K=True, shape=0, fused=False):
     buf.A.fill_(-9)
     buf.S.fill_(-9)
     if fused:                          # stage 1 + stage 2 in one launch, then set recovery
-        api.solve_fused(Td, Id, qi, qt, buf)
+        api.solve_fused(Td, Id, qi, qt, buf, one_launch=one_launch)
     else:
         api.solve(Td, Id, qi, qt, buf, shape=shape)
         api.dpc_stage2_check(buf.workspace)

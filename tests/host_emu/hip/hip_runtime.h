@@ -169,6 +169,19 @@ inline int __shfl(int v, int src, int)
 
 inline int __builtin_amdgcn_readlane(int v, int src) { return __shfl(v, src, 64); }
 
+// mask of the lanes of the wave for which `p` holds; every lane of the wave calls it
+inline unsigned long long __ballot(bool p)
+{
+    const int t = (int)threadIdx.x;
+    emu::g_exchange[t] = p ? 1 : 0;
+    wave_sync();
+    unsigned long long m = 0;
+    for (int l = 0; l < 64 && (t & ~63) + l < (int)blockDim.x; ++l)
+        if (emu::g_exchange[(t & ~63) + l]) m |= 1ull << l;
+    wave_sync();
+    return m;
+}
+
 // value of lane (lane ^ d) of the same wave; every lane of the wave calls it
 inline int __shfl_xor(int v, int d, int)
 {

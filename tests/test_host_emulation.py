@@ -127,13 +127,21 @@ def test_windows_wider_than_the_smallest_ring_slot(emu, tmp_path, shape, lo, hi,
 # ---- the single-launch kernel for small instances (stage 1 + stage 2) ----
 
 def _run_fused(emu_fused, tmp_path, T, I, P, lds_limit):
+    """Stage 1, stage 2 and, in the same launch, set recovery at four budgets per
+    instance plus one query that names no instance."""
     B, ld, _ = T.shape
+    L = ld - 1
     Topt, split, M, K = oracle.solve_batch(T, I, P, want_K=True, threads=4)
+    qi = np.concatenate([np.repeat(np.arange(B, dtype=np.int32), 4), [-1]]).astype(np.int32)
+    qt = np.concatenate([np.tile(np.array([0, P // 3, P // 2, P - 1], np.int32), B), [0]]).astype(np.int32)
+    Q = len(qi)
     fin, fout = str(tmp_path / "fin.bin"), str(tmp_path / "fout.bin")
     with open(fin, "wb") as f:
-        np.array([B, ld - 1, P, lds_limit], np.int32).tofile(f)
+        np.array([B, L, P, lds_limit, Q], np.int32).tofile(f)
         T.astype(np.int32).tofile(f)
         I.astype(np.float32).tofile(f)
+        qi.tofile(f)
+        qt.tofile(f)
     r = subprocess.run([emu_fused, fin, fout], capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stderr[-4000:]
     raw = np.fromfile(fout, np.uint8)
@@ -142,10 +150,24 @@ def _run_fused(emu_fused, tmp_path, T, I, P, lds_limit):
     Te = raw[o:o + 4 * n2].view(np.int32).reshape(B, ld, ld); o += 4 * n2
     Se = raw[o:o + n2].reshape(B, ld, ld); o += n2
     Me = raw[o:o + 4 * n].view(np.float32).reshape(B, ld, P); o += 4 * n
-    Ke = raw[o:o + n].reshape(B, ld, P)
+    Ke = raw[o:o + n].reshape(B, ld, P); o += n
     assert (Te == Topt).all() and (Se == split).all()
     assert (Me.view(np.uint32) == M.view(np.uint32)).all()
     assert (Ke == K).all()
+    Ae = raw[o:o + 4 * Q * L].view(np.int32).reshape(Q, L); o += 4 * Q * L
+    Sse = raw[o:o + 4 * Q * L].view(np.int32).reshape(Q, L); o += 4 * Q * L
+    small = raw[o:o + 16 * Q].view(np.int32).reshape(4, Q); o += 16 * Q
+    obj = raw[o:o + 4 * Q].view(np.float32)
+    for q in range(Q - 1):
+        b = int(qi[q])
+        ref = oracle.backtrack(Topt[b], split[b], I[b], M[b], K[b], int(qt[q]))
+        assert small[3, q] == ref["status"] and small[0, q] == ref["A_len"] and small[1, q] == ref["S_len"]
+        assert small[2, q] == ref["lat"]
+        assert obj[q:q + 1].view(np.uint32)[0] == np.array([ref["obj"]], np.float32).view(np.uint32)[0]
+        if ref["status"] == 0:
+            assert list(Ae[q][:ref["A_len"]]) == list(ref["A"])
+            assert list(Sse[q][:ref["S_len"]]) == list(ref["S"])
+    assert small[3, Q - 1] == 2 and small[0, Q - 1] == -1 and small[2, Q - 1] == -1     # bad query
 
 
 # lds_limit: 160 KB keeps every row of these shapes in LDS; the small limits

@@ -90,6 +90,9 @@ def test_argument_errors_of_the_widened_entry_points():
     # single-launch path
     assert lib.dpc_stage12_fused(1, 4, 8, None, p, p, p, p, p, None) == NULL
     assert lib.dpc_stage12_fused(1, 300, 8, p, p, p, p, p, p, None) == SHAPE
+    assert lib.dpc_solve_fused(1, 4, 8, p, p, p, p, p, p, -1, *([p] * 9), None) == SHAPE
+    assert lib.dpc_solve_fused(1, 4, 8, p, p, p, p, p, p, 2, None, *([p] * 8), None) == NULL
+    assert lib.dpc_solve_fused(1, 300, 8, p, p, p, p, p, p, 0, *([None] * 9), None) == SHAPE
     assert lib.dpc_stage12_fused_supported(64, 100) == 0
     assert lib.dpc_stage12_fused_supported(10, 4096) == 0
 
