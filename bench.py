@@ -444,8 +444,9 @@ def bench_ext(args, np, torch, api, inputs):
 
 def bench_sweep(args, np, torch, api, inputs):
     """Sweep over the normalisation constant: one step = dpc_importance_shift (n_raw tables x
-    n_alpha constants -> B instances) + stage 1 + stage 2 + dpc_front + dpc_front_queries +
-    dpc_backtrack at every point of every trade-off curve + dpc_chain_latency at A."""
+    n_alpha constants -> B instances) + stage 1 (once per raw table: the copies share it) +
+    stage 2 + dpc_front + dpc_front_queries + dpc_backtrack at every point of every trade-off
+    curve + dpc_chain_latency at A."""
     cid = 3 if args.config == 5 else args.config
     cfg = inputs.CONFIGS[cid]
     dev = torch.device("cuda:0")
@@ -455,7 +456,10 @@ def bench_sweep(args, np, torch, api, inputs):
     n_raw = T0.shape[0]
     B = n_raw * n_alpha
     T = np.repeat(T0, n_alpha, axis=0)
-    Td = torch.from_numpy(T).to(dev)
+    Td = torch.from_numpy(T).to(dev)            # (per instance: dpc_chain_latency indexes it by query)
+    T0d = torch.from_numpy(T0).to(dev)
+    Topt = torch.empty((n_raw, cfg.L + 1, cfg.L + 1), dtype=torch.int32, device=dev)
+    split = torch.empty((n_raw, cfg.L + 1, cfg.L + 1), dtype=torch.uint8, device=dev)
     Ird = torch.from_numpy(I_raw).to(dev)
     ald = torch.from_numpy(alphas).to(dev)
     # one query per point of every curve; the list is built on the device, so its
@@ -479,12 +483,12 @@ def bench_sweep(args, np, torch, api, inputs):
     def step(ev=None):
         calls = [
             lambda: api.dpc_importance_shift(Ird, ald, Id),
-            lambda: api.dpc_stage1_minplus(Td, buf.Topt, buf.split),
-            lambda: api.dpc_stage2_knapsack(buf.Topt, Id, buf.M, buf.K, buf.workspace),
+            lambda: api.dpc_stage1_minplus(T0d, Topt, split),
+            lambda: api.dpc_stage2_knapsack_shared(n_alpha, Topt, Id, buf.M, buf.K, buf.workspace),
             lambda: api.dpc_front(buf.M, ft, fo, fl),
             lambda: api.dpc_front_queries(ft, fl, qid, qtd, qn),
-            lambda: api.dpc_backtrack(buf.Topt, buf.split, Id, buf.M, buf.K, qid, qtd, buf.A,
-                                      buf.A_len, buf.S, buf.S_len, buf.obj, buf.lat, buf.status),
+            lambda: api.dpc_backtrack_shared(n_alpha, Topt, split, Id, buf.M, buf.K, qid, qtd, buf.A,
+                                             buf.A_len, buf.S, buf.S_len, buf.obj, buf.lat, buf.status),
             lambda: api.dpc_chain_latency(Td, qid, buf.A, buf.A_len, latA),
         ]
         for x, call in enumerate(calls):

@@ -305,6 +305,28 @@ int dpc_importance_shift(int32_t B, int32_t L, int32_t F, int32_t n_alpha, const
                          const float *alpha, float *I_out, double *mean_out, void *stream);
 
 /*
+ * Shared stage-1 tables.  In a sweep over the normalisation constant the B
+ * instances are `share` consecutive copies of each network (instance x is
+ * network x / share, as dpc_importance_shift lays them out): their latency
+ * tables are the same, so stage 1 has to run once per network only.
+ * dpc_stage2_knapsack_shared and dpc_backtrack_shared are dpc_stage2_knapsack
+ * and dpc_backtrack with
+ *   Topt, split   in  [ceil(B / share)][L+1][L+1]: table x / share serves instance x
+ * and every other argument (I, M, K, the queries and the outputs, all per
+ * instance) unchanged.  share >= 1; share = 1 is the plain call.
+ */
+int dpc_stage2_knapsack_shared(int32_t B, int32_t L, int32_t P, int32_t share,
+                               const int32_t *Topt, const float *I, float *M, uint8_t *K,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+int dpc_backtrack_shared(int32_t B, int32_t L, int32_t P, int32_t share, const int32_t *Topt,
+                         const uint8_t *split, const float *I, const float *M,
+                         const uint8_t *K, int32_t Q, const int32_t *q_inst,
+                         const int32_t *q_T0, int32_t *A, int32_t *A_len, int32_t *S,
+                         int32_t *S_len, float *obj, int32_t *lat, int32_t *status,
+                         void *stream);
+
+/*
  * dpc_front - the latency/objective trade-off curve of an instance, read off
  * the last row of the table of Algorithm 2: the budgets t at which the optimum
  * of Eq. 4 improves, M[L][t] > M[L][t-1] (column -1 counting as -inf).  At

@@ -25,6 +25,7 @@ EXPORTS = (
     "dpc_ext_importance_maxplus", "dpc_ext_workspace_bytes", "dpc_ext_knapsack",
     "dpc_ext_check", "dpc_ext_backtrack",
     "dpc_importance_shift", "dpc_front", "dpc_front_queries", "dpc_chain_latency",
+    "dpc_stage2_knapsack_shared", "dpc_backtrack_shared",
     "dpc_stage12_fused_supported", "dpc_stage12_fused", "dpc_solve_fused",
 )
 
@@ -307,8 +308,47 @@ def _load_sweep():
         lib.dpc_front_queries.restype = ctypes.c_int
         lib.dpc_chain_latency.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
         lib.dpc_chain_latency.restype = ctypes.c_int
+        sz = ctypes.c_size_t
+        lib.dpc_stage2_knapsack_shared.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.dpc_stage2_knapsack_shared.restype = ctypes.c_int
+        lib.dpc_backtrack_shared.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, i32] + [vp] * 10
+        lib.dpc_backtrack_shared.restype = ctypes.c_int
         lib._sweep_ready = True
     return lib
+
+
+def dpc_stage2_knapsack_shared(share, Topt, I, M, K, workspace, stream=None):
+    """Stage 2 for B = I.shape[0] instances, instance x reading table x // share of Topt
+    (int32 [ceil(B/share)][L+1][L+1])."""
+    B, ld, _ = I.shape
+    P = M.shape[2]
+    nt = (B + share - 1) // share
+    _check(_load_sweep().dpc_stage2_knapsack_shared(
+        B, ld - 1, P, int(share), _dev(Topt, torch.int32, (nt, ld, ld), "Topt"),
+        _dev(I, torch.float32, (B, ld, ld), "I"), _dev(M, torch.float32, (B, ld, P), "M"),
+        None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"),
+        ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream)))
+
+
+def dpc_backtrack_shared(share, Topt, split, I, M, K, q_inst, q_T0, A, A_len, S, S_len, obj, lat,
+                         status, stream=None):
+    """dpc_backtrack with the stage-1 tables of network x // share serving instance x."""
+    B, ld, _ = I.shape
+    L, P, Q = ld - 1, M.shape[2], q_inst.shape[0]
+    nt = (B + share - 1) // share
+    if Q == 0:
+        return
+    i32 = torch.int32
+    _check(_load_sweep().dpc_backtrack_shared(
+        B, L, P, int(share), _dev(Topt, i32, (nt, ld, ld), "Topt"),
+        _dev(split, torch.uint8, (nt, ld, ld), "split"), _dev(I, torch.float32, (B, ld, ld), "I"),
+        _dev(M, torch.float32, (B, ld, P), "M"),
+        None if K is None else _dev(K, torch.uint8, (B, ld, P), "K"), Q,
+        _dev(q_inst, i32, (Q,), "q_inst"), _dev(q_T0, i32, (Q,), "q_T0"),
+        _dev(A, i32, (Q, L), "A"), _dev(A_len, i32, (Q,), "A_len"),
+        _dev(S, i32, (Q, L), "S"), _dev(S_len, i32, (Q,), "S_len"),
+        _dev(obj, torch.float32, (Q,), "obj"), _dev(lat, i32, (Q,), "lat"),
+        _dev(status, i32, (Q,), "status"), _stream(stream)))
 
 
 def dpc_importance_shift(I_raw, alpha, I_out, mean_out=None, stream=None):

@@ -42,7 +42,8 @@ __device__ __forceinline__ void backtrack_query(
     const uint8_t* __restrict__ split, const float* __restrict__ I, const float* M,
     const uint8_t* K, int32_t* __restrict__ A, int32_t* __restrict__ A_len,
     int32_t* __restrict__ S, int32_t* __restrict__ S_len, float* __restrict__ obj,
-    int32_t* __restrict__ lat, int32_t* __restrict__ status, int32_t* listA, int32_t* listS, int lane)
+    int32_t* __restrict__ lat, int32_t* __restrict__ status, int32_t* listA, int32_t* listS, int lane,
+    int share = 1)
 {
     int st = DPC_Q_OK;
     if (b < 0 || b >= B || T0 < 0 || T0 >= P) st = DPC_Q_BAD_QUERY;
@@ -54,8 +55,10 @@ __device__ __forceinline__ void backtrack_query(
     const uint8_t* Kb = nullptr;
     float top = -INFINITY;
     if (st == DPC_Q_OK) {
-        To = Topt + (size_t)b * ld * ld;
-        Sp = split + (size_t)b * ld * ld;
+        // (share > 1: instance b uses the stage-1 tables of network b / share)
+        const size_t tb = (size_t)(share > 1 ? b / share : b);
+        To = Topt + tb * ld * ld;
+        Sp = split + tb * ld * ld;
         Ib = I + (size_t)b * ld * ld;
         Mb = M + (size_t)b * ld * P;
         Kb = K ? K + (size_t)b * ld * P : nullptr;

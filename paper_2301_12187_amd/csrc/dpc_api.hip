@@ -62,7 +62,7 @@ bool ext_shape_ok(int B, int L, int P) { return L >= 1 && L <= DPC_EXT_MAX_L && 
 
 namespace dpc {
 
-int stage2_run(int B, int L, int P, const int32_t* Topt, const float* I, float* M, uint8_t* K,
+int stage2_run(int B, int L, int P, ToptRef Topt, const float* I, float* M, uint8_t* K,
                void* workspace, int shape, hipStream_t stream)
 {
     hipError_t e;
@@ -124,7 +124,18 @@ int dpc_stage2_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, co
     if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
     if (workspace_bytes < dpc_stage2_workspace_bytes(B, L, P) || ((uintptr_t)workspace & 255))
         return DPC_ERR_WORKSPACE;
-    return dpc::stage2_run(B, L, P, Topt, I, M, K, workspace, 0, (hipStream_t)stream);
+    return dpc::stage2_run(B, L, P, dpc::ToptRef{Topt, 1}, I, M, K, workspace, 0, (hipStream_t)stream);
+}
+
+int dpc_stage2_knapsack_shared(int32_t B, int32_t L, int32_t P, int32_t share, const int32_t* Topt,
+                               const float* I, float* M, uint8_t* K, void* workspace,
+                               size_t workspace_bytes, void* stream)
+{
+    if (!Topt || !I || !M || !workspace) return DPC_ERR_NULL;
+    if (!shape_ok(B, L, P) || share < 1) return DPC_ERR_SHAPE;
+    if (workspace_bytes < dpc_stage2_workspace_bytes(B, L, P) || ((uintptr_t)workspace & 255))
+        return DPC_ERR_WORKSPACE;
+    return dpc::stage2_run(B, L, P, dpc::ToptRef{Topt, share}, I, M, K, workspace, 0, (hipStream_t)stream);
 }
 
 int dpc_stage2_knapsack_shape(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const float* I,
@@ -138,7 +149,7 @@ int dpc_stage2_knapsack_shape(int32_t B, int32_t L, int32_t P, const int32_t* To
         return DPC_ERR_SHAPE;
     if (workspace_bytes < dpc_stage2_workspace_bytes(B, L, P) || ((uintptr_t)workspace & 255))
         return DPC_ERR_WORKSPACE;
-    return dpc::stage2_run(B, L, P, Topt, I, M, K, workspace, shape, (hipStream_t)stream);
+    return dpc::stage2_run(B, L, P, dpc::ToptRef{Topt, 1}, I, M, K, workspace, shape, (hipStream_t)stream);
 }
 
 int dpc_stage2_check(const void* workspace, void* stream)
@@ -152,21 +163,43 @@ int dpc_stage2_check(const void* workspace, void* stream)
     return word != 0 ? DPC_ERR_TIMEOUT : DPC_OK;
 }
 
-int dpc_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const uint8_t* split,
-                  const float* I, const float* M, const uint8_t* K, int32_t Q,
-                  const int32_t* q_inst, const int32_t* q_T0, int32_t* A, int32_t* A_len,
-                  int32_t* S, int32_t* S_len, float* obj, int32_t* lat, int32_t* status,
-                  void* stream)
+namespace {
+int backtrack_checked(int32_t B, int32_t L, int32_t P, int32_t share, const int32_t* Topt,
+                      const uint8_t* split, const float* I, const float* M, const uint8_t* K, int32_t Q,
+                      const int32_t* q_inst, const int32_t* q_T0, int32_t* A, int32_t* A_len,
+                      int32_t* S, int32_t* S_len, float* obj, int32_t* lat, int32_t* status,
+                      void* stream)
 {
-    if (Q < 0) return DPC_ERR_SHAPE;
+    if (Q < 0 || share < 1) return DPC_ERR_SHAPE;
     if (!shape_ok(B, L, P)) return DPC_ERR_SHAPE;
     if (Q == 0) return DPC_OK;
     if (!Topt || !split || !I || !M || !q_inst || !q_T0 || !A || !A_len || !S || !S_len || !obj ||
         !lat || !status)
         return DPC_ERR_NULL;
     hipError_t e = dpc::launch_backtrack(B, L, P, Topt, split, I, M, K, Q, q_inst, q_T0, A, A_len,
-                                         S, S_len, obj, lat, status, (hipStream_t)stream);
+                                         S, S_len, obj, lat, status, share, (hipStream_t)stream);
     return e == hipSuccess ? DPC_OK : DPC_ERR_HIP;
+}
+}  // namespace
+
+int dpc_backtrack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const uint8_t* split,
+                  const float* I, const float* M, const uint8_t* K, int32_t Q,
+                  const int32_t* q_inst, const int32_t* q_T0, int32_t* A, int32_t* A_len,
+                  int32_t* S, int32_t* S_len, float* obj, int32_t* lat, int32_t* status,
+                  void* stream)
+{
+    return backtrack_checked(B, L, P, 1, Topt, split, I, M, K, Q, q_inst, q_T0, A, A_len, S, S_len,
+                             obj, lat, status, stream);
+}
+
+int dpc_backtrack_shared(int32_t B, int32_t L, int32_t P, int32_t share, const int32_t* Topt,
+                         const uint8_t* split, const float* I, const float* M, const uint8_t* K,
+                         int32_t Q, const int32_t* q_inst, const int32_t* q_T0, int32_t* A,
+                         int32_t* A_len, int32_t* S, int32_t* S_len, float* obj, int32_t* lat,
+                         int32_t* status, void* stream)
+{
+    return backtrack_checked(B, L, P, share, Topt, split, I, M, K, Q, q_inst, q_T0, A, A_len, S,
+                             S_len, obj, lat, status, stream);
 }
 
 int dpc_ext_importance_maxplus(int32_t B, int32_t L, const float* I4, float* Iopt, uint8_t* bsplit,
@@ -197,7 +230,8 @@ int dpc_ext_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const
     float* Iv = (float*)(base + lay.iv_off);
     hipError_t e = dpc::launch_ext_expand(B, L, Topt, Iopt, Tv, Iv, (hipStream_t)stream);
     if (e != hipSuccess) return DPC_ERR_HIP;
-    return dpc::stage2_run(B, 2 * L + 2, P, Tv, Iv, D, Kx, base + lay.s2_off, 0, (hipStream_t)stream);
+    return dpc::stage2_run(B, 2 * L + 2, P, dpc::ToptRef{Tv, 1}, Iv, D, Kx, base + lay.s2_off, 0,
+                           (hipStream_t)stream);
 }
 
 int dpc_ext_check(int32_t B, int32_t L, int32_t P, const void* workspace, void* stream)

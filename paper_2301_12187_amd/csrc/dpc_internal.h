@@ -6,10 +6,23 @@
 
 namespace dpc {
 
+// The latency tables of a batch as stage 2 reads them: instance b uses table
+// b / share.  share > 1: consecutive instances are copies of one network with
+// different importances (a sweep over the normalisation constant) and share
+// the one table stage 1 computed for it.
+struct ToptRef {
+    const int32_t* base;
+    int share;
+    __host__ __device__ const int32_t* of(int b, int ld) const
+    {
+        return base + (size_t)(share > 1 ? b / share : b) * ld * ld;
+    }
+};
+
 // kernel launchers; each returns a hipError_t from the launch
 hipError_t launch_stage1(int B, int L, const int32_t* T, int32_t* Topt, uint8_t* split,
                          hipStream_t st);
-hipError_t launch_stage2_rows(int B, int L, int P, const int32_t* Topt, const float* I,
+hipError_t launch_stage2_rows(int B, int L, int P, ToptRef Topt, const float* I,
                               float* M, uint8_t* K, hipStream_t st);
 // zero `nwords` 32-bit words with a small kernel (safe to record into a HIP graph)
 hipError_t launch_clear_words(void* p, int nwords, hipStream_t st);
@@ -19,18 +32,18 @@ constexpr size_t S2_ERROR_WORD_OFFSET = 148;
 constexpr int S2_HEADER_WORDS = 64;
 // shape 0: task shape chosen from the problem size; otherwise a fixed one
 // (stage2_wave_shape_known), for tests and measurements
-hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
+hipError_t launch_stage2_wave(int B, int L, int P, ToptRef Topt, const float* I, float* M,
                               uint8_t* K, void* workspace, int num_cu, int shape, hipStream_t st);
 bool stage2_wave_shape_known(int shape);
 // Stage 2 on checked arguments with the kernel family `shape` selects (see
 // dpc_hooks.h; 0 = the default choice).  Returns a DPC_* code.
-int stage2_run(int B, int L, int P, const int32_t* Topt, const float* I, float* M, uint8_t* K,
+int stage2_run(int B, int L, int P, ToptRef Topt, const float* I, float* M, uint8_t* K,
                void* workspace, int shape, hipStream_t st);
 hipError_t launch_backtrack(int B, int L, int P, const int32_t* Topt, const uint8_t* split,
                             const float* I, const float* M, const uint8_t* K, int Q,
                             const int32_t* q_inst, const int32_t* q_T0, int32_t* A,
                             int32_t* A_len, int32_t* S, int32_t* S_len, float* obj,
-                            int32_t* lat, int32_t* status, hipStream_t st);
+                            int32_t* lat, int32_t* status, int share, hipStream_t st);
 
 // extended solver (Appendix B): Algorithm 3, the virtual tables of Algorithm 4, set recovery
 hipError_t launch_ext_iopt(int B, int L, const float* I4, float* Iopt, uint8_t* bsplit,

@@ -98,7 +98,7 @@ S2Layout s2_layout(int B, int L, int P, int R);
 // choice word is set to 1 if more than 2 % of the groups have to run row by
 // row (so that a second, gated preparation with smaller groups takes over),
 // else to 0; the layout kernel that follows is then gated on 0.
-hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt, const float* I,
+hipError_t launch_stage2_prepare(int B, int L, int P, int R, ToptRef Topt, const float* I,
                                  float* M, uint8_t* K, void* workspace, int gmax, int dspread,
                                  int dpad, int wcap, int ahead, int ringf, hipStream_t st,
                                  bool gated = false, uint32_t want = 0, bool decide = false);

@@ -71,7 +71,7 @@ hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
 // every shift inside the group fits dpad and g <= gmax, else -1 (row by row).
 template <int R>
 __global__ __launch_bounds__(256) void stage2_pack_kernel(
-    int L, int P, int NQ, const int32_t* __restrict__ Topt, const float* __restrict__ I,
+    int L, int P, int NQ, ToptRef Topt, const float* __restrict__ I,
     S2Rec* __restrict__ recs, S2Info* __restrict__ infos, S2Shift* __restrict__ shifts,
     int32_t* __restrict__ groups, int gmax, int dspread, int dpad, int wcap, int ahead, int ringf,
     float* __restrict__ M, uint8_t* __restrict__ K, S2Gate gate, uint32_t* __restrict__ hdr_words,
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     const int b = blockIdx.y;
     const int j0 = s2_group_first_row(L, R, q);
     const int hq = s2_group_rows(L, R, q);
-    const int32_t* To = Topt + (size_t)b * ld * ld;
+    const int32_t* To = Topt.of(b, ld);
     const float* Ib = I + (size_t)b * ld * ld;
     if (i == 0) spread = 0;
     __syncthreads();
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     }
 }
 
-hipError_t launch_stage2_prepare(int B, int L, int P, int R, const int32_t* Topt, const float* I,
+hipError_t launch_stage2_prepare(int B, int L, int P, int R, ToptRef Topt, const float* I,
                                  float* M, uint8_t* K, void* workspace, int gmax, int dspread,
                                  int dpad, int wcap, int ahead, int ringf, hipStream_t st, bool gated,
                                  uint32_t want, bool decide)

@@ -14,14 +14,14 @@ namespace dpc {
 constexpr int S2R_THREADS = 256;
 
 __global__ __launch_bounds__(S2R_THREADS) void stage2_row_kernel(
-    int L, int P, int j, const int32_t* __restrict__ Topt, const float* __restrict__ I,
+    int L, int P, int j, ToptRef Topt, const float* __restrict__ I,
     float* M, uint8_t* K)
 {
     const int t = blockIdx.x * S2R_THREADS + threadIdx.x;
     const int b = blockIdx.y;
     if (t >= P) return;
     const int ld = L + 1;
-    const int32_t* To = Topt + (size_t)b * ld * ld;
+    const int32_t* To = Topt.of(b, ld);
     const float* Ib = I + (size_t)b * ld * ld;
     float* Mb = M + (size_t)b * ld * P;
 
@@ -39,7 +39,7 @@ __global__ __launch_bounds__(S2R_THREADS) void stage2_row_kernel(
     if (K) K[((size_t)b * ld + j) * P + t] = (uint8_t)arg;
 }
 
-hipError_t launch_stage2_rows(int B, int L, int P, const int32_t* Topt, const float* I,
+hipError_t launch_stage2_rows(int B, int L, int P, ToptRef Topt, const float* I,
                               float* M, uint8_t* K, hipStream_t st)
 {
     dim3 grid((P + S2R_THREADS - 1) / S2R_THREADS, B);

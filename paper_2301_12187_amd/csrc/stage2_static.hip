@@ -49,5 +49,5 @@ extern "C" int dpc_stage2_knapsack_static(int32_t B, int32_t L, int32_t P, const
     if (rc != DPC_OK) return rc;
     // the preparation kernels clear the header and the counters they use, so
     // what the previous call left in the array does not matter
-    return dpc::stage2_run(B, L, P, Topt, I, M, K, ws, 0, (hipStream_t)stream);
+    return dpc::stage2_run(B, L, P, dpc::ToptRef{Topt, 1}, I, M, K, ws, 0, (hipStream_t)stream);
 }

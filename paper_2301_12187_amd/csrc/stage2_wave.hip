@@ -140,7 +140,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     const S2Entry* __restrict__ entries, const S2Task* __restrict__ tasks,
     const S2Rec* __restrict__ recs, const S2Info* __restrict__ infos,
     const S2Shift* __restrict__ shifts, int NQ, long long wait_limit, S2Gate gate,
-    const int32_t* __restrict__ Topt, const float* __restrict__ I)
+    ToptRef Topt, const float* __restrict__ I)
 {
     if (s2_gate_closed(gate)) return;                // (another shape was chosen for this call)
     constexpr int U = 4;                             // columns per lane: one arg-max byte each
@@ -715,7 +715,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 if (pair_task) {
                     // operands of the even rows below the group, behind the two slots
                     PairOp* tab = (PairOp*)(lds + 2 * DSLOTW);
-                    const int32_t* To = Topt + (size_t)b * ld * ld;
+                    const int32_t* To = Topt.of(b, ld);
                     const float* Ib = I + (size_t)b * ld * ld;
                     const int nent = ((j0 + 1) >> 1) * R;          // pairs (2c, 2c + 1) with 2c < j0
                     constexpr int TRIPS = (PAIR_TAB + NT - 1) / NT;
@@ -800,7 +800,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
 // gated / want / decide: see launch_stage2_prepare; the main kernel is gated on
 // `want` when either is set
 template <int R, int NW, int RINGF, int DMAX, int WPE>
-static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
+static hipError_t launch_wave_cfg(int B, int L, int P, ToptRef Topt, const float* I, float* M,
                                   uint8_t* K, void* workspace, int num_cu, hipStream_t st,
                                   bool gated = false, uint32_t want = 0, bool decide = false)
 {
@@ -852,7 +852,7 @@ static hipError_t launch_wave_cfg(int B, int L, int P, const int32_t* Topt, cons
 
 // groups of 8 rows (shapes 1-4) or 16 rows (5, 6, 8): waves per task, floats of a
 // wave's ring, largest shift inside a group, waves per SIMD
-static hipError_t launch_wave_shape(int shape, int B, int L, int P, const int32_t* Topt, const float* I,
+static hipError_t launch_wave_shape(int shape, int B, int L, int P, ToptRef Topt, const float* I,
                                     float* M, uint8_t* K, void* workspace, int num_cu, hipStream_t st,
                                     bool gated, uint32_t want, bool decide)
 {
@@ -872,7 +872,7 @@ bool stage2_wave_shape_known(int shape) { return (shape >= 1 && shape <= 6) || s
 
 // shape 0: chosen from the problem size (below); otherwise one of the task
 // shapes of launch_wave_shape, whatever the size (tests and measurements)
-hipError_t launch_stage2_wave(int B, int L, int P, const int32_t* Topt, const float* I, float* M,
+hipError_t launch_stage2_wave(int B, int L, int P, ToptRef Topt, const float* I, float* M,
                               uint8_t* K, void* workspace, int num_cu, int shape, hipStream_t st)
 {
     // a window cell may read up to three floats past the end of a row

@@ -33,7 +33,7 @@ int main(int argc, char** argv)
     emu::register_region(ws, wsb, "workspace");
     emu::g_lds_lo = nullptr;
     emu::g_lds_hi = (const char*)~(uintptr_t)0;
-    const hipError_t e = dpc::launch_stage2_wave(B, L, P, Topt.data(), I.data(), M, K, ws, 1, shape, nullptr);
+    const hipError_t e = dpc::launch_stage2_wave(B, L, P, dpc::ToptRef{Topt.data(), 1}, I.data(), M, K, ws, 1, shape, nullptr);
     if (e != hipSuccess) { std::fprintf(stderr, "launch failed\n"); return 3; }
     if (std::getenv("EMU_DUMP_HEADER")) { for (int x = 0; x < 40; ++x) std::fprintf(stderr, "%08x ", ((uint32_t*)ws)[x]); std::fprintf(stderr, "\n"); }
     if (((uint32_t*)ws)[dpc::S2_ERROR_WORD_OFFSET / 4] != 0) { std::fprintf(stderr, "error word set\n"); return 4; }

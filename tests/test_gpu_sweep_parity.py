@@ -96,6 +96,50 @@ def test_importance_shift_on_the_batched_workload_then_solve():
         assert latA[q] >= latS[q]
 
 
+@pytest.mark.parametrize("cid,n_raw,n_alpha", [(3, 5, 4), (4, 3, 5), (1, 2, 3)])
+def test_shared_stage1_tables_in_a_sweep(cid, n_raw, n_alpha):
+    """Stage 1 once per network, stage 2 and set recovery on n_alpha shifted
+    copies of each that share its tables (dpc_stage2_knapsack_shared,
+    dpc_backtrack_shared): the same as solving every copy on its own."""
+    import dataclasses
+    cfg = dataclasses.replace(inputs.CONFIGS[cid], B=n_raw * n_alpha)
+    T0_, I0, bases, alphas = inputs.make_sweep_batch(cfg, seed=21, n_raw=n_raw, n_alpha=n_alpha)
+    shifted, _ = _shift_gpu(I0, alphas)
+    B, L, P = n_raw * n_alpha, cfg.L, cfg.P
+    qi = np.repeat(np.arange(B, dtype=np.int32), 4)
+    qt = np.tile(np.array([0, P // 3, P // 2, P - 1], np.int32), B)
+    Q = len(qi)
+    Td = torch.from_numpy(T0_).to(DEV)
+    Id = torch.from_numpy(shifted).to(DEV)
+    qid, qtd = torch.from_numpy(qi).to(DEV), torch.from_numpy(qt).to(DEV)
+    buf = api.Buffers(B, L, P, Q)
+    Topt = torch.full((n_raw, L + 1, L + 1), -7, dtype=torch.int32, device=DEV)
+    split = torch.full((n_raw, L + 1, L + 1), 0xEE, dtype=torch.uint8, device=DEV)
+    buf.M.fill_(float("nan"))
+    buf.K.fill_(0xEE)
+    api.dpc_stage1_minplus(Td, Topt, split)
+    api.dpc_stage2_knapsack_shared(n_alpha, Topt, Id, buf.M, buf.K, buf.workspace)
+    api.dpc_backtrack_shared(n_alpha, Topt, split, Id, buf.M, buf.K, qid, qtd, buf.A, buf.A_len,
+                             buf.S, buf.S_len, buf.obj, buf.lat, buf.status)
+    api.dpc_stage2_check(buf.workspace)
+    torch.cuda.synchronize()
+    T = np.repeat(T0_, n_alpha, axis=0)
+    To, sp, M, K = oracle.solve_batch(T, shifted, P, threads=8)
+    assert first_diff(Topt.cpu().numpy(), To[::n_alpha]) is None
+    assert first_diff(bits(buf.M.cpu().numpy()), bits(M)) is None
+    assert first_diff(buf.K.cpu().numpy(), K) is None
+    A, S = buf.A.cpu().numpy(), buf.S.cpu().numpy()
+    Al, Sl, lat, st = (x.cpu().numpy() for x in (buf.A_len, buf.S_len, buf.lat, buf.status))
+    obj = buf.obj.cpu().numpy()
+    for q in range(Q):
+        b = int(qi[q])
+        r = oracle.backtrack(To[b], sp[b], shifted[b], M[b], K[b], int(qt[q]))
+        assert st[q] == r["status"] and Al[q] == r["A_len"] and Sl[q] == r["S_len"] and lat[q] == r["lat"]
+        assert bits(obj[q:q + 1])[0] == bits(np.array([r["obj"]], np.float32))[0]
+        if r["status"] == 0:
+            assert list(A[q][:r["A_len"]]) == list(r["A"]) and list(S[q][:r["S_len"]]) == list(r["S"])
+
+
 @pytest.mark.parametrize("P,cap", [(1, 4), (63, 64), (64, 3), (257, 300), (1000, 1000),
                                    (16000, 0), (16000, 17)])
 def test_front_bit_exact_on_synthetic_rows(P, cap):

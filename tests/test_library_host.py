@@ -87,6 +87,11 @@ def test_argument_errors_of_the_widened_entry_points():
     assert lib.dpc_chain_latency(1, 4, p, -1, p, p, p, p, None) == SHAPE
     assert lib.dpc_chain_latency(1, 4, p, 0, None, None, None, None, None) == 0
     assert lib.dpc_chain_latency(1, 4, p, 3, p, None, p, p, None) == NULL
+    # shared stage-1 tables
+    assert lib.dpc_stage2_knapsack_shared(4, 50, 1000, 0, p, p, p, p, p, 1 << 30, None) == SHAPE
+    assert lib.dpc_stage2_knapsack_shared(4, 50, 1000, 2, None, p, p, p, p, 1 << 30, None) == NULL
+    assert lib.dpc_backtrack_shared(1, 4, 8, 0, p, p, p, p, p, 3, *([p] * 9), None) == SHAPE
+    assert lib.dpc_backtrack_shared(1, 4, 8, 2, p, None, p, p, p, 3, *([p] * 9), None) == NULL
     # single-launch path
     assert lib.dpc_stage12_fused(1, 4, 8, None, p, p, p, p, p, None) == NULL
     assert lib.dpc_stage12_fused(1, 300, 8, p, p, p, p, p, p, None) == SHAPE
