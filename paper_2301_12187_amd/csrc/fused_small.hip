@@ -45,7 +45,7 @@ inline int lds_address(char* p) { return (int)(p - emu::g_dyn_lds); }
 
 constexpr int FS_RING = 3;                      // LDS slots shared by the rows past the resident ones
 constexpr int FS_LIST = 64;                     // entries of a wave's set lists (L <= 63)
-constexpr int FS_LIST_BYTES = 16 * 2 * FS_LIST * 4;   // static LDS of the query phase: 16 waves, two lists
+constexpr int FS_LIST_BYTES = 16 * 2 * FS_LIST * 4;   // LDS of the query phase: 16 waves, two lists each
 
 // the query list of dpc_solve_fused (Q == 0: none)
 struct FsQueries {
@@ -255,8 +255,9 @@ __global__ __launch_bounds__(1024) void fused_small_kernel(
     if constexpr (QUERIES) {
         // ---------------- set recovery for the queries of this instance ----------------
         // Every wave has waited for its stores (the tables are complete at the
-        // level all compute units share) before any wave reads them back.
-        __shared__ int32_t lists[16][2][FS_LIST];
+        // level all compute units share) before any wave reads them back.  The
+        // lists of the walks lie over the candidate table, which is done with.
+        int32_t (*lists)[2][FS_LIST] = (int32_t (*)[2][FS_LIST])smem;
         wait_vm(0);
         __syncthreads();
         const int nchunks = (qs.Q + 63) / 64;
@@ -284,7 +285,9 @@ __global__ __launch_bounds__(1024) void fused_small_kernel(
 static size_t fs_lds_bytes(int L, int P, int nslots)
 {
     const size_t ld2 = (size_t)(L + 1) * (L + 1);
-    return ld2 * sizeof(FsCand) + std::max((size_t)nslots * (P + 1) * 4, ld2 * 4);
+    // (at least the room the lists of the query phase take, which reuse this block)
+    return std::max(ld2 * sizeof(FsCand) + std::max((size_t)nslots * (P + 1) * 4, ld2 * 4),
+                    (size_t)FS_LIST_BYTES);
 }
 
 // slots that fit, at most one per row
@@ -299,7 +302,6 @@ static int fs_slots(int L, int P, int lds_limit)
 bool fused_small_supported(int L, int P, int lds_limit)
 {
     if (L < 1 || L > 63 || P < 1 || P > 2048) return false;
-    lds_limit -= FS_LIST_BYTES;                         // (the query phase's lists are static LDS)
     const int n = fs_slots(L, P, lds_limit);
     // every row resident, or at least one resident row and the shared slots
     return (n == L + 1 || n >= 1 + FS_RING) && fs_lds_bytes(L, P, n) <= (size_t)lds_limit;
@@ -313,7 +315,6 @@ hipError_t launch_fused_small(int B, int L, int P, const int32_t* T, const float
                               hipStream_t st)
 {
     if (!fused_small_supported(L, P, lds_limit)) return hipErrorInvalidValue;
-    lds_limit -= FS_LIST_BYTES;
     const int nslots = fs_slots(L, P, lds_limit);
     const int NR = nslots == L + 1 ? nslots : nslots - FS_RING;
     const size_t lds = fs_lds_bytes(L, P, nslots);

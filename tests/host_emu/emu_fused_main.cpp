@@ -15,7 +15,7 @@ int main(int argc, char** argv)
     if (!f) return 2;
     int32_t hd[5];
     if (std::fread(hd, 4, 5, f) != 5) return 2;
-    const int B = hd[0], L = hd[1], P = hd[2], lds_limit = hd[3] + dpc::FS_LIST_BYTES, Q = hd[4], ld = L + 1;
+    const int B = hd[0], L = hd[1], P = hd[2], lds_limit = hd[3], Q = hd[4], ld = L + 1;
     const size_t n2 = (size_t)B * ld * ld, cells = (size_t)B * ld * P;
     // exact-size heap blocks: the sanitizer's red zones sit right behind them
     int32_t* T = (int32_t*)std::malloc(n2 * 4);
