@@ -111,6 +111,159 @@ __device__ __forceinline__ float max_cand(float a, float b)
     return b > a ? b : a;
 #endif
 }
+// The pair step's update with back-pointers: the new maximum of a cell and two
+// candidates is formed in the register of the first candidate (one three-way
+// maximum), compared with the old one, and takes its place: 5 vector
+// instructions per two candidates with the two additions.  The running maxima
+// therefore move to another register at every step.  Where they live is fixed
+// here rather than left to the register allocator (which otherwise spills one
+// or two of them into the loop and copies dozens at its back edge): 17 slots of
+// four registers, v60 .. v127.  A step of kind 0 takes the rows in ascending
+// order, row r from slot r + 1 to slot r (slot 0 is free before it); a step of
+// kind 1 takes them in descending order, row r from slot r back to slot r + 1.
+// The loop over pairs alternates the two kinds, so the maxima are back in
+// place at its back edge.
+template <int STEP, int RR, int COL>
+struct PairCell {
+    static __device__ __forceinline__ void run(float& best, uint32_t& argp, float ca, float cb,
+                                               uint32_t vc)
+    {
+        // (the plain form: the CPU emulation build, and any row the table below lacks)
+        ca = cb > ca ? cb : ca;
+        if (ca > best) {
+            best = ca;
+            argp = (argp & ~(0xFFu << (8 * COL))) | ((vc & 0xFFu) << (8 * COL));
+        }
+    }
+};
+#ifndef DPC_HOST_EMU
+#define DPC_STR_(x) #x
+#define DPC_STR(x) DPC_STR_(x)
+#define DPC_BR(slot, col) DPC_BR_##slot##_##col
+#define DPC_BR_0_0 60
+#define DPC_BR_0_1 61
+#define DPC_BR_0_2 62
+#define DPC_BR_0_3 63
+#define DPC_BR_1_0 64
+#define DPC_BR_1_1 65
+#define DPC_BR_1_2 66
+#define DPC_BR_1_3 67
+#define DPC_BR_2_0 68
+#define DPC_BR_2_1 69
+#define DPC_BR_2_2 70
+#define DPC_BR_2_3 71
+#define DPC_BR_3_0 72
+#define DPC_BR_3_1 73
+#define DPC_BR_3_2 74
+#define DPC_BR_3_3 75
+#define DPC_BR_4_0 76
+#define DPC_BR_4_1 77
+#define DPC_BR_4_2 78
+#define DPC_BR_4_3 79
+#define DPC_BR_5_0 80
+#define DPC_BR_5_1 81
+#define DPC_BR_5_2 82
+#define DPC_BR_5_3 83
+#define DPC_BR_6_0 84
+#define DPC_BR_6_1 85
+#define DPC_BR_6_2 86
+#define DPC_BR_6_3 87
+#define DPC_BR_7_0 88
+#define DPC_BR_7_1 89
+#define DPC_BR_7_2 90
+#define DPC_BR_7_3 91
+#define DPC_BR_8_0 92
+#define DPC_BR_8_1 93
+#define DPC_BR_8_2 94
+#define DPC_BR_8_3 95
+#define DPC_BR_9_0 96
+#define DPC_BR_9_1 97
+#define DPC_BR_9_2 98
+#define DPC_BR_9_3 99
+#define DPC_BR_10_0 100
+#define DPC_BR_10_1 101
+#define DPC_BR_10_2 102
+#define DPC_BR_10_3 103
+#define DPC_BR_11_0 104
+#define DPC_BR_11_1 105
+#define DPC_BR_11_2 106
+#define DPC_BR_11_3 107
+#define DPC_BR_12_0 108
+#define DPC_BR_12_1 109
+#define DPC_BR_12_2 110
+#define DPC_BR_12_3 111
+#define DPC_BR_13_0 112
+#define DPC_BR_13_1 113
+#define DPC_BR_13_2 114
+#define DPC_BR_13_3 115
+#define DPC_BR_14_0 116
+#define DPC_BR_14_1 117
+#define DPC_BR_14_2 118
+#define DPC_BR_14_3 119
+#define DPC_BR_15_0 120
+#define DPC_BR_15_1 121
+#define DPC_BR_15_2 122
+#define DPC_BR_15_3 123
+#define DPC_BR_16_0 124
+#define DPC_BR_16_1 125
+#define DPC_BR_16_2 126
+#define DPC_BR_16_3 127
+#define DPC_PAIR_CELL(STEP, RR, COL, IN, OUT)                                                \
+    template <>                                                                              \
+    struct PairCell<STEP, RR, COL> {                                                         \
+        static __device__ __forceinline__ void run(float& best, uint32_t& argp, float ca,    \
+                                                   float cb, uint32_t vc)                    \
+        {                                                                                    \
+            asm("v_max3_f32 %0, %2, %0, %3\n\t"                                              \
+                "v_cmp_lt_f32 vcc, %2, %0\n\t"                                               \
+                "s_nop 1\n\t"                                                                \
+                "v_cndmask_b32_sdwa %1, %1, %4, vcc dst_sel:BYTE_" #COL                      \
+                " dst_unused:UNUSED_PRESERVE src0_sel:BYTE_" #COL " src1_sel:DWORD"          \
+                : "+{v" DPC_STR(OUT) "}"(ca), "+v"(argp)                                     \
+                : "{v" DPC_STR(IN) "}"(best), "v"(cb), "v"(vc)                               \
+                : "vcc");                                                                    \
+            best = ca;                                                                       \
+        }                                                                                    \
+    };
+#define DPC_PAIR_ROW(r, r1)                                                                  \
+    DPC_PAIR_CELL(0, r, 0, DPC_BR(r1, 0), DPC_BR(r, 0))                                      \
+    DPC_PAIR_CELL(0, r, 1, DPC_BR(r1, 1), DPC_BR(r, 1))                                      \
+    DPC_PAIR_CELL(0, r, 2, DPC_BR(r1, 2), DPC_BR(r, 2))                                      \
+    DPC_PAIR_CELL(0, r, 3, DPC_BR(r1, 3), DPC_BR(r, 3))                                      \
+    DPC_PAIR_CELL(1, r, 0, DPC_BR(r, 0), DPC_BR(r1, 0))                                      \
+    DPC_PAIR_CELL(1, r, 1, DPC_BR(r, 1), DPC_BR(r1, 1))                                      \
+    DPC_PAIR_CELL(1, r, 2, DPC_BR(r, 2), DPC_BR(r1, 2))                                      \
+    DPC_PAIR_CELL(1, r, 3, DPC_BR(r, 3), DPC_BR(r1, 3))
+DPC_PAIR_ROW(0, 1)
+DPC_PAIR_ROW(1, 2)
+DPC_PAIR_ROW(2, 3)
+DPC_PAIR_ROW(3, 4)
+DPC_PAIR_ROW(4, 5)
+DPC_PAIR_ROW(5, 6)
+DPC_PAIR_ROW(6, 7)
+DPC_PAIR_ROW(7, 8)
+DPC_PAIR_ROW(8, 9)
+DPC_PAIR_ROW(9, 10)
+DPC_PAIR_ROW(10, 11)
+DPC_PAIR_ROW(11, 12)
+DPC_PAIR_ROW(12, 13)
+DPC_PAIR_ROW(13, 14)
+DPC_PAIR_ROW(14, 15)
+DPC_PAIR_ROW(15, 16)
+#undef DPC_PAIR_ROW
+#undef DPC_PAIR_CELL
+#endif
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in this order
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 // the running maximum against two candidates at once
 __device__ __forceinline__ void max_cand2(float& best, float a, float b)
 {
@@ -340,6 +493,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             constexpr int SLOTF = KU * S2W_UNIT;
             constexpr int NFULL = KU / 2;
             constexpr bool HALF = (KU & 1) != 0;
+            // (the lane number is taken afresh here: its multiples are two instructions
+            //  to recompute and would otherwise occupy registers throughout the task)
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
             const int lo = tW - maxs;
             const int lo4 = lo & ~3;                               // floor to a multiple of 4
             const int n4 = (WV + maxs - mins + (lo - lo4) + 3) & ~3;   // cells needed, in floats (<= SLOTF)
@@ -353,26 +510,26 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 const unsigned lastoff = (unsigned)(last - lo4) * 4u;
 #pragma unroll
                 for (int k = 0; k < NFULL; ++k) {
-                    const unsigned off = min((unsigned)(1024 * k + 16 * lane), lastoff);
+                    const unsigned off = min((unsigned)(1024 * k + 16 * ln), lastoff);
                     __builtin_amdgcn_global_load_lds((const float*)(base + off),
                                                      (lds_void*)(dst + 256 * k), 16, 0,
                                                      DMA_AGENT_SCOPE);
                 }
                 if constexpr (HALF) {
-                    const unsigned off = min((unsigned)(1024 * NFULL + 16 * lane), lastoff);
-                    lds_load16_if(lane < 32, (const float*)(base + off), dst + 256 * NFULL);
+                    const unsigned off = min((unsigned)(1024 * NFULL + 16 * ln), lastoff);
+                    lds_load16_if(ln < 32, (const float*)(base + off), dst + 256 * NFULL);
                 }
             } else {
 #pragma unroll
                 for (int k = 0; k < NFULL; ++k) {
-                    const int tp = min(lo4 + 256 * k + 4 * lane, last);
+                    const int tp = min(lo4 + 256 * k + 4 * ln, last);
                     const float* src = tp < 0 ? ninf : row + tp;
                     __builtin_amdgcn_global_load_lds(src, (lds_void*)(dst + 256 * k), 16, 0,
                                                      DMA_AGENT_SCOPE);
                 }
                 if constexpr (HALF) {
-                    const int tp = min(lo4 + 256 * NFULL + 4 * lane, last);
-                    lds_load16_if(lane < 32, tp < 0 ? ninf : row + tp, dst + 256 * NFULL);
+                    const int tp = min(lo4 + 256 * NFULL + 4 * ln, last);
+                    lds_load16_if(ln < 32, tp < 0 ? ninf : row + tp, dst + 256 * NFULL);
                 }
             }
         };
@@ -412,47 +569,105 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 for (int u = 0; u < U; ++u) mcur[u] = mnxt[u];
             }
         };
-        // Two predecessors at once (rows a and a + 1, windows at baseA and baseB):
+        // Two predecessors at once (rows a and a + 1, windows at byte offsets baseA and
+        // baseB from this lane's place in the ring, lbase):
         // the larger of their two candidates is offered to the cell, and the byte
         // that is recorded is the number of the pair (a / 2).  Which of the two it
-        // was is settled once per cell after the last predecessor (resolve_pairs):
-        // 6 instead of 8 vector instructions per two candidates.
-        auto relax_pair_half = [&](auto hh, const char* baseA, const char* baseB, const S2Rec& ra,
-                                   const S2Rec& rb, uint32_t vc) __attribute__((always_inline)) {
-            constexpr int h = decltype(hh)::value;
-            float acur[U], anxt[U], bcur[U], bnxt[U];
+        // was is settled once per cell after the last predecessor (resolve_pairs).
+        // The operands of the sixteen rows are taken from the two rows' records a
+        // quarter (four rows: 6 scalar registers) at a time, the next quarter while
+        // the current one is in use, so that few scalar registers are live; qa and
+        // qb arrive with the first quarter and leave with the first quarter of the
+        // rows whose records start at nextA and nextB.  LDS reads run one row ahead.
+        struct Quarter { uint32_t offp[2]; float imp[4]; };
+        auto load_quarter = [&](const S2Rec* row, auto kk) __attribute__((always_inline)) {
+            constexpr int k = decltype(kk)::value;         // quarter of the row's R / 4
+            const S2Rec& r = row[k / 2];
+            Quarter q;
+            q.offp[0] = r.offp[2 * (k & 1)];
+            q.offp[1] = r.offp[2 * (k & 1) + 1];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                acur[u] = *(const float*)(baseA + rec_off4(ra, 0) + 256 * u);
-                bcur[u] = *(const float*)(baseB + rec_off4(rb, 0) + 256 * u);
+            for (int x = 0; x < 4; ++x) q.imp[x] = r.imp[4 * (k & 1) + x];
+            return q;
+        };
+        auto quarter_off4 = [](const Quarter& q, int x) __attribute__((always_inline)) {
+            return (x & 1) ? (int)(q.offp[x >> 1] >> 16) : (int)(q.offp[x >> 1] & 0xFFFFu);
+        };
+        // step_c: the kind of the step (see PairCell): which way it goes through the
+        // rows, and hence which quarter comes first.
+        auto relax_pair_rows = [&](auto step_c, int baseA, int baseB, const S2Rec* rowA,
+                                   const S2Rec* rowB, Quarter& qa, Quarter& qb, const S2Rec* nextA,
+                                   const S2Rec* nextB, uint32_t vc) __attribute__((always_inline)) {
+            static_assert(!PAIRS || R == 16, "four quarters per row of records");
+            static_assert(U == 4, "two halves of two columns per row");
+            constexpr int STEP = decltype(step_c)::value;
+            constexpr int NQU = R / 4;
+            constexpr int K0 = STEP == 0 ? 0 : NQU - 1;     // first quarter of this step
+            constexpr int R0 = STEP == 0 ? 0 : R - 1;       // and its first row
+            Quarter QA[NQU + 1], QB[NQU + 1];               // [NQU]: for the step that follows
+            QA[K0] = qa;
+            QB[K0] = qb;
+            // (reads half a row ahead: two columns of each window per instruction)
+            float av[2][2], bv[2][2];
+            const char* rowa = lbase + (baseA + quarter_off4(QA[K0], R0 & 3));
+            const char* rowb = lbase + (baseB + quarter_off4(QB[K0], R0 & 3));
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                av[0][c] = *(const float*)(rowa + 256 * c);
+                bv[0][c] = *(const float*)(rowb + 256 * c);
             }
-#pragma unroll
-            for (int r8 = 0; r8 < S2_H; ++r8) {
-                if (r8 + 1 < S2_H) {
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        anxt[u] = *(const float*)(baseA + rec_off4(ra, r8 + 1) + 256 * u);
-                        bnxt[u] = *(const float*)(baseB + rec_off4(rb, r8 + 1) + 256 * u);
+            static_for<R>([&](auto nn) __attribute__((always_inline)) {
+                constexpr int n = decltype(nn)::value;      // n-th row of this step
+                constexpr int rr = STEP == 0 ? n : R - 1 - n;
+                constexpr int k = rr / 4, x = rr % 4;
+                if constexpr (n % 4 == 0) {
+                    // the operands of the four rows after these four
+                    if constexpr (n + 4 < R) {
+                        constexpr int kn = STEP == 0 ? k + 1 : k - 1;
+                        QA[kn] = load_quarter(rowA, std::integral_constant<int, kn>{});
+                        QB[kn] = load_quarter(rowB, std::integral_constant<int, kn>{});
+                    } else {
+                        constexpr int kn = STEP == 0 ? NQU - 1 : 0;   // the other kind comes next
+                        QA[NQU] = load_quarter(nextA, std::integral_constant<int, kn>{});
+                        QB[NQU] = load_quarter(nextB, std::integral_constant<int, kn>{});
                     }
                 }
-                const float ia = ra.imp[r8], ib = rb.imp[r8];
-                if constexpr (STORE_K) {
-                    float cand[U];
+                const float ia = QA[k].imp[x], ib = QB[k].imp[x];
+                // columns 2, 3 of this row on their way, columns 0, 1 relaxed
 #pragma unroll
-                    for (int u = 0; u < U; ++u) cand[u] = max_cand(acur[u] + ia, bcur[u] + ib);
-                    relax_cell<0, true>(best[h * S2_H + r8][0], argp[h * S2_H + r8], cand[0], vc);
-                    relax_cell<1, true>(best[h * S2_H + r8][1], argp[h * S2_H + r8], cand[1], vc);
-                    relax_cell<2, true>(best[h * S2_H + r8][2], argp[h * S2_H + r8], cand[2], vc);
-                    relax_cell<3, true>(best[h * S2_H + r8][3], argp[h * S2_H + r8], cand[3], vc);
+                for (int c = 0; c < 2; ++c) {
+                    av[1][c] = *(const float*)(rowa + 256 * (2 + c));
+                    bv[1][c] = *(const float*)(rowb + 256 * (2 + c));
+                }
+                if constexpr (STORE_K) {
+                    PairCell<STEP, rr, 0>::run(best[rr][0], argp[rr], av[0][0] + ia, bv[0][0] + ib, vc);
+                    PairCell<STEP, rr, 1>::run(best[rr][1], argp[rr], av[0][1] + ia, bv[0][1] + ib, vc);
                 } else {
                     // values only: one three-way maximum per two candidates
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        max_cand2(best[h * S2_H + r8][u], acur[u] + ia, bcur[u] + ib);
+                    max_cand2(best[rr][0], av[0][0] + ia, bv[0][0] + ib);
+                    max_cand2(best[rr][1], av[0][1] + ia, bv[0][1] + ib);
                 }
+                // columns 0, 1 of the next row on their way, columns 2, 3 relaxed
+                if constexpr (n + 1 < R) {
+                    constexpr int r2 = STEP == 0 ? rr + 1 : rr - 1;
+                    rowa = lbase + (baseA + quarter_off4(QA[r2 / 4], r2 & 3));
+                    rowb = lbase + (baseB + quarter_off4(QB[r2 / 4], r2 & 3));
 #pragma unroll
-                for (int u = 0; u < U; ++u) { acur[u] = anxt[u]; bcur[u] = bnxt[u]; }
-            }
+                    for (int c = 0; c < 2; ++c) {
+                        av[0][c] = *(const float*)(rowa + 256 * c);
+                        bv[0][c] = *(const float*)(rowb + 256 * c);
+                    }
+                }
+                if constexpr (STORE_K) {
+                    PairCell<STEP, rr, 2>::run(best[rr][2], argp[rr], av[1][0] + ia, bv[1][0] + ib, vc);
+                    PairCell<STEP, rr, 3>::run(best[rr][3], argp[rr], av[1][1] + ia, bv[1][1] + ib, vc);
+                } else {
+                    max_cand2(best[rr][2], av[1][0] + ia, bv[1][0] + ib);
+                    max_cand2(best[rr][3], av[1][1] + ia, bv[1][1] + ib);
+                }
+            });
+            qa = QA[NQU];
+            qb = QB[NQU];
         };
         // After the last predecessor below the group every arg-max byte holds a
         // pair number c (or DPC_NOARG).  The arg-max is 2c if that row's candidate
@@ -575,16 +790,17 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 // while rows a and a + 1 are relaxed the copies of a + 2, a + 3 and
                 // a + 4 are in flight.  The window of row r + 4 is in the record of
                 // row r (the pack kernel looks 4 rows ahead for these groups).
-                S2Rec A[H], Bn[H];
-#pragma unroll
-                for (int h = 0; h < H; ++h) {
-                    A[h] = brec[h];
-                    Bn[h] = brec[min(1, L) * H + h];
-                }
+                const S2Rec* rowA = brec;              // records of rows a and a + 1
+                const S2Rec* rowB = brec + min(1, L) * H;
+                Quarter qa = load_quarter(rowA, std::integral_constant<int, 0>{});
+                Quarter qb = load_quarter(rowB, std::integral_constant<int, 0>{});
+                // (largest shift, then the window of the row four rows on)
+                uint32_t pa0 = rowA->pad[0], pa1 = rowA->pad[1], pa2 = rowA->pad[2];
+                uint32_t pb0 = rowB->pad[0], pb1 = rowB->pad[1], pb2 = rowB->pad[2];
                 int sa = 0;                            // ring slot of row a
                 int pw_max = 0, pw_min = 0;            // window of row a + 3
                 int a = 0;
-                for (; a + 1 < ilimit; a += 2) {
+                auto pair_step = [&](auto step_c) __attribute__((always_inline)) {
                     const int s3 = sa + 3 >= NSL ? sa + 3 - NSL : sa + 3;
                     const int s4 = sa + 4 >= NSL ? sa + 4 - NSL : sa + 4;
                     if (a >= 2 && a + 3 < ilimit) {
@@ -593,47 +809,50 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     }
                     if (a + 4 < ilimit) {
                         if (a + 4 == prev_row0) wait_prev();
-                        issue_row(nld_c, a + 4, s4, (int)A[0].pad[1], (int)A[0].pad[2]);
+                        issue_row(nld_c, a + 4, s4, (int)pa1, (int)pa2);
                     }
                     // rows up to min(ilimit, a + 5) - 1 have been issued; a and a + 1 must have landed
                     wait_vm((min(ilimit, a + 5) - (a + 2)) * NLD);
                     asm volatile("" ::: "memory");
-                    pw_max = (int)Bn[0].pad[1];
-                    pw_min = (int)Bn[0].pad[2];
+                    pw_max = (int)pb1;
+                    pw_min = (int)pb2;
                     const int sb = sa + 1 >= NSL ? 0 : sa + 1;
-                    const int dA = (tS - (int)A[0].pad[0]) & 3;
-                    const int dB = (tS - (int)Bn[0].pad[0]) & 3;
-                    const char* baseA = lbase + (sa * SLOTF + dA) * 4;
-                    const char* baseB = lbase + (sb * SLOTF + dB) * 4;
+                    const int dA = (tS - (int)pa0) & 3;
+                    const int dB = (tS - (int)pb0) & 3;
+                    const int baseA = (sa * SLOTF + dA) * 4;
+                    const int baseB = (sb * SLOTF + dB) * 4;
                     const uint32_t vc = (uint32_t)a >> 1;
-                    const int na = min(a + 2, L) * H, nb = min(a + 3, L) * H;
-                    if constexpr (H == 1) {
-                        const S2Rec nA = brec[na], nB = brec[nb];
-                        relax_pair_half(std::integral_constant<int, 0>{}, baseA, baseB, A[0], Bn[0], vc);
-                        A[0] = nA;
-                        Bn[0] = nB;
-                    } else {
-                        relax_pair_half(std::integral_constant<int, 0>{}, baseA, baseB, A[0], Bn[0], vc);
-                        const S2Rec nA0 = brec[na], nB0 = brec[nb];
-                        relax_pair_half(std::integral_constant<int, 1>{}, baseA, baseB, A[H - 1],
-                                        Bn[H - 1], vc);
-                        A[H - 1] = brec[na + H - 1];
-                        Bn[H - 1] = brec[nb + H - 1];
-                        A[0] = nA0;
-                        Bn[0] = nB0;
-                    }
+                    const S2Rec* nextA = brec + min(a + 2, L) * H;
+                    const S2Rec* nextB = brec + min(a + 3, L) * H;
+                    const uint32_t na0 = nextA->pad[0], na1 = nextA->pad[1], na2 = nextA->pad[2];
+                    const uint32_t nb0 = nextB->pad[0], nb1 = nextB->pad[1], nb2 = nextB->pad[2];
+                    relax_pair_rows(step_c, baseA, baseB, rowA, rowB, qa, qb, nextA, nextB, vc);
+                    rowA = nextA;
+                    rowB = nextB;
+                    pa0 = na0; pa1 = na1; pa2 = na2;
+                    pb0 = nb0; pb1 = nb1; pb2 = nb2;
                     sa = sa + 2 >= NSL ? sa + 2 - NSL : sa + 2;
+                    a += 2;
+                };
+                // (two steps per trip, one of each kind: see PairCell)
+                while (a + 3 < ilimit) {
+                    pair_step(std::integral_constant<int, 0>{});
+                    pair_step(std::integral_constant<int, 1>{});
                 }
+                if (a + 1 < ilimit) pair_step(std::integral_constant<int, 0>{});
                 if (a < ilimit) {
                     // an odd number of rows: the last one is a pair of its own
                     wait_vm(0);
                     asm volatile("" ::: "memory");
-                    const int dA = (tS - (int)A[0].pad[0]) & 3;
+                    const int dA = (tS - (int)pa0) & 3;
                     const char* base = lbase + (sa * SLOTF + dA) * 4;
                     const uint32_t vc = (uint32_t)a >> 1;
-                    relax_half(std::integral_constant<int, 0>{}, base, A[0], vc);
-                    if constexpr (H == 2)
-                        relax_half(std::integral_constant<int, 1>{}, base, A[H - 1], vc);
+                    const S2Rec last0 = rowA[0];
+                    relax_half(std::integral_constant<int, 0>{}, base, last0, vc);
+                    if constexpr (H == 2) {
+                        const S2Rec last1 = rowA[H - 1];
+                        relax_half(std::integral_constant<int, 1>{}, base, last1, vc);
+                    }
                 }
                 return;
               }
