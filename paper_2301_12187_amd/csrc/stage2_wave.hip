@@ -312,7 +312,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     // Two predecessors per step (relax_pair_half) where tasks are long, with a
     // table of the pairs' operands behind the diagonal slots (resolve_pairs).
     constexpr int PAIR_TAB = 128 * R;                // entries: pairs below the group x rows
-    constexpr bool PAIRS = R == 16 && (!STORE_K || (LDSF - 2 * DSLOTW) * 4 >= PAIR_TAB * 8);
+    constexpr bool PAIRS = STORE_K ? (LDSF - 2 * DSLOTW) * 4 >= PAIR_TAB * 8 : R == 16;
     static_assert(R == 8 || R == 16, "one or two records per predecessor");
     static_assert(RINGF >= 5 * 3 * S2W_UNIT, "five slots of the smallest window fit the ring");
     static_assert(WV == 256, "the window sizes in stage2_common.h are for 256 columns per wave");
@@ -598,7 +598,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
         auto relax_pair_rows = [&](auto step_c, int baseA, int baseB, const S2Rec* rowA,
                                    const S2Rec* rowB, Quarter& qa, Quarter& qb, const S2Rec* nextA,
                                    const S2Rec* nextB, uint32_t vc) __attribute__((always_inline)) {
-            static_assert(!PAIRS || R == 16, "four quarters per row of records");
             static_assert(U == 4, "two halves of two columns per row");
             constexpr int STEP = decltype(step_c)::value;
             constexpr int NQU = R / 4;
@@ -607,19 +606,23 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             Quarter QA[NQU + 1], QB[NQU + 1];               // [NQU]: for the step that follows
             QA[K0] = qa;
             QB[K0] = qb;
-            // (reads half a row ahead: two columns of each window per instruction)
-            float av[2][2], bv[2][2];
+            // (reads a whole row ahead, two columns of each window per instruction:
+            //  three buffers of half a row)
+            float av[3][2], bv[3][2];
             const char* rowa = lbase + (baseA + quarter_off4(QA[K0], R0 & 3));
             const char* rowb = lbase + (baseB + quarter_off4(QB[K0], R0 & 3));
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
                 av[0][c] = *(const float*)(rowa + 256 * c);
                 bv[0][c] = *(const float*)(rowb + 256 * c);
+                av[1][c] = *(const float*)(rowa + 256 * (2 + c));
+                bv[1][c] = *(const float*)(rowb + 256 * (2 + c));
             }
             static_for<R>([&](auto nn) __attribute__((always_inline)) {
                 constexpr int n = decltype(nn)::value;      // n-th row of this step
                 constexpr int rr = STEP == 0 ? n : R - 1 - n;
                 constexpr int k = rr / 4, x = rr % 4;
+                constexpr int b0 = (2 * n) % 3, b1 = (2 * n + 1) % 3, b2 = (2 * n + 2) % 3;
                 if constexpr (n % 4 == 0) {
                     // the operands of the four rows after these four
                     if constexpr (n + 4 < R) {
@@ -633,37 +636,39 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     }
                 }
                 const float ia = QA[k].imp[x], ib = QB[k].imp[x];
-                // columns 2, 3 of this row on their way, columns 0, 1 relaxed
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    av[1][c] = *(const float*)(rowa + 256 * (2 + c));
-                    bv[1][c] = *(const float*)(rowb + 256 * (2 + c));
-                }
-                if constexpr (STORE_K) {
-                    PairCell<STEP, rr, 0>::run(best[rr][0], argp[rr], av[0][0] + ia, bv[0][0] + ib, vc);
-                    PairCell<STEP, rr, 1>::run(best[rr][1], argp[rr], av[0][1] + ia, bv[0][1] + ib, vc);
-                } else {
-                    // values only: one three-way maximum per two candidates
-                    max_cand2(best[rr][0], av[0][0] + ia, bv[0][0] + ib);
-                    max_cand2(best[rr][1], av[0][1] + ia, bv[0][1] + ib);
-                }
-                // columns 0, 1 of the next row on their way, columns 2, 3 relaxed
+                // columns 0, 1 of the next row on their way, columns 0, 1 relaxed
                 if constexpr (n + 1 < R) {
                     constexpr int r2 = STEP == 0 ? rr + 1 : rr - 1;
                     rowa = lbase + (baseA + quarter_off4(QA[r2 / 4], r2 & 3));
                     rowb = lbase + (baseB + quarter_off4(QB[r2 / 4], r2 & 3));
 #pragma unroll
                     for (int c = 0; c < 2; ++c) {
-                        av[0][c] = *(const float*)(rowa + 256 * c);
-                        bv[0][c] = *(const float*)(rowb + 256 * c);
+                        av[b2][c] = *(const float*)(rowa + 256 * c);
+                        bv[b2][c] = *(const float*)(rowb + 256 * c);
                     }
                 }
                 if constexpr (STORE_K) {
-                    PairCell<STEP, rr, 2>::run(best[rr][2], argp[rr], av[1][0] + ia, bv[1][0] + ib, vc);
-                    PairCell<STEP, rr, 3>::run(best[rr][3], argp[rr], av[1][1] + ia, bv[1][1] + ib, vc);
+                    PairCell<STEP, rr, 0>::run(best[rr][0], argp[rr], av[b0][0] + ia, bv[b0][0] + ib, vc);
+                    PairCell<STEP, rr, 1>::run(best[rr][1], argp[rr], av[b0][1] + ia, bv[b0][1] + ib, vc);
                 } else {
-                    max_cand2(best[rr][2], av[1][0] + ia, bv[1][0] + ib);
-                    max_cand2(best[rr][3], av[1][1] + ia, bv[1][1] + ib);
+                    // values only: one three-way maximum per two candidates
+                    max_cand2(best[rr][0], av[b0][0] + ia, bv[b0][0] + ib);
+                    max_cand2(best[rr][1], av[b0][1] + ia, bv[b0][1] + ib);
+                }
+                // columns 2, 3 of the next row on their way, columns 2, 3 relaxed
+                if constexpr (n + 1 < R) {
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        av[b0][c] = *(const float*)(rowa + 256 * (2 + c));
+                        bv[b0][c] = *(const float*)(rowb + 256 * (2 + c));
+                    }
+                }
+                if constexpr (STORE_K) {
+                    PairCell<STEP, rr, 2>::run(best[rr][2], argp[rr], av[b1][0] + ia, bv[b1][0] + ib, vc);
+                    PairCell<STEP, rr, 3>::run(best[rr][3], argp[rr], av[b1][1] + ia, bv[b1][1] + ib, vc);
+                } else {
+                    max_cand2(best[rr][2], av[b1][0] + ia, bv[b1][0] + ib);
+                    max_cand2(best[rr][3], av[b1][1] + ia, bv[b1][1] + ib);
                 }
             });
             qa = QA[NQU];
