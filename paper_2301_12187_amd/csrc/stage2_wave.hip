@@ -1106,18 +1106,20 @@ hipError_t launch_stage2_wave(int B, int L, int P, ToptRef Topt, const float* I,
     // Task shape.  Groups of 8 rows: the narrowest task that covers a narrow
     // table, 2048 columns per task for wide ones.  Chains of 64 layers and more
     // run in groups of 16 rows where the table is wider than 512 budgets: they
-    // halve the number of times every row of M is read back and take two
-    // predecessors per step.  Their tasks are 1024 columns wide, except where
-    // one task of 8 or 16 waves covers the whole width and there are instances
-    // enough to fill the chip with such tasks (no strip edges at all then).
-    // Measured on the L=53, L=100 and L=200 workloads at 1000 to 16000 budgets
-    // and on the 109-layer chains of the extended solver.
+    // halve the number of times every row of M is read back.  Their tasks are
+    // 1024 columns wide, except where one task of 8 or 16 waves covers the whole
+    // width and there are instances enough to fill the chip with such tasks (no
+    // strip edges at all then); that shape also wins for shorter chains, with
+    // twice the instances where it is the 8-wave one.
+    // Measured on chains of 32 to 200 layers at 1000 to 16000 budgets and on the
+    // 109-layer chains of the extended solver.
     const int narrow = P <= 256 ? 4 : P <= 512 ? 3 : P <= 1536 ? 1 : 2;
     int wide = 0;
-    if (L >= 64 && P > 512) {
-        if (P > 1536 && P <= 2048 && 2LL * B >= num_cu) wide = 6;
+    if (P > 512 && L > 16) {
+        const long long fill8 = L >= 64 ? num_cu : 4LL * num_cu;
+        if (P > 1536 && P <= 2048 && 2LL * B >= fill8) wide = 6;
         else if (P > 2048 && P <= 4096 && B >= num_cu) wide = 8;
-        else wide = 5;
+        else if (L >= 64) wide = 5;
     }
     if (wide == 0)
         return launch_wave_shape(narrow, B, L, P, Topt, I, M, K, workspace, num_cu, st, false, 0u, false);
