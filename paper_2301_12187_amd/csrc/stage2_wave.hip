@@ -934,28 +934,46 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                 store_row(j0 + rr, rr);
             }
         } else {
+            // operands of the even rows below the group for the pair settlement: the
+            // first ones are fetched before the barrier (whose wait covers their
+            // latency); all go behind the two diagonal slots after it
+            constexpr int TRIPS = (PAIR_TAB + NT - 1) / NT;
+            constexpr int EARLY = TRIPS < 2 ? TRIPS : 2;
+            const int nent = ((j0 + 1) >> 1) * R;              // pairs (2c, 2c + 1) with 2c < j0
+            auto pair_operands = [&](int k) __attribute__((always_inline)) {
+                const int32_t* To = Topt.of(b, ld);
+                const float* Ib = I + (size_t)b * ld * ld;
+                const int en = min(tid + k * NT, nent - 1);
+                const int c = en / R, rr = en - c * R;
+                const int x = 2 * c * ld + min(j0 + rr, L);
+                const int w = To[x];
+                PairOp o;
+                o.w4 = w >= 0 && w < P ? 4 * w : 0x7FFFFFFF;       // (the pack kernel's rule)
+                o.imp = Ib[x];
+                return o;
+            };
+            PairOp early[EARLY];
+            if constexpr (PAIRS && STORE_K) {
+                if (pair_task) {
+#pragma unroll
+                    for (int k = 0; k < EARLY; ++k)
+                        if (k * NT < nent) early[k] = pair_operands(k);
+                }
+            }
             __syncthreads();                           // every ring is idle: the slots below lie over them
             if constexpr (PAIRS && STORE_K) {
                 if (pair_task) {
-                    // operands of the even rows below the group, behind the two slots
                     PairOp* tab = (PairOp*)(lds + 2 * DSLOTW);
-                    const int32_t* To = Topt.of(b, ld);
-                    const float* Ib = I + (size_t)b * ld * ld;
-                    const int nent = ((j0 + 1) >> 1) * R;          // pairs (2c, 2c + 1) with 2c < j0
-                    constexpr int TRIPS = (PAIR_TAB + NT - 1) / NT;
-                    PairOp o[TRIPS];
+                    PairOp late[TRIPS - EARLY + 1];
 #pragma unroll
-                    for (int k = 0; k < TRIPS; ++k) {
-                        const int en = min(tid + k * NT, nent - 1);
-                        const int c = en / R, rr = en - c * R;
-                        const int x = 2 * c * ld + min(j0 + rr, L);
-                        const int w = To[x];
-                        o[k].w4 = w >= 0 && w < P ? 4 * w : 0x7FFFFFFF;   // (the pack kernel's rule)
-                        o[k].imp = Ib[x];
-                    }
+                    for (int k = EARLY; k < TRIPS; ++k)
+                        if (k * NT < nent) late[k - EARLY] = pair_operands(k);
 #pragma unroll
-                    for (int k = 0; k < TRIPS; ++k)
-                        if (tid + k * NT < nent) tab[tid + k * NT] = o[k];
+                    for (int k = 0; k < EARLY; ++k)
+                        if (tid + k * NT < nent) tab[tid + k * NT] = early[k];
+#pragma unroll
+                    for (int k = EARLY; k < TRIPS; ++k)
+                        if (tid + k * NT < nent) tab[tid + k * NT] = late[k - EARLY];
                     __syncthreads();
                     if (!wave_idle) resolve_pairs(tab, (j0 + 1) >> 1);
                 }
