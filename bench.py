@@ -48,25 +48,26 @@ VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9        # 39.3e12
 # launch (FETCH_SIZE / WRITE_SIZE runs) and VALU instructions issued per
 # candidate (SQ_INSTS_VALU x 64 lanes / exact candidates), keyed by config.
 PROFILED = {
-    3: {"file": "profiles/stage2_cfg3.md", "traffic_bytes": 0.563e9 + 0.293e9,
-        "issued_valu_per_relax": 5.00},
+    3: {"file": "profiles/stage2_cfg3.md", "traffic_bytes": 0.636e9 + 0.293e9,
+        "issued_valu_per_relax": 4.41},
     4: {"file": "profiles/stage2_cfg4.md", "traffic_bytes": 1.839e9,
-        "issued_valu_per_relax": 4.18},
-    5: {"file": "profiles/stage2_wave_kernel_cfg5.md", "traffic_bytes": 7.219e9,
-        "issued_valu_per_relax": 4.00},
+        "issued_valu_per_relax": 3.79},
+    5: {"file": "profiles/stage2_wave_kernel_cfg5.md", "traffic_bytes": 7.271e9,
+        "issued_valu_per_relax": 3.52},
 }
 
 
 def variant_floor_ops(L, P, store_K):
-    """VALU instructions per candidate that the main loop of the kernel shape the
-    library picks for (L, P) cannot go below: 16-row groups take two predecessor
-    rows per step (2 adds + 1 max + compare + 2 selects per two candidates = 3 with
-    back-pointers, 2 adds + 1 three-way max = 1.5 without); 8-row groups take one
-    (add, compare, 2 selects = 4; add, max = 2)."""
-    pairs = L >= 64 and P > 512
+    """VALU instructions per candidate that the arithmetic of the main loop of the
+    kernel shape the library picks for (L, P) cannot go below.  With
+    back-pointers, tables wider than 512 budgets take two predecessor rows per
+    step: 2 adds, 1 three-way max, 1 compare, 1 byte select per two candidates =
+    2.5; narrower ones take one: add, compare, 2 selects = 4.  Without
+    back-pointers: 2 adds + 1 three-way max = 1.5 for 16-row groups, add + max = 2
+    for 8-row groups."""
     if store_K:
-        return 3.0 if pairs else 4.0
-    return 1.5 if pairs else 2.0
+        return 2.5 if P > 512 else 4.0
+    return 1.5 if (L >= 64 and P > 512) else 2.0
 
 
 class Workload:

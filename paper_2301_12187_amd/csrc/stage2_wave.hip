@@ -35,15 +35,16 @@
 // A row that offers no candidate to the group is fetched all the same; its
 // importances are -inf in the records, so it never wins.
 //
-// With groups of 16 rows and back-pointers stored, the rows below the group
-// are taken two at a time: a cell is offered the larger of the two rows'
-// candidates, the byte that is kept is the number of the pair, and which of the
-// two rows it was is settled once per cell when the last row below the group is
-// done, by looking the even row's candidate up again (relax_pair_half,
-// resolve_pairs).  Values and arg-max indices are those of the one-at-a-time
-// update: the maximum of two candidates has the bits of whichever is larger,
-// a strict comparison against the running maximum keeps the first pair that
-// attains it, and inside the pair the lower row wins a tie.
+// Where the ring has five slots, the rows below the group are taken two at a
+// time: a cell is offered the larger of the two rows' candidates (one
+// three-way maximum with the running maximum), the byte that is kept is the
+// number of the pair, and which of the two rows it was is settled once per cell
+// when the last row below the group is done, by looking the even row's
+// candidate up again (relax_pair_rows, PairCell, resolve_pairs).  Values and
+// arg-max indices are those of the one-at-a-time update: the maximum of two
+// candidates has the bits of whichever is larger, a strict comparison against
+// the running maximum keeps the first pair that attains it, and inside the
+// pair the lower row wins a tie.
 //
 // The diagonal part (predecessors inside the group) is shared by the waves of
 // the workgroup: a finished row goes to one of two LDS
@@ -309,8 +310,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
     constexpr int DSLOTW = WCAP + DMAX + 4;          // floats per diagonal slot
     constexpr int LDSF = NW * RINGF > 2 * DSLOTW ? NW * RINGF : 2 * DSLOTW;
     constexpr float NINF = -INFINITY;
-    // Two predecessors per step (relax_pair_half) where tasks are long, with a
-    // table of the pairs' operands behind the diagonal slots (resolve_pairs).
+    // Two predecessors per step (relax_pair_rows).  With back-pointers the step
+    // needs a table of the pairs' operands behind the diagonal slots for the
+    // settlement (resolve_pairs): shapes whose LDS has no room for it take one
+    // predecessor per step.  Without back-pointers only 16-row groups use it.
     constexpr int PAIR_TAB = 128 * R;                // entries: pairs below the group x rows
     constexpr bool PAIRS = STORE_K ? (LDSF - 2 * DSLOTW) * 4 >= PAIR_TAB * 8 : R == 16;
     static_assert(R == 8 || R == 16, "one or two records per predecessor");
