@@ -105,7 +105,7 @@ __global__ __launch_bounds__(1024) void fused_small_kernel(
     __syncthreads();
     for (int k = wave; k <= L; k += nw) {
         int32_t cur[1], arg[1];
-        stage1_row<1, 16>(L, Tl, k, lane, cur, arg);
+        stage1_row<1, 16, true>(L, Tl, k, lane, cur, arg);
         const int l = lane;
         if (l <= L) {
             const bool upper = l > k;

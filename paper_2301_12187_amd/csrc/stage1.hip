@@ -27,7 +27,7 @@ __global__ __launch_bounds__(64 * S1_WAVES) void stage1_kernel(
 
     int32_t cur[S1_U];
     int32_t arg[S1_U];
-    stage1_row<S1_U, S1_AHEAD>(L, Tb, k, lane, cur, arg);
+    stage1_row<S1_U, S1_AHEAD, false>(L, Tb, k, lane, cur, arg);
 #pragma unroll
     for (int u = 0; u < S1_U; ++u) {
         const int l = lane + 64 * u;
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(1024) void stage1_lds_kernel(
     for (int k = wave; k <= L; k += nw) {
         int32_t cur[S1_U];
         int32_t arg[S1_U];
-        stage1_row<S1_U, 8>(L, s1_T, k, lane, cur, arg);
+        stage1_row<S1_U, 8, true>(L, s1_T, k, lane, cur, arg);
 #pragma unroll
         for (int u = 0; u < S1_U; ++u) {
             const int l = lane + 64 * u;
