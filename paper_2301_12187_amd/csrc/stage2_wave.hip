@@ -254,6 +254,20 @@ DPC_PAIR_ROW(15, 16)
 #undef DPC_PAIR_ROW
 #undef DPC_PAIR_CELL
 #endif
+// issue priority x mod 4 for this wave (the instruction takes an immediate)
+__device__ __forceinline__ void rotate_priority(uint32_t x)
+{
+#ifndef DPC_HOST_EMU
+    switch (x & 3u) {
+        case 0: __builtin_amdgcn_s_setprio(0); break;
+        case 1: __builtin_amdgcn_s_setprio(1); break;
+        case 2: __builtin_amdgcn_s_setprio(2); break;
+        default: __builtin_amdgcn_s_setprio(3); break;
+    }
+#else
+    (void)x;
+#endif
+}
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in this order
 template <class F, int... I>
 __device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, I...>)
@@ -829,6 +843,12 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
                     const int dB = (tS - (int)pb0) & 3;
                     const int baseA = (sa * SLOTF + dA) * 4;
                     const int baseB = (sb * SLOTF + dB) * 4;
+                    // Workgroups of 8 or 16 waves have two or four waves on every SIMD,
+                    // which all reach the barrier in front of the diagonal part before any
+                    // goes on: the issue priority goes round them from step to step, so
+                    // that they advance together instead of finishing one after the other
+                    // (the last ones alone on their SIMD).
+                    if constexpr (NW >= 8) rotate_priority(((uint32_t)a >> 1) + (uint32_t)(wave >> 2));
                     const uint32_t vc = (uint32_t)a >> 1;
                     const S2Rec* nextA = brec + min(a + 2, L) * H;
                     const S2Rec* nextB = brec + min(a + 3, L) * H;
@@ -929,6 +949,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             else if (need <= U3) offdiag(integral_constant<int, U3>{}, integral_constant<int, 3>{});
             else offdiag(integral_constant<int, U2>{}, integral_constant<int, 2>{});
         }
+        if constexpr (NW >= 8) rotate_priority(0u);
         if (!full) {
             // ---------------- a one-row task only has its row to store ----------------
 #pragma unroll
