@@ -1148,20 +1148,31 @@ hipError_t launch_stage2_wave(int B, int L, int P, ToptRef Topt, const float* I,
     // Task shape.  Groups of 8 rows: the narrowest task that covers a narrow
     // table, 2048 columns per task for wide ones.  Chains of 64 layers and more
     // run in groups of 16 rows where the table is wider than 512 budgets: they
-    // halve the number of times every row of M is read back.  Their tasks are
-    // 1024 columns wide, except where one task of 8 or 16 waves covers the whole
-    // width and there are instances enough to fill the chip with such tasks (no
-    // strip edges at all then); that shape also wins for shorter chains, with
-    // twice the instances where it is the 8-wave one.
-    // Measured on chains of 32 to 200 layers at 1000 to 16000 budgets and on the
-    // 109-layer chains of the extended solver.
+    // halve the number of times every row of M is read back.  Their tasks are as
+    // wide as the table where 4, 8 or 16 waves cover it (no strip edges at all
+    // then), and 16 waves wide beyond that (4096 columns: a quarter of the ghost
+    // columns of 1024-column strips), except where the tasks of a level would
+    // fill the chip's compute units a whole number of times and a little more:
+    // then the finer 4-wave tasks.  The whole-width shapes of 8 and 16 waves also
+    // win for shorter chains when the batch fills the chip with such tasks.
+    // Measured on chains of 32 to 200 layers at 1000 to 16000 budgets, batches
+    // of 32 to 1024, and on the 109-layer chains of the extended solver.
     const int narrow = P <= 256 ? 4 : P <= 512 ? 3 : P <= 1536 ? 1 : 2;
     int wide = 0;
-    if (P > 512 && L > 16) {
-        const long long fill8 = L >= 64 ? num_cu : 4LL * num_cu;
-        if (P > 1536 && P <= 2048 && 2LL * B >= fill8) wide = 6;
+    if (P > 512 && L >= 64) {
+        if (P <= 1024) wide = 5;
+        else if (P <= 2048) wide = 6;
+        else if (P <= 4096) wide = 8;
+        else {
+            // (the ghost width is only known on the device: 128 columns assumed)
+            const long long strips = 1 + ((long long)P - 4096 + 3967) / 3968;
+            const long long tasks = strips * B;
+            const long long rounds = (tasks + num_cu - 1) / num_cu, rem = tasks % num_cu;
+            wide = (rounds >= 2 && rem != 0 && 4 * rem < num_cu) ? 5 : 8;
+        }
+    } else if (P > 512 && L > 16) {
+        if (P > 1536 && P <= 2048 && B >= 2LL * num_cu) wide = 6;
         else if (P > 2048 && P <= 4096 && B >= num_cu) wide = 8;
-        else if (L >= 64) wide = 5;
     }
     if (wide == 0)
         return launch_wave_shape(narrow, B, L, P, Topt, I, M, K, workspace, num_cu, st, false, 0u, false);
