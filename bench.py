@@ -19,10 +19,12 @@ target is quoted on.  Prints ONE JSON line.
                (the 157.3 TFLOP/s fp32 vector figure without the FMA and
                packed factors of 2).  Duration from HIP events on the launch
                stream around dpc_stage2_knapsack in every timed step.
-               `frac` counts 4 lane-ops per candidate whatever the kernel
-               issues; `variant_floor_ops` / `frac_of_variant_floor` count
-               what the main loop of the kernel shape that ran needs at
-               least, `issued_valu_per_relax` what the counters saw.
+               `frac` counts 4 lane-ops per candidate (the update taken
+               one candidate at a time) whatever the kernel issues, so it
+               can pass 1; `variant_floor_ops` / `frac_of_variant_floor`
+               count what the arithmetic of the main loop of the kernel
+               shape that ran needs at least, `issued_valu_per_relax` /
+               `frac_issued` what the counters saw.
   cpu_baseline the CPU oracle, as it stands, on every instance and query of the
                same workload, one instance per host thread (`cores` threads
                of `host_cores`).
@@ -48,12 +50,12 @@ VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9        # 39.3e12
 # launch (FETCH_SIZE / WRITE_SIZE runs) and VALU instructions issued per
 # candidate (SQ_INSTS_VALU x 64 lanes / exact candidates), keyed by config.
 PROFILED = {
-    3: {"file": "profiles/stage2_cfg3.md", "traffic_bytes": 0.636e9 + 0.293e9,
+    3: {"file": "profiles/stage2_cfg3.md", "traffic_bytes": 0.929e9,
         "issued_valu_per_relax": 4.41},
-    4: {"file": "profiles/stage2_cfg4.md", "traffic_bytes": 1.839e9,
-        "issued_valu_per_relax": 3.79},
-    5: {"file": "profiles/stage2_wave_kernel_cfg5.md", "traffic_bytes": 7.271e9,
-        "issued_valu_per_relax": 3.52},
+    4: {"file": "profiles/stage2_cfg4.md", "traffic_bytes": 1.806e9,
+        "issued_valu_per_relax": 3.84},
+    5: {"file": "profiles/stage2_wave_kernel_cfg5.md", "traffic_bytes": 6.643e9,
+        "issued_valu_per_relax": 3.39},
 }
 
 
@@ -306,6 +308,9 @@ def main():
             "variant_floor_ops": floor_ops,
             "frac_of_variant_floor": floor_ops * exact / (s2_avg * 1e-3) / VALU_PEAK_LANE_OPS,
             "issued_valu_per_relax": prof["issued_valu_per_relax"] if prof else None,
+            # the VALU instructions the kernel issued, as a fraction of the peak
+            "frac_issued": (prof["issued_valu_per_relax"] * exact / (s2_avg * 1e-3) / VALU_PEAK_LANE_OPS)
+                           if prof else None,
             "traffic": prof["traffic_bytes"] if prof else None,
             "traffic_source": (prof["file"] + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not this run)")
                               if prof else None,
