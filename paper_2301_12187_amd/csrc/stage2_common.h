@@ -18,7 +18,8 @@ struct S2Header {
     uint32_t pad0[31];             // a cache line with nothing that waiting waves poll
     float ninf[4];                 // byte 128: sixteen bytes of -inf, the source of window
                                    // cells that lie below column 0 (layout kernel)
-    uint32_t choice;               // which of two prepared shapes runs (launch_stage2_decide)
+    uint32_t choice;               // which of two prepared shapes runs (set by the layout
+                                   // kernel of the first one)
     uint32_t error;                // set when a bounded wait ran out (dpc_stage2_check)
     uint32_t total;                // number of tasks, written by the layout kernel
     uint32_t pad1[25];
@@ -94,10 +95,10 @@ S2Layout s2_layout(int B, int L, int P, int R);
 // `wcap` columns.  `ahead`: see S2Rec::pad; a negative value asks for
 // min(-ahead, s2_rows_ahead(ringf, spread of the group)).
 // gated: every kernel returns at once unless the header's choice word equals
-// `want` (the word survives this call's clearing).  decide: after packing, the
-// choice word is set to 1 if more than 2 % of the groups have to run row by
+// `want` (the word survives this call's clearing).  decide: the layout kernel
+// sets the choice word to 1 if more than 2 % of the groups have to run row by
 // row (so that a second, gated preparation with smaller groups takes over),
-// else to 0; the layout kernel that follows is then gated on 0.
+// else to 0.
 hipError_t launch_stage2_prepare(int B, int L, int P, int R, ToptRef Topt, const float* I,
                                  float* M, uint8_t* K, void* workspace, int gmax, int dspread,
                                  int dpad, int wcap, int ahead, int ringf, hipStream_t st,

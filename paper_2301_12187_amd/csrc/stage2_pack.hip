@@ -36,22 +36,6 @@ __global__ void stage2_clear_kernel(uint32_t* w, int n)
     if (i < n) w[i] = 0;
 }
 
-// Sets the choice word: 1 if more than 2 % of the groups run row by row (a
-// group of 16 rows that does costs about eight times a whole one, groups of 8
-// rows about a tenth more overall), else 0.
-__global__ __launch_bounds__(256) void stage2_decide_kernel(int n, const int32_t* __restrict__ groups,
-                                                            S2Header* hdr)
-{
-    __shared__ int bad;
-    if (threadIdx.x == 0) bad = 0;
-    __syncthreads();
-    int mine = 0;
-    for (int x = threadIdx.x; x < n; x += 256) mine += groups[x] < 0 ? 1 : 0;
-    if (mine) atomicAdd(&bad, mine);
-    __syncthreads();
-    if (threadIdx.x == 0) hdr->choice = (long long)bad * 50 > n ? 1u : 0u;
-}
-
 hipError_t launch_clear_words(void* p, int nwords, hipStream_t st)
 {
     hipLaunchKernelGGL(stage2_clear_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st,
@@ -245,11 +229,12 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
 // one combine of the 16 wave totals per tile.
 __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     int B, int L, int P, int NQ, int R, int wcap, const int32_t* __restrict__ groups,
-    S2Entry* __restrict__ entries, S2Task* __restrict__ tasks, S2Header* hdr, S2Gate gate)
+    S2Entry* __restrict__ entries, S2Task* __restrict__ tasks, S2Header* hdr, S2Gate gate, bool decide)
 {
     if (s2_gate_closed(gate)) return;
     __shared__ int wsum[2][16];
     __shared__ int red[16];
+    __shared__ int redbad[16];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int level = blockIdx.x;                   // = q * R + sub
@@ -289,21 +274,25 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     };
 
     // ---- tickets before this level
-    int part = 0;
+    int part = 0, bad = 0;                          // bad: groups that run row by row
     for (int b = tid; b < B; b += 1024)
         for (int qq = 0; qq <= q; ++qq) {
             const int below = qq < q ? R : sub;     // levels of group qq that lie below this one
             if (below == 0) continue;
             const int grp = group_of(b, qq);
             part += grp >= 0 ? whole_count(grp) : strips1 * min(below, s2_group_rows(L, R, qq));
+            bad += grp < 0 ? 1 : 0;
         }
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
-    if (lane == 0) red[wave] = part;
+    for (int d = 32; d >= 1; d >>= 1) {
+        part += __shfl_xor(part, d, 64);
+        bad += __shfl_xor(bad, d, 64);
+    }
+    if (lane == 0) { red[wave] = part; redbad[wave] = bad; }
     __syncthreads();
-    int base = 0;
+    int base = 0, allbad = 0;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) base += red[w];
+    for (int w = 0; w < 16; ++w) { base += red[w]; allbad += redbad[w]; }
 
     // ---- this level's entries and tasks
     for (int b0 = 0, it = 0; b0 < B; b0 += 1024, ++it) {
@@ -359,6 +348,13 @@ __global__ __launch_bounds__(1024) void stage2_layout_kernel(
     if (blockIdx.x == gridDim.x - 1) {
         if (tid == 0) hdr->total = (uint32_t)base;
         if (tid < 4) hdr->ninf[tid] = -INFINITY;
+        // The workgroup of the last level has looked at every group (R >= 2: its
+        // row is not the first of its group).  Where the caller has another shape
+        // queued behind this one it sets the choice word: 1 (the other shape) if
+        // more than 2 % of the groups run row by row (a group of 16 rows that does
+        // costs about eight times a whole one, groups of 8 rows about a tenth
+        // more overall), else 0.
+        if (decide && tid == 0) hdr->choice = (long long)allbad * 50 > (long long)NQ * B ? 1u : 0u;
     }
 }
 
@@ -393,18 +389,9 @@ hipError_t launch_stage2_prepare(int B, int L, int P, int R, ToptRef Topt, const
                            (uint32_t*)hdr, done, keep_word);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    S2Gate layout_gate = gate;
-    if (decide) {
-        if ((long long)NQ * B > 0x3FFFFFF0LL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(stage2_decide_kernel, dim3(1), dim3(256), 0, st, NQ * B,
-                           (const int32_t*)groups, hdr);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        layout_gate = S2Gate{&hdr->choice, 0u};
-    }
     hipLaunchKernelGGL(stage2_layout_kernel, dim3(NQ * R), dim3(1024), 0, st, B, L, P, NQ, R, wcap,
                        (const int32_t*)groups, (S2Entry*)(base + lay.entry_off),
-                       (S2Task*)(base + lay.task_off), hdr, layout_gate);
+                       (S2Task*)(base + lay.task_off), hdr, gate, decide);
     return hipGetLastError();
 }
 
