@@ -587,15 +587,16 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             }
         };
         // Two predecessors at once (rows a and a + 1, windows at byte offsets baseA and
-        // baseB from this lane's place in the ring, lbase):
-        // the larger of their two candidates is offered to the cell, and the byte
-        // that is recorded is the number of the pair (a / 2).  Which of the two it
-        // was is settled once per cell after the last predecessor (resolve_pairs).
-        // The operands of the sixteen rows are taken from the two rows' records a
-        // quarter (four rows: 6 scalar registers) at a time, the next quarter while
-        // the current one is in use, so that few scalar registers are live; qa and
-        // qb arrive with the first quarter and leave with the first quarter of the
-        // rows whose records start at nextA and nextB.  LDS reads run one row ahead.
+        // baseB from this lane's place in the ring, lbase): each cell is offered both
+        // candidates in one update (PairCell), and the byte that is recorded is the
+        // number of the pair (a / 2).  Which of the two it was is settled once per
+        // cell after the last predecessor (resolve_pairs).  The operands of the
+        // group's rows are taken from the two rows' records a quarter (four rows: 6
+        // scalar registers per record) at a time, the next quarter while the current
+        // one is in use, so that few scalar registers are live; qa and qb arrive with
+        // the first quarter this step needs and leave with the first quarter that the
+        // next step needs of the rows whose records start at nextA and nextB.  LDS
+        // reads run one row ahead of the arithmetic.
         struct Quarter { uint32_t offp[2]; float imp[4]; };
         auto load_quarter = [&](const S2Rec* row, auto kk) __attribute__((always_inline)) {
             constexpr int k = decltype(kk)::value;         // quarter of the row's R / 4
