@@ -1,5 +1,7 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element
 by element, tolerance 0 (integers, indices and binary32 bit patterns)."""
+import dataclasses
+
 import numpy as np
 import oracle
 import pytest
@@ -269,6 +271,31 @@ def test_bad_queries_and_empty_query_list():
     assert np.isneginf(g["obj"][1:]).all()
     g = run_gpu(T, I, cfg.P, np.zeros(0, np.int32), np.zeros(0, np.int32))
     assert g["M"].shape == (1, cfg.L + 1, cfg.P)
+
+
+@pytest.mark.parametrize("L,P,B", [(53, 1400, 14), (63, 1700, 10), (7, 700, 28)])
+def test_long_query_list_over_short_chains(L, P, B):
+    """Set recovery with several queries per wave (lists of 16384 queries and more over
+    chains of at most 63 layers): every budget of every instance, in shuffled order, with
+    queries that name no instance or no budget and infeasible budgets among them."""
+    cfg = dataclasses.replace(inputs.CONFIGS[3], L=L, P=P)
+    T, I, _ = inputs.make_batch(cfg, seed=11, B=B)
+    qi = np.repeat(np.arange(B, dtype=np.int32), P)
+    qt = np.tile(np.arange(P, dtype=np.int32), B)
+    qi = np.concatenate([qi, [-1, B, 3, 5]]).astype(np.int32)
+    qt = np.concatenate([qt, [5, 5, P, -2]]).astype(np.int32)
+    rng = np.random.default_rng(3)
+    perm = rng.permutation(len(qi))
+    qi, qt = qi[perm], qt[perm]
+    assert len(qi) >= 16384
+    g = run_gpu(T, I, P, qi, qt)
+    bad = (qi < 0) | (qi >= B) | (qt < 0) | (qt >= P)
+    assert (g["status"][bad] == 2).all() and (g["A_len"][bad] == -1).all()
+    ok = ~bad
+    r = run_oracle(T, I, P, qi[ok], qt[ok], threads=16)
+    assert (g["status"][ok] == 1).any()          # some budgets are below the cheapest network
+    gs = {k: (v if k in ("Topt", "split", "M", "K") else v[ok]) for k, v in g.items()}
+    compare(gs, r, L, f"long query list, L={L}")
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
