@@ -86,13 +86,12 @@ __global__ __launch_bounds__(64 * X1_WAVES) void ext_iopt_kernel(
                 float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, own), m & 63));
 #pragma unroll
             for (int u = 0; u < X1_U; ++u) {
-                const int l = lane + 64 * u;
-                if (l > m && l <= L) {
-                    const float c0 = vm + iv[x][u].x;
-                    if (c0 > best[u][0]) { best[u][0] = c0; arg[u][0] = m; }
-                    const float c1 = vm + iv[x][u].y;
-                    if (c1 > best[u][1]) { best[u][1] = c1; arg[u][1] = m; }
-                }
+                // (a target that does not take part got -inf at the load: its
+                //  candidate is -inf and replaces nothing, so no test here)
+                const float c0 = vm + iv[x][u].x;
+                if (c0 > best[u][0]) { best[u][0] = c0; arg[u][0] = m; }
+                const float c1 = vm + iv[x][u].y;
+                if (c1 > best[u][1]) { best[u][1] = c1; arg[u][1] = m; }
             }
         }
     }
