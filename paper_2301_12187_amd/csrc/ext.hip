@@ -38,21 +38,14 @@ __device__ __forceinline__ size_t i4_index(int ld, int k, int l, int a, int b)
 // The importances I[m][l][0][.] do not depend on the walk: X1_AHEAD rows of
 // them are fetched at once (both flags b of a target are one 8-byte load).
 // X1_U: targets per lane, 64 * X1_U > L.
-template <int X1_U, int X1_AHEAD>
-__global__ __launch_bounds__(64 * X1_WAVES) void ext_iopt_kernel(
-    int L, const float* __restrict__ I4, float* __restrict__ Iopt, uint8_t* __restrict__ bsplit)
+// The walk of one wave for one (k, a).  PAIRS_IN_LDS: the pairs
+// (I[m][l][0][0], I[m][l][0][1]) of the instance have been copied to LDS, sI[m * ld + l].
+template <int X1_U, int X1_AHEAD, bool PAIRS_IN_LDS>
+__device__ __forceinline__ void ext_iopt_row(int L, const float* __restrict__ Ib, const float2* sI,
+                                             int k, int a, int lane, float (&best)[X1_U][2],
+                                             int (&arg)[X1_U][2])
 {
-    const int lane = threadIdx.x & 63;
-    const int w = blockIdx.x * X1_WAVES + (threadIdx.x >> 6);   // = 2k + a
-    const int k = w >> 1, a = w & 1;
-    const int b = blockIdx.y;
-    if (k > L) return;                      // whole wave leaves together
     const int ld = L + 1;
-    const size_t inst = (size_t)b * ld * ld * 4;
-    const float* Ib = I4 + inst;
-
-    float best[X1_U][2];
-    int arg[X1_U][2];
 #pragma unroll
     for (int u = 0; u < X1_U; ++u) {
         const int l = lane + 64 * u;
@@ -70,8 +63,14 @@ __global__ __launch_bounds__(64 * X1_WAVES) void ext_iopt_kernel(
 #pragma unroll
             for (int u = 0; u < X1_U; ++u) {
                 const int l = lane + 64 * u;
-                iv[x][u] = (l > m && l <= L) ? *(const float2*)(Ib + i4_index(ld, m, l, 0, 0))
-                                             : make_float2(-INFINITY, -INFINITY);
+                if constexpr (PAIRS_IN_LDS) {
+                    // (every lane reads: cheaper there than a read under a lane mask)
+                    const float2 v = sI[m * ld + min(l, L)];
+                    iv[x][u] = (l > m && l <= L) ? v : make_float2(-INFINITY, -INFINITY);
+                } else {
+                    iv[x][u] = (l > m && l <= L) ? *(const float2*)(Ib + i4_index(ld, m, l, 0, 0))
+                                                 : make_float2(-INFINITY, -INFINITY);
+                }
             }
         }
 #pragma unroll
@@ -95,6 +94,15 @@ __global__ __launch_bounds__(64 * X1_WAVES) void ext_iopt_kernel(
             }
         }
     }
+}
+
+template <int X1_U>
+__device__ __forceinline__ void ext_iopt_store(int L, size_t inst, int k, int a, int lane,
+                                               const float (&best)[X1_U][2],
+                                               const int (&arg)[X1_U][2], float* __restrict__ Iopt,
+                                               uint8_t* __restrict__ bsplit)
+{
+    const int ld = L + 1;
 #pragma unroll
     for (int u = 0; u < X1_U; ++u) {
         const int l = lane + 64 * u;
@@ -106,6 +114,53 @@ __global__ __launch_bounds__(64 * X1_WAVES) void ext_iopt_kernel(
                 bsplit[inst + i4_index(ld, k, l, a, f)] = upper ? (uint8_t)arg[u][f] : (uint8_t)0;
             }
         }
+    }
+}
+
+template <int X1_U, int X1_AHEAD>
+__global__ __launch_bounds__(64 * X1_WAVES) void ext_iopt_kernel(
+    int L, const float* __restrict__ I4, float* __restrict__ Iopt, uint8_t* __restrict__ bsplit)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * X1_WAVES + (threadIdx.x >> 6);   // = 2k + a
+    const int k = w >> 1, a = w & 1;
+    const int b = blockIdx.y;
+    if (k > L) return;                      // whole wave leaves together
+    const int ld = L + 1;
+    const size_t inst = (size_t)b * ld * ld * 4;
+    float best[X1_U][2];
+    int arg[X1_U][2];
+    ext_iopt_row<X1_U, X1_AHEAD, false>(L, I4 + inst, nullptr, k, a, lane, best, arg);
+    ext_iopt_store<X1_U>(L, inst, k, a, lane, best, arg, Iopt, bsplit);
+}
+
+// Short chains in a batch: one workgroup per instance first copies the pairs
+// I[m][l][0][.] that every walk reads into LDS (each of the 2 (L + 1) walks of an
+// instance reads about half of them; from global memory that is the bandwidth
+// of the second-level cache), then its waves take the (k, a) in turn.
+constexpr int X1L_MAX_L = 63;
+
+__global__ __launch_bounds__(1024) void ext_iopt_lds_kernel(
+    int L, const float* __restrict__ I4, float* __restrict__ Iopt, uint8_t* __restrict__ bsplit)
+{
+    extern __shared__ float2 x1_pairs[];
+    const int ld = L + 1;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nw = blockDim.x >> 6;
+    const size_t inst = (size_t)blockIdx.x * ld * ld * 4;
+    const float* Ib = I4 + inst;
+    for (int x = threadIdx.x; x < ld * ld; x += blockDim.x) {
+        const int m = x / ld, l = x - m * ld;
+        x1_pairs[x] = *(const float2*)(Ib + i4_index(ld, m, l, 0, 0));
+    }
+    __syncthreads();
+    for (int w = wave; w < 2 * ld; w += nw) {
+        const int k = w >> 1, a = w & 1;
+        float best[1][2];
+        int arg[1][2];
+        ext_iopt_row<1, 8, true>(L, Ib, x1_pairs, k, a, lane, best, arg);
+        ext_iopt_store<1>(L, inst, k, a, lane, best, arg, Iopt, bsplit);
     }
 }
 
@@ -261,6 +316,12 @@ __global__ __launch_bounds__(64 * XB_WAVES) void ext_backtrack_kernel(
 
 hipError_t launch_ext_iopt(int B, int L, const float* I4, float* Iopt, uint8_t* bsplit, hipStream_t st)
 {
+    if (L <= X1L_MAX_L && B >= 128) {
+        const int nt = 64 * std::min(16, 2 * (L + 1));
+        const size_t lds = (size_t)(L + 1) * (L + 1) * sizeof(float2);
+        hipLaunchKernelGGL(ext_iopt_lds_kernel, dim3(B), dim3(nt), lds, st, L, I4, Iopt, bsplit);
+        return hipGetLastError();
+    }
     dim3 grid((2 * (L + 1) + X1_WAVES - 1) / X1_WAVES, B);
     if (L < 64)
         hipLaunchKernelGGL((ext_iopt_kernel<1, 8>), grid, dim3(64 * X1_WAVES), 0, st, L, I4, Iopt, bsplit);

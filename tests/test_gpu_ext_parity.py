@@ -94,6 +94,24 @@ def test_mobilenet_shaped_extended_batch():
     assert (g["status"] == 0).any()
 
 
+@pytest.mark.parametrize("L", [53, 63, 9])
+def test_extended_batch_of_short_chains(L):
+    """Batches of 128 instances and more with chains of at most 63 layers take the
+    kernels that stage an instance's tables in LDS (Algorithms 1 and 3)."""
+    rng = np.random.default_rng(7200 + L)
+    B, P = 160, 260
+    Ts, Is = [], []
+    for b in range(B):
+        T, _ = rand_tables(rng, L, tmax=7, inf_frac=0.25, ikind="int", span=8)
+        Ts.append(T)
+        Is.append(rand_i4(rng, L, "exact" if b % 3 == 0 else "float", paper_rules=b % 5 != 4))
+    T, I4 = np.stack(Ts), np.stack(Is)
+    qi = np.repeat(np.arange(B, dtype=np.int32), 3)
+    qt = np.tile(np.array([P // 3, P // 2, P - 1], np.int32), B)
+    g = run_ext_gpu(T, I4, P, qi, qt)
+    compare_ext(g, T, I4, P, qi, qt, f"ext batch of short chains L={L}", threads=16)
+
+
 def test_largest_supported_chain():
     rng = np.random.default_rng(7100)
     B, L, P = 2, api.DPC_EXT_MAX_L, 700
