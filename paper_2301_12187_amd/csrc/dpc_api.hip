@@ -62,6 +62,11 @@ bool ext_shape_ok(int B, int L, int P) { return L >= 1 && L <= DPC_EXT_MAX_L && 
 
 namespace dpc {
 
+bool stage2_runs_row_by_row(int P, int shape)
+{
+    return shape == DPC_SHAPE_ROWS || P < 16 || P >= (1 << 29);
+}
+
 int stage2_run(int B, int L, int P, ToptRef Topt, const float* I, float* M, uint8_t* K,
                void* workspace, int shape, hipStream_t stream)
 {
@@ -69,8 +74,7 @@ int stage2_run(int B, int L, int P, ToptRef Topt, const float* I, float* M, uint
     // The wave-window family copies whole 16-byte cells of a row and keeps byte
     // offsets inside a row in 32 bits: tables narrower than 16 budgets (and
     // absurdly wide ones) are solved row by row, one launch per row.
-    const bool rows = shape == DPC_SHAPE_ROWS || P < 16 || P >= (1 << 29);
-    if (rows) {
+    if (stage2_runs_row_by_row(P, shape)) {
         // this family uses no workspace; clear the header so that a later
         // dpc_stage2_check reads "no error"
         e = launch_clear_words(workspace, S2_HEADER_WORDS, stream);
@@ -228,6 +232,12 @@ int dpc_ext_knapsack(int32_t B, int32_t L, int32_t P, const int32_t* Topt, const
     char* base = (char*)workspace;
     int32_t* Tv = (int32_t*)(base + lay.tv_off);
     float* Iv = (float*)(base + lay.iv_off);
+    // The wave-window family computes the entries of the virtual tables where it
+    // reads them (its preparation kernel and the pair settlement); the
+    // row-by-row family reads expanded tables.
+    if (!dpc::stage2_runs_row_by_row(P, 0))
+        return dpc::stage2_run(B, 2 * L + 2, P, dpc::ToptRef{Topt, 1, L, Iopt}, nullptr, D, Kx,
+                               base + lay.s2_off, 0, (hipStream_t)stream);
     hipError_t e = dpc::launch_ext_expand(B, L, Topt, Iopt, Tv, Iv, (hipStream_t)stream);
     if (e != hipSuccess) return DPC_ERR_HIP;
     return dpc::stage2_run(B, 2 * L + 2, P, dpc::ToptRef{Tv, 1}, Iv, D, Kx, base + lay.s2_off, 0,

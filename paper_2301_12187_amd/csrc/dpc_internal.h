@@ -6,16 +6,61 @@
 
 namespace dpc {
 
+// Index of I4[k][l][a][b] / Iopt[k][l][a][b] of the extended solver inside an instance
+__host__ __device__ __forceinline__ size_t i4_index(int ld, int k, int l, int a, int b)
+{
+    return ((((size_t)k * ld + l) * 2 + a) * 2 + b);
+}
+
 // The latency tables of a batch as stage 2 reads them: instance b uses table
 // b / share.  share > 1: consecutive instances are copies of one network with
 // different importances (a sweep over the normalisation constant) and share
 // the one table stage 1 computed for it.
+// ext_L > 0: the chain stage 2 runs on is the extended solver's chain of
+// (layer, flag) states over ext_L real layers (Algorithm 4 as Algorithm 2 on the
+// virtual layers v = 2 l + a, plus a last one); `base` is then the real Topt
+// and ext_iopt the real I_opt, and the kernels that can (operands()) compute
+// the virtual entries from them instead of reading expanded tables.
 struct ToptRef {
     const int32_t* base;
     int share;
+    int ext_L = 0;
+    const float* ext_iopt = nullptr;
     __host__ __device__ const int32_t* of(int b, int ld) const
     {
         return base + (size_t)(share > 1 ? b / share : b) * ld * ld;
+    }
+    // latency and importance of the block (i, j) of instance b of a chain whose
+    // tables have ld = (layers + 1) rows; I: the importances of a plain chain
+    __device__ __forceinline__ void operands(const float* __restrict__ I, int b, int ld, int i, int j,
+                                              int32_t& t, float& imp) const
+    {
+        if (ext_L == 0) {
+            t = of(b, ld)[(size_t)i * ld + j];
+            imp = I[((size_t)b * ld + i) * ld + j];
+            return;
+        }
+        // An entry (u, v) = (i, j), u < v, of the virtual chain, V = 2 L + 3 layers:
+        //   u = 0, v = 1      latency 0, importance +0  (D[0][t][1] = D[0][t][0] = +0)
+        //   v <= 2L+1         from (k', alpha') = (u / 2, u % 2) to (l, a) = (v / 2, v % 2), k' < l:
+        //                     latency Topt[k'][l], importance I_opt[k'][l][alpha'][a]
+        //   v = 2L+2          from (L, 0) and (L, 1): latency 0, importance +0
+        // everything else: none (latency DPC_INF, importance -inf).
+        const int L = ext_L, rl = L + 1, V = 2 * L + 3;
+        t = DPC_INF;
+        imp = -INFINITY;
+        if (i < j) {
+            const int kp = i >> 1, al = i & 1, l = j >> 1, a = j & 1;
+            if (j == V - 1) {
+                if (kp == L) { t = 0; imp = 0.0f; }
+            } else if (kp < l) {
+                t = base[(size_t)b * rl * rl + (size_t)kp * rl + l];
+                imp = ext_iopt[(size_t)b * rl * rl * 4 + i4_index(rl, kp, l, al, a)];
+            } else if (i == 0 && j == 1) {
+                t = 0;
+                imp = 0.0f;
+            }
+        }
     }
 };
 
@@ -39,6 +84,8 @@ bool stage2_wave_shape_known(int shape);
 // dpc_hooks.h; 0 = the default choice).  Returns a DPC_* code.
 int stage2_run(int B, int L, int P, ToptRef Topt, const float* I, float* M, uint8_t* K,
                void* workspace, int shape, hipStream_t st);
+// whether stage2_run takes the one-launch-per-row family for this width and shape
+bool stage2_runs_row_by_row(int P, int shape);
 hipError_t launch_backtrack(int B, int L, int P, const int32_t* Topt, const uint8_t* split,
                             const float* I, const float* M, const uint8_t* K, int Q,
                             const int32_t* q_inst, const int32_t* q_T0, int32_t* A,

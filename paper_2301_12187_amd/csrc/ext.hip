@@ -22,11 +22,6 @@ namespace dpc {
 
 constexpr int X1_WAVES = 4;       // waves per workgroup
 
-__device__ __forceinline__ size_t i4_index(int ld, int k, int l, int a, int b)
-{
-    return ((((size_t)k * ld + l) * 2 + a) * 2 + b);
-}
-
 // One wave per (instance, k, a).  Lanes own the targets l = lane + 64u, both
 // end flags b.  The running maximum starts from the single block (k, l) with
 // flags (a, b); the wave then walks the split points m = k+1, k+2, ... in
@@ -175,25 +170,14 @@ __global__ __launch_bounds__(256) void ext_expand_kernel(
     int L, const int32_t* __restrict__ Topt, const float* __restrict__ Iopt,
     int32_t* __restrict__ Tv, float* __restrict__ Iv)
 {
-    const int V = 2 * L + 3, ld = L + 1;
+    const int V = 2 * L + 3;
     const int b = blockIdx.y;
     const int x = blockIdx.x * 256 + threadIdx.x;
     if (x >= V * V) return;
     const int u = x / V, v = x - u * V;
-    int32_t t = DPC_INF;
-    float imp = -INFINITY;
-    if (u < v) {
-        const int kp = u >> 1, al = u & 1, l = v >> 1, a = v & 1;
-        if (v == V - 1) {
-            if (kp == L) { t = 0; imp = 0.0f; }
-        } else if (kp < l) {
-            t = Topt[(size_t)b * ld * ld + (size_t)kp * ld + l];
-            imp = Iopt[(size_t)b * ld * ld * 4 + i4_index(ld, kp, l, al, a)];
-        } else if (u == 0 && v == 1) {
-            t = 0;
-            imp = 0.0f;
-        }
-    }
+    int32_t t;
+    float imp;
+    ToptRef{Topt, 1, L, Iopt}.operands(nullptr, b, V, u, v, t, imp);
     Tv[(size_t)b * V * V + x] = t;
     Iv[(size_t)b * V * V + x] = imp;
 }

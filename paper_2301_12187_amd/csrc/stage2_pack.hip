@@ -95,8 +95,6 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
     const int b = blockIdx.y;
     const int j0 = s2_group_first_row(L, R, q);
     const int hq = s2_group_rows(L, R, q);
-    const int32_t* To = Topt.of(b, ld);
-    const float* Ib = I + (size_t)b * ld * ld;
     if (i == 0) spread = 0;
     __syncthreads();
     if (q == 0) {
@@ -119,8 +117,9 @@ __global__ __launch_bounds__(256) void stage2_pack_kernel(
         const int x = i + k * nt;
         const int row = x / R, rr = x - row * R;
         const bool ok = row < ld && rr < hq;
-        tv[k] = ok ? To[row * ld + j0 + rr] : 0;
-        iv[k] = ok ? Ib[row * ld + j0 + rr] : 0.0f;
+        tv[k] = 0;
+        iv[k] = 0.0f;
+        if (ok) Topt.operands(I, b, ld, row, j0 + rr, tv[k], iv[k]);
     }
 #pragma unroll
     for (int k = 0; k < R; ++k) {

@@ -966,15 +966,12 @@ __global__ __launch_bounds__(NW * 64, WPE) void stage2_wave_kernel(
             constexpr int EARLY = TRIPS < 2 ? TRIPS : 2;
             const int nent = ((j0 + 1) >> 1) * R;              // pairs (2c, 2c + 1) with 2c < j0
             auto pair_operands = [&](int k) __attribute__((always_inline)) {
-                const int32_t* To = Topt.of(b, ld);
-                const float* Ib = I + (size_t)b * ld * ld;
                 const int en = min(tid + k * NT, nent - 1);
                 const int c = en / R, rr = en - c * R;
-                const int x = 2 * c * ld + min(j0 + rr, L);
-                const int w = To[x];
+                int32_t w;
                 PairOp o;
+                Topt.operands(I, b, ld, 2 * c, min(j0 + rr, L), w, o.imp);
                 o.w4 = w >= 0 && w < P ? 4 * w : 0x7FFFFFFF;       // (the pack kernel's rule)
-                o.imp = Ib[x];
                 return o;
             };
             PairOp early[EARLY];

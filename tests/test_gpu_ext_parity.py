@@ -81,6 +81,22 @@ def test_tiny_tie_rich_extended_instances(seed):
     compare_ext(g, T, I4, P, qi, qt, f"tiny ext seed {seed} L={L} P={P}")
 
 
+def test_extended_tables_narrower_than_the_window_kernels_take():
+    """Fewer than 16 budgets: stage 2 runs row by row on the expanded virtual tables."""
+    rng = np.random.default_rng(7300)
+    B, L, P = 4, 9, 13
+    Ts, Is = [], []
+    for b in range(B):
+        T, _ = rand_tables(rng, L, tmax=3, inf_frac=0.2, ikind="int")
+        Ts.append(T)
+        Is.append(rand_i4(rng, L, "exact" if b % 2 else "float"))
+    T, I4 = np.stack(Ts), np.stack(Is)
+    qi = np.repeat(np.arange(B, dtype=np.int32), P)
+    qt = np.tile(np.arange(P, dtype=np.int32), B)
+    g = run_ext_gpu(T, I4, P, qi, qt)
+    compare_ext(g, T, I4, P, qi, qt, "narrow ext table")
+
+
 def test_mobilenet_shaped_extended_batch():
     """L = 53 (the paper's MobileNetV2 chain), P = 1000, a batch of instances
     with the identity pattern and exclusions of Appendix B.2."""
