@@ -18,7 +18,9 @@ target is quoted on.  Prints ONE JSON line.
                peak = 256 CU x 64 lanes/clk x 2.4 GHz = 39.3 T lane-ops/s
                (the 157.3 TFLOP/s fp32 vector figure without the FMA and
                packed factors of 2).  Duration from HIP events on the launch
-               stream around dpc_stage2_knapsack in every timed step.
+               stream around dpc_stage2_knapsack in every timed step (the only
+               events in the timed region; stage 1 and set recovery are timed
+               in further steps after it).
                `frac` counts 4 lane-ops per candidate (the update taken
                one candidate at a time) whatever the kernel issues, so it
                can pass 1; `variant_floor_ops` / `frac_of_variant_floor`
@@ -28,9 +30,9 @@ target is quoted on.  Prints ONE JSON line.
   cpu_baseline the CPU oracle, as it stands, on every instance and query of the
                same workload, one instance per host thread (`cores` threads
                of `host_cores`).
-  parity       the GPU buffers of the last timed step against that oracle
-               run, element by element, tolerance 0; a mismatch makes the
-               exit status 1.
+  parity       the GPU buffers as the last step left them (every step solves the
+               same inputs) against that oracle run, element by element,
+               tolerance 0; a mismatch makes the exit status 1.
   per_config   (default run only) workloads 1-4 timed and checked the same way.
 """
 import argparse
@@ -87,46 +89,46 @@ class Workload:
 
 def time_workload(w, args, torch, api, np, steps, warmup, fused=False, graph=False):
     """W untimed and K timed steps of the whole path; -> (ms per step by the host
-    clock around the K steps, per-stage ms from events on the launch stream)."""
+    clock around the K steps, per-stage ms from events on the launch stream).
+    The timed steps carry one event pair each, around stage 2 (the roofline's
+    duration); the durations of stage 1 and of the set recovery come from K more
+    steps after the timed region, which carry an event at every stage boundary."""
     buf, stream = w.buf, torch.cuda.current_stream()
     one_launch = fused and 0 < len(w.qi) <= api.ONE_LAUNCH_QUERIES_PER_INSTANCE * w.cfg.B
 
-    def step(ev=None):
-        if ev:
-            ev[0].record(stream)
+    def step(ev=None, which=()):
+        def mark(x):
+            if ev is not None and x in which:
+                ev[x].record(stream)
+        mark(0)
         if fused and one_launch:
             # the whole path in one kernel: its time is reported as stage 2
-            if ev:
-                ev[1].record(stream)
+            mark(1)
             api.dpc_solve_fused(w.Td, w.Id, buf.Topt, buf.split, buf.M, buf.K, w.qid, w.qtd, buf.A,
                                 buf.A_len, buf.S, buf.S_len, buf.obj, buf.lat, buf.status)
-            if ev:
-                ev[2].record(stream)
-                ev[3].record(stream)
+            mark(2)
+            mark(3)
             return
         if fused:
-            if ev:
-                ev[1].record(stream)         # (stage 1 runs inside the one kernel)
+            mark(1)                          # (stage 1 runs inside the one kernel)
             api.dpc_stage12_fused(w.Td, w.Id, buf.Topt, buf.split, buf.M, buf.K)
         else:
             api.dpc_stage1_minplus(w.Td, buf.Topt, buf.split)
-            if ev:
-                ev[1].record(stream)
+            mark(1)
             api.dpc_stage2_knapsack(buf.Topt, w.Id, buf.M, buf.K, buf.workspace, shape=args.shape)
-        if ev:
-            ev[2].record(stream)
+        mark(2)
         api.dpc_backtrack(buf.Topt, buf.split, w.Id, buf.M, buf.K, w.qid, w.qtd, buf.A, buf.A_len,
                           buf.S, buf.S_len, buf.obj, buf.lat, buf.status)
-        if ev:
-            ev[3].record(stream)
+        mark(3)
 
+    S2_ONLY, ALL = (1, 2), (0, 1, 2, 3)
     for _ in range(warmup):
         step()
     api.dpc_stage2_check(buf.workspace)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
     torch.cuda.synchronize()
     if graph:
-        # (per-stage events are recorded inside the graph once; the replays are timed as a whole)
+        # (the stage-2 events are recorded inside the graph once; the replays are timed as a whole)
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             step()
@@ -141,26 +143,35 @@ def time_workload(w, args, torch, api, np, steps, warmup, fused=False, graph=Fal
                 evs[k][x].record(stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-    else:
-        t0 = time.perf_counter()
-        for k in range(steps):
-            step(evs[k])
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
+        api.dpc_stage2_check(buf.workspace)
+        seg = [[e[x].elapsed_time(e[x + 1]) for e in evs] for x in range(3)]
+        return (t1 - t0) * 1e3 / steps, {
+            "stage1": float(np.mean(seg[0])), "stage2": float(np.mean(seg[1])),
+            "stage2_min": float(np.min(seg[1])), "backtrack": float(np.mean(seg[2]))}
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(evs[k], S2_ONLY)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
     api.dpc_stage2_check(buf.workspace)
     ms_step = (t1 - t0) * 1e3 / steps
-    seg = [[e[x].elapsed_time(e[x + 1]) for e in evs] for x in range(3)]
-    stage_ms = {"stage1": float(np.mean(seg[0])), "stage2": float(np.mean(seg[1])),
-                "stage2_min": float(np.min(seg[1])), "backtrack": float(np.mean(seg[2]))}
-    # The same K steps once more without the per-stage events in the stream: on
-    # the small workloads the four event records of a step take as long as a kernel.
-    if not graph:
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(steps):
-            step()
-        torch.cuda.synchronize()
-        stage_ms["step_without_events"] = (time.perf_counter() - t0) * 1e3 / steps
+    s2 = [e[1].elapsed_time(e[2]) for e in evs]
+    stage_ms = {"stage2": float(np.mean(s2)), "stage2_min": float(np.min(s2))}
+    # the other stages: the same K steps again, after the timed region, with an
+    # event at every stage boundary
+    evs2 = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    for k in range(steps):
+        step(evs2[k], ALL)
+    torch.cuda.synchronize()
+    stage_ms["stage1"] = float(np.mean([e[0].elapsed_time(e[1]) for e in evs2]))
+    stage_ms["backtrack"] = float(np.mean([e[2].elapsed_time(e[3]) for e in evs2]))
+    # and once more with no events in the stream at all: on the small workloads
+    # an event record takes as long as a kernel
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step()
+    torch.cuda.synchronize()
+    stage_ms["step_without_events"] = (time.perf_counter() - t0) * 1e3 / steps
     return ms_step, stage_ms
 
 
